@@ -1,0 +1,148 @@
+"""Pins of the dequantisation and FFN oracle: exact round trips, a group worked
+by hand, error bounds, and the one-expert case against a dense SwiGLU MLP
+computed with torch's own fp64 silu and matmul."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import moe as O
+from workloads import SHAPES, gen_hidden, gen_gate, gen_expert, gen_shared_gate, quantize_sym
+
+
+def _f(t):
+    return t.to(torch.float32).numpy()
+
+
+def test_dequant_hand_worked_group():
+    # one row, two groups of 4, int4.  Group 0: max|w| = 0.7 -> s = fp16(0.1);
+    # group 1 all zero -> s = 1, q = 0.
+    w = np.array([[0.7, -0.35, 0.04, -0.7, 0.0, 0.0, 0.0, 0.0]])
+    q, s = O.quantize_sym(w, 4, 4)
+    s0 = np.float16(0.7 / 7)
+    assert s.dtype == np.float16 and s[0, 0] == s0 and s[0, 1] == np.float16(1.0)
+    # -0.35 / fp16(0.1): fp16(0.1) = 0.0999755859375 -> -3.5009 -> -4 ; 0.04/s = 0.4001 -> 0
+    assert q.tolist() == [[7, -4, 0, -7, 0, 0, 0, 0]]
+    packed = O.pack_codes(q, 4)
+    # nibble u = q + 8, low nibble is the even column: (15 | 4<<4), (8 | 1<<4), 0x88, 0x88
+    assert packed.tolist() == [[0x4F, 0x18, 0x88, 0x88]]
+    assert np.array_equal(O.unpack_codes(packed, 4), q)
+    d = O.dequant(packed, s, 4, 4)
+    assert d[0, 0] == 7 * float(s0) and d[0, 1] == -4 * float(s0) and d[0, 4] == 0.0
+    # int8 two's complement storage
+    q8 = np.array([[-127, -1, 0, 127]])
+    p8 = O.pack_codes(q8, 8)
+    assert p8.tolist() == [[0x81, 0xFF, 0x00, 0x7F]]
+    assert np.array_equal(O.unpack_codes(p8, 8), q8)
+
+
+@pytest.mark.parametrize("bits,group", [(8, 64), (4, 128)])
+def test_quant_round_trip_and_error_bound(bits, group):
+    rng = np.random.default_rng(bits)
+    w = rng.normal(size=(48, 4 * group)) * 0.02
+    w[3, :group] = 0.0                                  # an all-zero group
+    q, s = O.quantize_sym(w, bits, group)
+    qmax = 127 if bits == 8 else 7
+    assert np.abs(q).max() <= qmax
+    d = O.dequant(O.pack_codes(q, bits), s, bits, group)
+    sfull = np.repeat(s.astype(np.float64), group, axis=1)
+    assert (np.abs(w - d) <= sfull / 2 + 1e-18).all()
+    # q*s is exact in fp32 as well as in fp64
+    d32 = (q.astype(np.float32) * np.repeat(s.astype(np.float32), group, axis=1)).astype(np.float64)
+    assert np.array_equal(d, d32)
+    # re-quantising the dequantised weights with the same scales gives the same codes
+    q2 = np.clip(np.rint(d / sfull), -qmax, qmax).astype(np.int32)
+    assert np.array_equal(q2, q)
+    # every non-zero group uses its full range
+    gmax = np.abs(q).reshape(48, 4, group).max(axis=-1)
+    assert (gmax[np.abs(w).reshape(48, 4, group).max(-1) > 0] == qmax).all()
+    assert s[3, 0] == np.float16(1.0) and (q[3, :group] == 0).all()
+
+
+@pytest.mark.parametrize("bits,group", [(8, 64), (4, 128)])
+def test_workload_quantizer_agrees_with_oracle_reading(bits, group):
+    """The generator's stored weights obey the oracle's format: same scales,
+    and codes that differ at most where w/s sits on a rounding boundary."""
+    g = torch.Generator().manual_seed(5)
+    w = torch.randn(32, 2 * group, generator=g) * 0.02
+    codes, s = quantize_sym(w, bits, group)
+    q_ref, s_ref = O.quantize_sym(w.numpy().astype(np.float64), bits, group)
+    assert np.array_equal(s.numpy(), s_ref)
+    q = O.unpack_codes(codes.numpy(), bits)
+    assert np.abs(q - q_ref).max() <= 1 and (q != q_ref).mean() < 1e-3
+
+
+def _dense_swiglu_torch(x, W1, W3, W2):
+    x, W1, W3, W2 = (torch.from_numpy(np.ascontiguousarray(a)).double() for a in (x, W1, W3, W2))
+    return ((F.silu(x @ W1.T) * (x @ W3.T)) @ W2.T).numpy()
+
+
+def _oracle_expert(ex):
+    ex = ex.cpu()
+    return O.OracleExpert(ex.w1.numpy(), ex.s1.numpy(), ex.w3.numpy(), ex.s3.numpy(),
+                          ex.w2.numpy(), ex.s2.numpy(), ex.bits, ex.group)
+
+
+def test_silu_matches_torch():
+    a = np.linspace(-30, 30, 1001)
+    assert np.allclose(O.silu(a), F.silu(torch.from_numpy(a)).numpy(), rtol=1e-14, atol=1e-300)
+
+
+def test_ffn_one_expert_is_a_dense_swiglu_mlp():
+    cfg = SHAPES["tiny"]
+    x = _f(gen_hidden(cfg, 5))
+    ex = _oracle_expert(gen_expert(cfg, 0, 3))
+    assert ex.W1.shape == (cfg.I, cfg.H) and ex.W2.shape == (cfg.H, cfg.I)
+    ids = np.full((5, 1), 3, dtype=np.int32)
+    w = np.ones((5, 1))
+    y = O.moe_ffn(x, ids, w, {3: ex})
+    ref = _dense_swiglu_torch(x.astype(np.float64), ex.W1, ex.W3, ex.W2)
+    assert np.allclose(y, ref, rtol=1e-12, atol=1e-15)
+    # swapping gate and up projections, or dropping silu, must not pass
+    wrong = _dense_swiglu_torch(x.astype(np.float64), ex.W3, ex.W1, ex.W2)
+    assert not np.allclose(y, wrong, rtol=1e-3)
+
+
+def test_ffn_combination_linearity_and_shared_term():
+    cfg = SHAPES["tiny"]
+    N = 6
+    x = _f(gen_hidden(cfg, N))
+    Wg, _ = gen_gate(cfg, 0)
+    ids, w, _, _ = O.gate_route(x, _f(Wg), None, cfg.k, True)
+    experts = {e: _oracle_expert(gen_expert(cfg, 0, e)) for e in range(cfg.E)}
+    y = O.moe_ffn(x, ids, w, experts)
+    # definition by pairs with torch's dense MLP per expert
+    ref = np.zeros_like(y)
+    for t in range(N):
+        for j in range(cfg.k):
+            ex = experts[int(ids[t, j])]
+            ref[t] += w[t, j] * _dense_swiglu_torch(x[t:t + 1].astype(np.float64), ex.W1, ex.W3, ex.W2)[0]
+    assert np.allclose(y, ref, rtol=1e-12, atol=1e-15)
+    # linear in the routing weights
+    y2 = O.moe_ffn(x, ids, 2.5 * w, experts)
+    assert np.allclose(y2, 2.5 * y, rtol=1e-12)
+    wa = w.copy(); wa[:, 1] = 0
+    wb = w.copy(); wb[:, 0] = 0
+    assert np.allclose(O.moe_ffn(x, ids, wa, experts) + O.moe_ffn(x, ids, wb, experts), y, rtol=1e-12, atol=1e-15)
+    # shared experts: ungated term alone, then the sigmoid gate
+    sh = [_oracle_expert(gen_expert(cfg, 0, 0, shared=False)), _oracle_expert(gen_expert(cfg, 0, 1))]
+    y_sh = O.moe_ffn(x, ids, np.zeros_like(w), experts, shared=sh)
+    ref_sh = sum(_dense_swiglu_torch(x.astype(np.float64), s.W1, s.W3, s.W2) for s in sh)
+    assert np.allclose(y_sh, ref_sh, rtol=1e-12, atol=1e-15)
+    sg = np.random.default_rng(0).normal(size=cfg.H) / 16
+    y_g = O.moe_ffn(x, ids, np.zeros_like(w), experts, shared=sh, shared_gate=sg)
+    gate = torch.sigmoid(torch.from_numpy(x.astype(np.float64) @ sg)).numpy()
+    assert np.allclose(y_g, gate[:, None] * ref_sh, rtol=1e-12, atol=1e-15)
+    # routed + shared add
+    y_all = O.moe_ffn(x, ids, w, experts, shared=sh, shared_gate=sg)
+    assert np.allclose(y_all, y + y_g, rtol=1e-12, atol=1e-15)
+
+
+def test_ffn_rows_subset():
+    cfg = SHAPES["tiny"]
+    x = _f(gen_hidden(cfg, 8))
+    Wg, _ = gen_gate(cfg, 0)
+    ids, w, _, _ = O.gate_route(x, _f(Wg), None, cfg.k, True)
+    experts = {e: _oracle_expert(gen_expert(cfg, 0, e)) for e in range(cfg.E)}
+    y = O.moe_ffn(x, ids, w, experts)
+    assert np.array_equal(O.moe_ffn_rows(x, ids, w, experts, rows=[5, 2]), y[[5, 2]])
