@@ -1,0 +1,98 @@
+// fate_moe_ffn_q: argument checks, workspace carving, dispatch.
+#include "common.h"
+#include "ffn_internal.h"
+
+namespace fate {
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static fate_status check_desc(const fate_ffn_desc* d) {
+    if (d == nullptr) FATE_FAIL(FATE_EINVAL, "descriptor is NULL");
+    if (d->N < 0) FATE_FAIL(FATE_EINVAL, "N = %d < 0", d->N);
+    if (d->E < 1 || d->E > kMaxE) FATE_FAIL(FATE_ESHAPE, "E = %d outside [1, %d]", d->E, kMaxE);
+    if (d->k < 1 || d->k > d->E) FATE_FAIL(FATE_EINVAL, "k = %d outside [1, E]", d->k);
+    if (d->H < 64 || d->H % 64) FATE_FAIL(FATE_ESHAPE, "H = %d must be a positive multiple of 64", d->H);
+    if (d->bits != 4 && d->bits != 8) FATE_FAIL(FATE_EINVAL, "bits = %d (4 or 8)", d->bits);
+    if (d->group < 64 || d->group % 64) FATE_FAIL(FATE_ESHAPE, "group = %d must be a multiple of 64", d->group);
+    if (d->I_max < 64 || d->I_max % 64) FATE_FAIL(FATE_ESHAPE, "I_max = %d must be a multiple of 64", d->I_max);
+    if (d->H % d->group || d->I_max % d->group)
+        FATE_FAIL(FATE_ESHAPE, "H and I_max must be multiples of the group (%d)", d->group);
+    if (d->n_shared < 0 || d->n_shared > 16) FATE_FAIL(FATE_EINVAL, "n_shared = %d outside [0, 16]", d->n_shared);
+    if (d->n_shared) {
+        if (d->shared_bits != 4 && d->shared_bits != 8) FATE_FAIL(FATE_EINVAL, "shared_bits = %d", d->shared_bits);
+        if (d->shared_group < 64 || d->shared_group % 64) FATE_FAIL(FATE_ESHAPE, "shared_group = %d", d->shared_group);
+        if (d->I_shared_max < 64 || d->I_shared_max % 64 || d->I_shared_max % d->shared_group || d->H % d->shared_group)
+            FATE_FAIL(FATE_ESHAPE, "I_shared_max = %d / H must be multiples of 64 and of the shared group", d->I_shared_max);
+    }
+    if (d->mode < 0 || d->mode > 2) FATE_FAIL(FATE_EINVAL, "mode = %d", d->mode);
+    if ((long long)d->N * d->k > 0x3fffffffLL) FATE_FAIL(FATE_ESHAPE, "N*k too large");
+    return FATE_OK;
+}
+
+static void carve(const fate_ffn_desc& d, void* base, FfnWorkspace* w) {
+    char* p = static_cast<char*>(base);
+    size_t off = 0;
+    w->status = reinterpret_cast<int32_t*>(p + off); off += 256;
+    w->h_r = reinterpret_cast<__half*>(p + off);
+    off += align_up((size_t)d.N * d.k * d.I_max * 2, 256);
+    w->h_s = reinterpret_cast<__half*>(p + off);
+    off += align_up((size_t)d.n_shared * d.N * (d.n_shared ? d.I_shared_max : 0) * 2, 256);
+    w->ybuf = reinterpret_cast<float*>(p + off);
+    if (!d.y_is_fp32) off += align_up((size_t)d.N * d.H * 4, 256);
+    w->sgate = reinterpret_cast<float*>(p + off);
+    off += align_up((size_t)d.N * 4, 256);
+    w->bytes = off + 256;
+}
+
+}  // namespace fate
+
+using namespace fate;
+
+extern "C" fate_status fate_moe_ffn_q_workspace(const fate_ffn_desc* d, size_t* bytes) {
+    fate_status s = check_desc(d);
+    if (s != FATE_OK) return s;
+    if (bytes == nullptr) FATE_FAIL(FATE_EINVAL, "bytes is NULL");
+    FfnWorkspace w;
+    carve(*d, nullptr, &w);
+    *bytes = w.bytes;
+    return FATE_OK;
+}
+
+extern "C" fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, const void* x_bf16,
+                                      const fate_qexpert* experts_dev, const int32_t* counts,
+                                      const int32_t* offsets, const int32_t* perm, const int32_t* expert_order,
+                                      const float* topk_w, const fate_qexpert* shared_dev,
+                                      const void* shared_gate_bf16, void* y, void* workspace,
+                                      size_t workspace_bytes) {
+    fate_status s = check_desc(d);
+    if (s != FATE_OK) return s;
+    if (d->N == 0) return FATE_OK;
+    FATE_CHECK_PTR(x_bf16);
+    FATE_CHECK_PTR(y);
+    FATE_CHECK_PTR_OPT(shared_gate_bf16);
+    if (!experts_dev || !counts || !offsets || !perm || !expert_order || !topk_w)
+        FATE_FAIL(FATE_EINVAL, "experts, counts, offsets, perm, expert_order and topk_w must not be NULL");
+    if (d->n_shared && !shared_dev) FATE_FAIL(FATE_EINVAL, "shared_dev is NULL with n_shared = %d", d->n_shared);
+    FfnWorkspace w;
+    carve(*d, workspace, &w);
+    if (workspace == nullptr || workspace_bytes < w.bytes)
+        FATE_FAIL(FATE_EWORKSPACE, "workspace of %zu bytes needed, %zu given", w.bytes, workspace_bytes);
+    FATE_CHECK_PTR(workspace);
+
+    DecodeArgs a{};
+    a.x = static_cast<const uint16_t*>(x_bf16);
+    a.N = d->N; a.H = d->H; a.E = d->E; a.k = d->k;
+    a.experts = experts_dev; a.shared = shared_dev; a.n_shared = d->n_shared;
+    a.counts = counts; a.offsets = offsets; a.perm = perm; a.order = expert_order; a.topk_w = topk_w;
+    a.shared_gate = static_cast<const uint16_t*>(shared_gate_bf16);
+    a.bits_r = d->bits; a.group_r = d->group;
+    a.bits_s = d->n_shared ? d->shared_bits : d->bits; a.group_s = d->n_shared ? d->shared_group : d->group;
+    a.h_r = w.h_r; a.ldh_r = d->I_max;
+    a.h_s = w.h_s; a.ldh_s = d->n_shared ? d->I_shared_max : 0;
+    a.y = d->y_is_fp32 ? static_cast<float*>(y) : w.ybuf;
+    a.status = w.status;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int mode = d->mode ? d->mode : (d->N <= 16 ? 1 : 2);
+    if (mode == 1) return launch_ffn_decode(st, *d, a, y);
+    return launch_ffn_mfma(st, *d, a, w.sgate, y);
+}

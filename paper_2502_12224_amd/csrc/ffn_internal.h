@@ -1,0 +1,42 @@
+// Shared between the FFN translation units.
+#pragma once
+#include <hip/hip_fp16.h>
+#include "common.h"
+
+namespace fate {
+
+struct DecodeArgs {
+    const uint16_t* x;
+    int N, H, E, k;
+    const fate_qexpert* experts;
+    const fate_qexpert* shared;
+    int n_shared;
+    const int32_t* counts;
+    const int32_t* offsets;
+    const int32_t* perm;
+    const int32_t* order;
+    const float* topk_w;
+    const uint16_t* shared_gate;
+    int nact;            // routed expert slots in the grid: min(E, N*k)
+    int rb_r, rb_s;      // 32-row blocks per routed / shared expert (up kernel)
+    int bits_r, group_r, bits_s, group_s;
+    __half* h_r; int ldh_r;   // [P][I_max] fp16, rows in sorted pair order
+    __half* h_s; int ldh_s;   // [n_shared*N][I_shared_max] fp16
+    float* y;                 // [N,H] fp32 accumulator
+    int32_t* status;
+    int nchunk_r, nchunk_s, cg_r, cg_s;   // reduction chunks of the down kernel
+};
+
+struct FfnWorkspace {
+    int32_t* status;
+    __half* h_r;
+    __half* h_s;
+    float* ybuf;     // only when the output is bf16
+    float* sgate;    // [N] shared gate values (MFMA path)
+    size_t bytes;
+};
+
+fate_status launch_ffn_decode(hipStream_t st, const fate_ffn_desc& d, DecodeArgs a, void* y_out);
+fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs a, float* sgate, void* y_out);
+
+}  // namespace fate

@@ -1,0 +1,289 @@
+// Gate routing, cross-layer prediction, permutation: kernels and C entry points.
+//
+// fate_gate_route / fate_cross_layer_predict: one wavefront per token row.
+// The wave keeps its token rows in LDS, streams the gate matrix (L2
+// resident) row by row, reduces each logit with wavefront shuffles, then
+// does the softmax and the top-m selection in registers.
+//
+// fate_route_fused: decode-side variant.  With a handful of tokens the gate
+// matrices (2 x E rows) are the only sizeable data, so one wave takes one gate
+// row for all tokens and the rows are spread over the chip; the workgroup
+// that finishes last (ticket counter) does softmax, selection, popularity
+// and the permutation for all tokens.
+#include "common.h"
+#include "route_device.h"
+
+namespace fate {
+
+__global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+__device__ __forceinline__ float dot8_bf16(const uint4& a, const uint4& b, float acc) {
+    acc = fmaf(bf16_lo(a.x), bf16_lo(b.x), acc);
+    acc = fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
+    acc = fmaf(bf16_lo(a.y), bf16_lo(b.y), acc);
+    acc = fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
+    acc = fmaf(bf16_lo(a.z), bf16_lo(b.z), acc);
+    acc = fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
+    acc = fmaf(bf16_lo(a.w), bf16_lo(b.w), acc);
+    acc = fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
+    return acc;
+}
+
+// 4 waves per block, TPW token rows per wave.
+template <int TPW>
+__global__ __launch_bounds__(256) void route_rows_kernel(const uint16_t* __restrict__ x,
+                                                         const uint16_t* __restrict__ Wg,
+                                                         const float* __restrict__ bias, int N, int H, int E,
+                                                         int m, int renorm, int32_t* __restrict__ ids,
+                                                         float* __restrict__ w, float* __restrict__ probs,
+                                                         int32_t* __restrict__ pop) {
+    extern __shared__ uint4 smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nvec = H >> 3;
+    const int tok0 = (blockIdx.x * 4 + wave) * TPW;
+    uint4* xw = smem + (size_t)wave * TPW * nvec;
+    float* zw = reinterpret_cast<float*>(smem + (size_t)4 * TPW * nvec) + (size_t)wave * TPW * E;
+
+    for (int t = 0; t < TPW; ++t) {
+        int tok = tok0 + t;
+        const uint4* xr = reinterpret_cast<const uint4*>(x) + (size_t)tok * nvec;
+        for (int c = lane; c < nvec; c += 64) xw[t * nvec + c] = (tok < N) ? xr[c] : make_uint4(0, 0, 0, 0);
+    }
+    __syncthreads();
+    for (int e = 0; e < E; ++e) {
+        float acc[TPW];
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) acc[t] = 0.f;
+        const uint4* wr = reinterpret_cast<const uint4*>(Wg) + (size_t)e * nvec;
+        for (int c = lane; c < nvec; c += 64) {
+            uint4 wv = wr[c];
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) acc[t] = dot8_bf16(xw[t * nvec + c], wv, acc[t]);
+        }
+        float b = bias ? bias[e] : 0.f;
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+            float s = wave_sum(acc[t]);
+            if (lane == 0) zw[t * E + e] = s + b;
+        }
+    }
+    __syncthreads();
+    for (int t = 0; t < TPW; ++t) {
+        int tok = tok0 + t;
+        if (tok < N)
+            wave_softmax_topm(zw + t * E, E, m, renorm, ids + (size_t)tok * m, w + (size_t)tok * m,
+                              probs ? probs + (size_t)tok * E : nullptr, pop);
+    }
+}
+
+__global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict__ ids, int P, int E,
+                                                       int32_t* counts, int32_t* offsets, int32_t* perm,
+                                                       int32_t* inv_perm, int32_t* order) {
+    __shared__ int32_t sm[kPermSmemInts];
+    block_permute(ids, P, E, counts, offsets, perm, inv_perm, order, sm);
+}
+
+// ---- fused decode-side routing --------------------------------------------
+// workspace: [0] ticket counter (int32, zero between calls), then at byte 256
+// the logits zbuf[2][N][E] fp32.
+constexpr int kFusedMaxN = 16;
+
+__global__ __launch_bounds__(256) void route_fused_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg, const float* __restrict__ bias,
+    const uint16_t* __restrict__ Wg2, const float* __restrict__ bias2, int N, int H, int E, int k, int m,
+    int renorm, int32_t* ids, float* w, int32_t* pids, float* pw, int32_t* pop, int32_t* counts,
+    int32_t* offsets, int32_t* perm, int32_t* inv_perm, int32_t* order, int32_t* ticket, float* zbuf) {
+    extern __shared__ uint4 smem[];   // x rows: N*H bf16
+    __shared__ int32_t sm_perm[kPermSmemInts];
+    __shared__ float sm_z[4][kMaxE];
+    __shared__ int32_t sm_ids[kFusedMaxN * kMaxM];
+    __shared__ int32_t sm_pop[kMaxE];
+    __shared__ int sm_last;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nvec = H >> 3;
+    const int nrows = Wg2 ? 2 * E : E;
+    const uint4* xg = reinterpret_cast<const uint4*>(x);
+    for (int i = threadIdx.x; i < N * nvec; i += 256) smem[i] = xg[i];
+    __syncthreads();
+    const int r = blockIdx.x * 4 + wave;
+    if (r < nrows) {
+        const int g = r >= E, e = g ? r - E : r;
+        const uint4* wr = reinterpret_cast<const uint4*>(g ? Wg2 : Wg) + (size_t)e * nvec;
+        const float* bb = g ? bias2 : bias;
+        const float b = bb ? bb[e] : 0.f;
+        for (int t0 = 0; t0 < N; t0 += 4) {
+            float acc[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int c = lane; c < nvec; c += 64) {
+                uint4 wv = wr[c];
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if (t0 + t < N) acc[t] = dot8_bf16(smem[(t0 + t) * nvec + c], wv, acc[t]);
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                float s = wave_sum(acc[t]);
+                if (lane == 0 && t0 + t < N) zbuf[((size_t)g * N + t0 + t) * E + e] = s + b;
+            }
+        }
+    }
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) sm_last = (atomicAdd(ticket, 1) == (int)gridDim.x - 1);
+    __syncthreads();
+    if (!sm_last) return;
+    __threadfence();
+    for (int i = threadIdx.x; i < E; i += 256) sm_pop[i] = 0;
+    __syncthreads();
+    const int njobs = (Wg2 ? 2 : 1) * N;
+    for (int j0 = 0; j0 < njobs; j0 += 4) {
+        int job = j0 + wave;
+        int g = job >= N, t = g ? job - N : job;
+        if (job < njobs) {
+            const volatile float* zr = zbuf + ((size_t)g * N + t) * E;
+            for (int e = lane; e < E; e += 64) sm_z[wave][e] = zr[e];
+        }
+        __syncthreads();
+        if (job < njobs) {
+            if (!g) {
+                wave_softmax_topm(sm_z[wave], E, k, renorm, sm_ids + t * k, w + (size_t)t * k, nullptr, nullptr);
+            } else {
+                wave_softmax_topm(sm_z[wave], E, m, 0, pids + (size_t)t * m, pw + (size_t)t * m, nullptr, sm_pop);
+            }
+        }
+        __syncthreads();
+    }
+    for (int i = threadIdx.x; i < N * k; i += 256) ids[i] = sm_ids[i];
+    if (Wg2)
+        for (int i = threadIdx.x; i < E; i += 256) pop[i] = sm_pop[i];
+    block_permute(sm_ids, N * k, E, counts, offsets, perm, inv_perm, order, sm_perm);
+    if (threadIdx.x == 0) *ticket = 0;
+}
+
+static fate_status check_route_args(const void* x, const void* Wg, const float* bias, int N, int H, int E, int k,
+                                    int m, const void* ids, const void* w) {
+    if (N < 0) FATE_FAIL(FATE_EINVAL, "N = %d < 0", N);
+    if (E < 1 || E > kMaxE) FATE_FAIL(FATE_ESHAPE, "E = %d outside [1, %d]", E, kMaxE);
+    if (H < 64 || (H % 64) != 0) FATE_FAIL(FATE_ESHAPE, "H = %d must be a positive multiple of 64", H);
+    if (k < 1 || k > m) FATE_FAIL(FATE_EINVAL, "need 1 <= k <= m (k = %d, m = %d)", k, m);
+    if (m > E || m > kMaxM) FATE_FAIL(FATE_EINVAL, "m = %d exceeds min(E, %d)", m, kMaxM);
+    if (N == 0) return FATE_OK;
+    FATE_CHECK_PTR(x);
+    FATE_CHECK_PTR(Wg);
+    FATE_CHECK_PTR_OPT(bias);
+    FATE_CHECK_PTR(ids);
+    FATE_CHECK_PTR(w);
+    return FATE_OK;
+}
+
+static int pick_tpw(int N, int H, int E) {
+    if (N < 256) return 1;
+    for (int tpw = 4; tpw > 1; tpw >>= 1)
+        if ((size_t)4 * tpw * (2 * (size_t)H + 4 * (size_t)E) <= 65536) return tpw;
+    return 1;
+}
+
+static fate_status launch_route_rows(hipStream_t st, const void* x, const void* Wg, const float* bias, int N,
+                                     int H, int E, int m, int renorm, int32_t* ids, float* w, float* probs,
+                                     int32_t* pop) {
+    const int tpw = pick_tpw(N, H, E);
+    const size_t lds = (size_t)4 * tpw * (2 * (size_t)H + 4 * (size_t)E);
+    if (lds > 65536) FATE_FAIL(FATE_ESHAPE, "H = %d, E = %d need %zu bytes of LDS (> 64 KiB)", H, E, lds);
+    const int grid = (N + 4 * tpw - 1) / (4 * tpw);
+    auto xs = static_cast<const uint16_t*>(x);
+    auto ws = static_cast<const uint16_t*>(Wg);
+    switch (tpw) {
+        case 4: route_rows_kernel<4><<<grid, 256, lds, st>>>(xs, ws, bias, N, H, E, m, renorm, ids, w, probs, pop); break;
+        case 2: route_rows_kernel<2><<<grid, 256, lds, st>>>(xs, ws, bias, N, H, E, m, renorm, ids, w, probs, pop); break;
+        default: route_rows_kernel<1><<<grid, 256, lds, st>>>(xs, ws, bias, N, H, E, m, renorm, ids, w, probs, pop); break;
+    }
+    FATE_HIP(hipGetLastError());
+    return FATE_OK;
+}
+
+}  // namespace fate
+
+using namespace fate;
+
+extern "C" fate_status fate_gate_route(void* stream, const void* x_bf16, const void* Wg_bf16, const float* bias,
+                                       int N, int H, int E, int k, int renorm, int32_t* topk_ids, float* topk_w,
+                                       float* probs) {
+    fate_status s = check_route_args(x_bf16, Wg_bf16, bias, N, H, E, k, k, topk_ids, topk_w);
+    if (s != FATE_OK) return s;
+    FATE_CHECK_PTR_OPT(probs);
+    if (N == 0) return FATE_OK;
+    return launch_route_rows(static_cast<hipStream_t>(stream), x_bf16, Wg_bf16, bias, N, H, E, k, renorm != 0,
+                             topk_ids, topk_w, probs, nullptr);
+}
+
+extern "C" fate_status fate_cross_layer_predict(void* stream, const void* x_bf16, const void* Wg_next_bf16,
+                                                const float* bias_next, int N, int H, int E, int k, int m,
+                                                int32_t* pred_ids, float* pred_w, int32_t* pred_pop) {
+    fate_status s = check_route_args(x_bf16, Wg_next_bf16, bias_next, N, H, E, k, m, pred_ids, pred_w);
+    if (s != FATE_OK) return s;
+    if (pred_pop == nullptr) FATE_FAIL(FATE_EINVAL, "pred_pop is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    fill_i32_kernel<<<(E + 255) / 256, 256, 0, st>>>(pred_pop, E, 0);
+    FATE_HIP(hipGetLastError());
+    if (N == 0) return FATE_OK;
+    return launch_route_rows(st, x_bf16, Wg_next_bf16, bias_next, N, H, E, m, 0, pred_ids, pred_w, nullptr,
+                             pred_pop);
+}
+
+extern "C" fate_status fate_permute(void* stream, const int32_t* topk_ids, int N, int k, int E, int32_t* counts,
+                                    int32_t* offsets, int32_t* perm, int32_t* inv_perm, int32_t* expert_order) {
+    if (N < 0 || k < 1) FATE_FAIL(FATE_EINVAL, "need N >= 0 and k >= 1 (N = %d, k = %d)", N, k);
+    if (E < 1 || E > kMaxE) FATE_FAIL(FATE_ESHAPE, "E = %d outside [1, %d]", E, kMaxE);
+    if ((long long)N * k > 0x7fffffffLL) FATE_FAIL(FATE_ESHAPE, "N*k overflows int32");
+    if (counts == nullptr || offsets == nullptr || expert_order == nullptr)
+        FATE_FAIL(FATE_EINVAL, "counts, offsets and expert_order must not be NULL");
+    if (N > 0 && (topk_ids == nullptr || perm == nullptr || inv_perm == nullptr))
+        FATE_FAIL(FATE_EINVAL, "topk_ids, perm and inv_perm must not be NULL when N > 0");
+    permute_kernel<<<1, 1024, 0, static_cast<hipStream_t>(stream)>>>(topk_ids, N * k, E, counts, offsets, perm,
+                                                                    inv_perm, expert_order);
+    FATE_HIP(hipGetLastError());
+    return FATE_OK;
+}
+
+extern "C" fate_status fate_route_fused_workspace(int N, int E, size_t* bytes) {
+    if (bytes == nullptr) FATE_FAIL(FATE_EINVAL, "bytes is NULL");
+    if (N < 0 || E < 1 || E > kMaxE) FATE_FAIL(FATE_EINVAL, "bad N or E");
+    *bytes = 256 + (size_t)2 * (size_t)(N > 0 ? N : 1) * E * sizeof(float);
+    return FATE_OK;
+}
+
+extern "C" fate_status fate_route_fused(void* stream, const void* x_bf16, const void* Wg_bf16, const float* bias,
+                                        const void* Wg_next_bf16, const float* bias_next, int N, int H, int E,
+                                        int k, int m, int renorm, int32_t* topk_ids, float* topk_w,
+                                        int32_t* pred_ids, float* pred_w, int32_t* pred_pop, int32_t* counts,
+                                        int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                                        int32_t* expert_order, void* workspace, size_t workspace_bytes) {
+    fate_status s = check_route_args(x_bf16, Wg_bf16, bias, N, H, E, k, m, topk_ids, topk_w);
+    if (s != FATE_OK) return s;
+    if (N < 1 || N > kFusedMaxN) FATE_FAIL(FATE_ESHAPE, "fused routing needs 1 <= N <= %d (N = %d)", kFusedMaxN, N);
+    if ((size_t)N * H * 2 > 65536 - 0) FATE_FAIL(FATE_ESHAPE, "N*H = %d*%d does not fit the 64 KiB x tile", N, H);
+    if (Wg_next_bf16) {
+        FATE_CHECK_PTR(Wg_next_bf16);
+        FATE_CHECK_PTR_OPT(bias_next);
+        if (!pred_ids || !pred_w || !pred_pop) FATE_FAIL(FATE_EINVAL, "pred outputs must not be NULL");
+    }
+    if (!counts || !offsets || !perm || !inv_perm || !expert_order)
+        FATE_FAIL(FATE_EINVAL, "permutation outputs must not be NULL");
+    size_t need = 0;
+    fate_route_fused_workspace(N, E, &need);
+    if (workspace == nullptr || workspace_bytes < need)
+        FATE_FAIL(FATE_EWORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    FATE_CHECK_PTR(workspace);
+    const int nrows = Wg_next_bf16 ? 2 * E : E;
+    const int grid = (nrows + 3) / 4;
+    const size_t lds = (size_t)N * H * 2;
+    route_fused_kernel<<<grid, 256, lds, static_cast<hipStream_t>(stream)>>>(
+        static_cast<const uint16_t*>(x_bf16), static_cast<const uint16_t*>(Wg_bf16), bias,
+        static_cast<const uint16_t*>(Wg_next_bf16), bias_next, N, H, E, k, m, renorm != 0, topk_ids, topk_w,
+        pred_ids, pred_w, pred_pop, counts, offsets, perm, inv_perm, expert_order,
+        static_cast<int32_t*>(workspace), reinterpret_cast<float*>(static_cast<char*>(workspace) + 256));
+    FATE_HIP(hipGetLastError());
+    return FATE_OK;
+}
