@@ -1,0 +1,266 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+Workloads (all synthetic, seeded):
+  qwen_decode (default)  Qwen1.5-MoE-shaped stack, 24 layers, batch 1 decode.
+                         A step is one token through all 24 layers: fused
+                         routing + cross-layer prediction + permutation, the
+                         quantised expert FFN, and the cache step.
+  qwen_prefill512 / qwen_prefill2048 / deepseek_prefill1024 / mixtral_prefill2048
+                         one prefill pass of N tokens through the stack's layers.
+Prints one JSON line (see the design doc for the fields).
+"""
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2500.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def expert_bytes(H, I, bits, group):
+    """Algorithmic bytes of one expert: codes + fp16 scales of W1, W3, W2."""
+    return 3 * (H * I * bits // 8 + H * I // group * 2)
+
+
+def cpu_baseline_decode(cfg, xs, layers_sample, tokens_sample):
+    """Times the plain fp64 oracle on host cores for a bounded sample."""
+    import numpy as np
+    import torch
+    from oracle import moe as O
+    from workloads import gen_expert, gen_gate, gen_shared_gate
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    dev = "cuda"
+    # stage the stored weights of the sampled layers on the host first (not timed)
+    staged = {}
+    for l in layers_sample:
+        Wg, b = gen_gate(cfg, l, dev)
+        staged[l] = dict(Wg=Wg.float().cpu().numpy(), b=None if b is None else b.cpu().numpy(),
+                         sg=gen_shared_gate(cfg, l, dev), experts={}, shared=[])
+        if staged[l]["sg"] is not None:
+            staged[l]["sg"] = staged[l]["sg"].float().cpu().numpy()
+    t_total = 0.0
+    n_units = 0
+    for s in tokens_sample:
+        for l in layers_sample:
+            x = xs[s, l].float().cpu().numpy()
+            st = staged[l]
+            ids, w, _, _ = O.gate_route(x, st["Wg"], st["b"], cfg.k, cfg.renorm)
+            need = sorted(set(ids.ravel().tolist()))
+            host = {e: gen_expert(cfg, l, e, device=dev).cpu() for e in need}
+            sh = [gen_expert(cfg, l, i, shared=True, device=dev).cpu() for i in range(cfg.n_shared)]
+            t0 = time.perf_counter()
+            ids, w, _, _ = O.gate_route(x, st["Wg"], st["b"], cfg.k, cfg.renorm)
+            if l + 1 < cfg.layers and (l + 1) in staged:
+                O.cross_layer_predict(x, staged[l + 1]["Wg"], staged[l + 1]["b"], cfg.m)
+            O.permute(ids, cfg.E)
+            ex = {e: O.OracleExpert(h.w1.numpy(), h.s1.numpy(), h.w3.numpy(), h.s3.numpy(), h.w2.numpy(),
+                                    h.s2.numpy(), h.bits, h.group) for e, h in host.items()}
+            shx = [O.OracleExpert(h.w1.numpy(), h.s1.numpy(), h.w3.numpy(), h.s3.numpy(), h.w2.numpy(),
+                                  h.s2.numpy(), h.bits, h.group) for h in sh]
+            O.moe_ffn(x, ids, w, ex, shx, st["sg"])
+            t_total += time.perf_counter() - t0
+            n_units += 1
+    per_layer_token = t_total / n_units
+    return per_layer_token, n_units, t_total
+
+
+def bench_decode(args):
+    import numpy as np
+    import torch
+    import paper_2502_12224_amd.binding as B
+    from paper_2502_12224_amd.stack import LayerBuffers, MoEStack, layer_forward
+    from workloads import SHAPES
+
+    cfg = SHAPES["qwen"]
+    dev = "cuda"
+    N, S = 1, 128
+    L, E, H = cfg.layers, cfg.E, cfg.H
+    t0 = time.time()
+    log(f"[bench] generating {L} layers x ({E} routed + {cfg.n_shared} shared) experts on the device ...")
+    stack = MoEStack(cfg, dev, progress=lambda l: log(f"[bench]   layer {l} packed ({time.time() - t0:.0f}s)") if l % 6 == 5 else None)
+    log(f"[bench] weights resident: {stack.nbytes() / 1e9:.2f} GB")
+
+    # untimed free-running chain: the gate inputs of every layer and step
+    xs, true_ids, pred_ids = stack.chain(N, S)
+    torch.cuda.synchronize()
+    log(f"[bench] chained {S} decode steps ({time.time() - t0:.0f}s)")
+    t_ids = true_ids.cpu().numpy()       # [S, L, N, k]
+    p_ids = pred_ids.cpu().numpy()       # [S, L, N, m]  (prediction made at layer l for layer l+1)
+    acc_k = rec_m = 0.0
+    for s in range(S):
+        for l in range(L - 1):
+            tr = set(t_ids[s, l + 1, 0].tolist())
+            acc_k += len(tr & set(p_ids[s, l, 0, :cfg.k].tolist())) / cfg.k
+            rec_m += len(tr & set(p_ids[s, l, 0].tolist())) / cfg.k
+    acc_k /= S * (L - 1)
+    rec_m /= S * (L - 1)
+
+    # per-layer buffers whose counts / predicted popularity sit in one arena
+    bufs = [LayerBuffers(cfg, N, dev) for _ in range(L)]
+    counts_all = torch.zeros(L, E, dtype=torch.int32, device=dev)
+    pop_all = torch.zeros(L, E, dtype=torch.int32, device=dev)
+    for l, b in enumerate(bufs):
+        b.counts = counts_all[l]
+        b.pred_pop = pop_all[l]
+    x_in = torch.zeros(L, N, H, dtype=torch.bfloat16, device=dev)
+    host_counts = [torch.zeros(2, L, E, dtype=torch.int32).pin_memory() for _ in range(2)]
+
+    def enqueue_token():
+        for l in range(L):
+            layer_forward(cfg, stack.layers[l], stack.layers[l + 1] if l + 1 < L else None, x_in[l], bufs[l])
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        x_in.copy_(xs[0])
+        enqueue_token()            # warm every kernel before capture
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            enqueue_token()
+    torch.cuda.synchronize()
+
+    # the cache: every expert resident (capacity = L*E), accounting only
+    lib = B.lib()
+    cache = lib.fate_cache_create(L, E, L * E, cfg.L_shallow, 0, 0, B.COPY_FN(0), None)
+    stats = B.fate_cache_stats()
+    tot = dict(hits=0, misses=0)
+    evs = [torch.cuda.Event() for _ in range(2)]
+
+    def account(slot):
+        evs[slot].synchronize()
+        hc = host_counts[slot]
+        rc = lib.fate_expert_cache_step_layers(cache, 0, L, C.c_void_p(hc[0].data_ptr()),
+                                               C.c_void_p(hc[1].data_ptr()), C.byref(stats))
+        assert rc == 0, lib.fate_last_error()
+        tot["hits"] += stats.n_hit_cache + stats.n_hit_prefetch
+        tot["misses"] += stats.n_miss
+
+    def run_tokens(n, first_step):
+        for i in range(n):
+            s = (first_step + i) % S
+            x_in.copy_(xs[s], non_blocking=True)
+            graph.replay()
+            slot = i & 1
+            host_counts[slot][0].copy_(counts_all, non_blocking=True)
+            host_counts[slot][1].copy_(pop_all, non_blocking=True)
+            evs[slot].record()
+            if i > 0:
+                account(slot ^ 1)
+        if n > 0:
+            account((n - 1) & 1)
+
+    run_tokens(args.warmup, 0)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    run_tokens(args.steps, args.warmup)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed * 1e3 / args.steps
+    tok_s = args.steps * N / elapsed
+    log(f"[bench] {args.steps} tokens in {elapsed * 1e3:.1f} ms -> {tok_s:.1f} tok/s")
+
+    # results of the graph path equal the eager chain (same inputs)
+    x_in.copy_(xs[3]); graph.replay(); torch.cuda.synchronize()
+    assert np.array_equal(bufs[5].ids.cpu().numpy(), t_ids[3, 5]), "graph replay diverged from the chain"
+
+    # roofline of the dominant kernel (first FFN half: W1/W3 stream = 2/3 of the bytes)
+    up_bytes = 2 * (cfg.k * (cfg.I * H // 2 + cfg.I * H // cfg.group * 2)
+                    + cfg.n_shared * (cfg.I_shared * H // 2 + cfg.I_shared * H // cfg.group * 2)) + N * H * 2
+    reps = 20
+    blocker = torch.randn(8192, 8192, dtype=torch.float32, device=dev)   # keeps the queue busy while launches pile up
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    x_in.copy_(xs[1]); graph.replay()
+    up_ms = []
+    for phase in (1, 0):
+        for _ in range(3):
+            torch.mm(blocker, blocker)
+        e0.record()
+        for _ in range(reps):
+            for l in range(L):
+                bufs[l].desc.phases = phase
+                B.fate_moe_ffn_q(bufs[l].desc, x_in[l], stack.layers[l].table, bufs[l].counts, bufs[l].offsets,
+                                 bufs[l].perm, bufs[l].inv_perm, bufs[l].order, bufs[l].w,
+                                 stack.layers[l].shared_table, stack.layers[l].shared_gate, bufs[l].y,
+                                 bufs[l].ffn_ws)
+        e1.record()
+        torch.cuda.synchronize()
+        up_ms.append(e0.elapsed_time(e1) / (reps * L))
+    for b in bufs:
+        b.desc.phases = 0
+    up_us, ffn_us = up_ms[0] * 1e3, up_ms[1] * 1e3
+    achieved = up_bytes / (up_us * 1e-6) / 1e9
+    layer_bytes = cfg.k * expert_bytes(H, cfg.I, cfg.bits, cfg.group) + \
+        cfg.n_shared * expert_bytes(H, cfg.I_shared, cfg.shared_bits, cfg.group) + 2 * E * H * 2
+    log(f"[bench] up kernel {up_us:.2f} us/launch ({achieved:.0f} GB/s), whole FFN call {ffn_us:.2f} us, "
+        f"layer algorithmic bytes {layer_bytes / 1e6:.1f} MB")
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        ncores = len(os.sched_getaffinity(0))
+        per, n_units, t_cpu = cpu_baseline_decode(cfg, xs, layers_sample=[0, 1, 12], tokens_sample=[0, 1])
+        cpu = {"value": 1.0 / (per * L), "unit": "tokens/s", "cores": min(ncores, torch.get_num_threads()),
+               "kind": "oracle",
+               "sample": f"{n_units} (token, layer) units of the same stack (layers 0, 1, 12; decode steps 0, 1), "
+                         f"{t_cpu:.1f} s of oracle time, scaled to {L} layers per token"}
+        log(f"[bench] oracle: {per:.2f} s per (token, layer) on the host")
+
+    out = {
+        "metric": "MoE-layer tokens/s (decode b=1, prefill 512) + % HBM / MFMA roofline",
+        "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int4 weights, bf16/fp16 activations, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": "configs[1]: Qwen1.5-MoE-shaped decode, 24 layers chained, batch 1, "
+                               "60 experts top-4 (I=1408) + gated shared expert (I=5632), int4 g128",
+                   "step": "one token through 24 MoE layers (route+predict+permute fused, FFN, cache step)",
+                   "layers": L, "batch": N, "decode_steps_cycled": S,
+                   "layer_us": ms_per_step * 1e3 / L, "layer_algorithmic_MB": layer_bytes / 1e6,
+                   "layer_hbm_frac": layer_bytes / (ms_per_step * 1e-3 / L) / 1e9 / HBM_PEAK_GBS,
+                   "prediction_accuracy_topk": acc_k, "prediction_recall_topm": rec_m, "m": cfg.m,
+                   "cache_hit_rate": tot["hits"] / max(1, tot["hits"] + tot["misses"]),
+                   "ffn_call_us": ffn_us},
+        "roofline": {"bound": "hbm", "kernel": "ffn_up_decode_kernel<1>", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": up_bytes, "us_per_launch": up_us},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--workload", default="qwen_decode")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); the multi-GPU sharding is design-only.",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback.", file=sys.stderr)
+        sys.exit(3)
+    if args.workload == "qwen_decode":
+        bench_decode(args)
+    else:
+        from paper_2502_12224_amd.bench_prefill import bench_prefill
+        bench_prefill(args)
+
+
+if __name__ == "__main__":
+    main()

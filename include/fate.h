@@ -154,7 +154,8 @@ typedef struct {
  *
  * x_bf16 [N,H] dev.  experts_dev: device array [E] of fate_qexpert; shared_dev:
  * device array [n_shared] or NULL.  counts/offsets/perm: outputs of
- * fate_permute for this layer's ids (dev).  topk_w [N,k] dev.
+ * fate_permute for this layer's ids (dev), as are inv_perm and expert_order.
+ * topk_w [N,k] dev.
  * expert_order [E] dev (from fate_permute).  y [N,H] dev, fp32 (y_is_fp32) or
  * bf16, overwritten.  I_max / I_shared_max bound the intermediate sizes in the
  * tables (host-known; used to size launches and scratch); bits/group of the
@@ -171,12 +172,15 @@ typedef struct {
     int32_t n_shared, I_shared_max, shared_bits, shared_group;
     int32_t y_is_fp32;
     int32_t mode;
+    int32_t phases;   /* profiling aid: 0 = whole FFN; 1 = first half only (up/gate
+                         projections + SwiGLU into scratch); 2 = second half only */
 } fate_ffn_desc;
 
 fate_status fate_moe_ffn_q_workspace(const fate_ffn_desc* d, size_t* bytes);
 fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, const void* x_bf16,
                            const fate_qexpert* experts_dev, const int32_t* counts, const int32_t* offsets,
-                           const int32_t* perm, const int32_t* expert_order, const float* topk_w,
+                           const int32_t* perm, const int32_t* inv_perm, const int32_t* expert_order,
+                           const float* topk_w,
                            const fate_qexpert* shared_dev, const void* shared_gate_bf16,
                            void* y, void* workspace, size_t workspace_bytes);
 
@@ -241,6 +245,20 @@ fate_status fate_expert_cache_step(fate_cache*, int layer,
                                    const int32_t* pred_ids, const int32_t* pred_pop, int n_pred,
                                    int32_t* compute_order, int32_t* slots,
                                    fate_cache_load* loads, int max_loads, fate_cache_stats* stats);
+
+/* Dense front ends.  counts [E] and pred_pop [E] (may be NULL) are the arrays
+ * fate_permute / fate_cross_layer_predict produce, copied to the host; experts
+ * are taken in id order (so ties in count or popularity go to the lower id).
+ * compute_order / slots: host arrays of E entries; n_actual_out may be NULL. */
+fate_status fate_expert_cache_step_dense(fate_cache*, int layer, const int32_t* counts, const int32_t* pred_pop,
+                                         int32_t* compute_order, int32_t* slots, int32_t* n_actual_out,
+                                         fate_cache_load* loads, int max_loads, fate_cache_stats* stats);
+/* Accounting over a range of fully cached layers [layer_begin, layer_end):
+ * counts / pred_pop are [layers][E]; the statistics are summed.  Returns
+ * FATE_ENOTRESIDENT if a layer of the range is not fully cached (such layers
+ * need their own step before their FFN runs). */
+fate_status fate_expert_cache_step_layers(fate_cache*, int layer_begin, int layer_end, const int32_t* counts,
+                                          const int32_t* pred_pop, fate_cache_stats* stats_sum);
 
 /* Built-in HIP copy engine.  slot_pool_dev: total_slots * slot_bytes of device
  * memory; host_pool_pinned: num_layers*E experts of slot_bytes each (pinned),

@@ -22,7 +22,8 @@ EXPORTS = [
     "fate_route_fused_workspace", "fate_route_fused", "fate_pack_weight", "fate_moe_ffn_q_workspace",
     "fate_moe_ffn_q", "fate_cache_total_from_budget", "fate_n_max_from_times", "fate_cache_layer_capacities",
     "fate_cache_create", "fate_cache_destroy", "fate_cache_total_slots", "fate_cache_slot_of",
-    "fate_cache_resident", "fate_expert_cache_step", "fate_hip_engine_create", "fate_hip_engine_destroy",
+    "fate_cache_resident", "fate_expert_cache_step", "fate_expert_cache_step_dense",
+    "fate_expert_cache_step_layers", "fate_hip_engine_create", "fate_hip_engine_destroy",
     "fate_hip_engine_copy", "fate_hip_engine_begin_step", "fate_hip_engine_wait_ready",
     "fate_hip_engine_preload", "fate_hip_engine_bytes_copied",
 ]
@@ -36,7 +37,8 @@ class FateError(RuntimeError):
 
 class fate_ffn_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("N", "H", "E", "k", "I_max", "bits", "group", "n_shared",
-                                         "I_shared_max", "shared_bits", "shared_group", "y_is_fp32", "mode")]
+                                         "I_shared_max", "shared_bits", "shared_group", "y_is_fp32", "mode",
+                                         "phases")]
 
 
 class fate_qexpert(C.Structure):
@@ -91,6 +93,9 @@ def lib():
         L.fate_expert_cache_step.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
                                              C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                              C.c_void_p]
+        L.fate_expert_cache_step_dense.argtypes = [C.c_void_p, C.c_int] + [C.c_void_p] * 6 + [C.c_int, C.c_void_p]
+        L.fate_expert_cache_step_layers.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                                    C.c_void_p]
         L.fate_hip_engine_create.restype = C.c_void_p
         L.fate_hip_engine_create.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                              C.c_void_p, C.c_void_p, C.c_void_p]
@@ -173,10 +178,10 @@ def fate_moe_ffn_q_workspace(desc):
     return b.value
 
 
-def fate_moe_ffn_q(desc, x, experts_dev, counts, offsets, perm, expert_order, topk_w, shared_dev, shared_gate,
-                   y, workspace, stream=None):
+def fate_moe_ffn_q(desc, x, experts_dev, counts, offsets, perm, inv_perm, expert_order, topk_w, shared_dev,
+                   shared_gate, y, workspace, stream=None):
     _check(lib().fate_moe_ffn_q(_stream(stream), C.byref(desc), _p(x), _p(experts_dev), _p(counts), _p(offsets),
-                                _p(perm), _p(expert_order), _p(topk_w), _p(shared_dev), _p(shared_gate), _p(y),
+                                _p(perm), _p(inv_perm), _p(expert_order), _p(topk_w), _p(shared_dev), _p(shared_gate), _p(y),
                                 _p(workspace), C.c_size_t(workspace.numel() * workspace.element_size())))
 
 
@@ -219,6 +224,6 @@ def expert_table(structs, device="cuda"):
 
 
 def make_ffn_desc(N, H, E, k, I_max, bits, group, n_shared=0, I_shared_max=0, shared_bits=4, shared_group=128,
-                  y_is_fp32=True, mode=0):
+                  y_is_fp32=True, mode=0, phases=0):
     return fate_ffn_desc(N, H, E, k, I_max, bits, group, n_shared, I_shared_max, shared_bits, shared_group,
-                         int(y_is_fp32), mode)
+                         int(y_is_fp32), mode, phases)

@@ -368,3 +368,59 @@ extern "C" fate_status fate_expert_cache_step(fate_cache* c, int layer, const in
     *stats = st;
     return FATE_OK;
 }
+
+// ---- dense-count front ends -------------------------------------------------
+// The device produces per-expert pair counts [E] (fate_permute) and predicted
+// popularity [E] (fate_cross_layer_predict); these wrappers take those arrays
+// as they are, in id order, and build the unique lists themselves.
+
+extern "C" fate_status fate_expert_cache_step_dense(fate_cache* c, int layer, const int32_t* counts,
+                                                    const int32_t* pred_pop, int32_t* compute_order,
+                                                    int32_t* slots, int32_t* n_actual_out,
+                                                    fate_cache_load* loads, int max_loads,
+                                                    fate_cache_stats* stats) {
+    if (!c || !counts || !compute_order || !slots || !stats) {
+        fate::set_error("fate_expert_cache_step_dense: bad argument");
+        return FATE_EINVAL;
+    }
+    const int E = c->E;
+    int32_t ids[256], cnt[256], pids[256], ppop[256];
+    int n = 0, np = 0;
+    for (int e = 0; e < E; ++e)
+        if (counts[e] > 0) { ids[n] = e; cnt[n] = counts[e]; ++n; }
+    if (pred_pop)
+        for (int e = 0; e < E; ++e)
+            if (pred_pop[e] > 0) { pids[np] = e; ppop[np] = pred_pop[e]; ++np; }
+    if (n_actual_out) *n_actual_out = n;
+    return fate_expert_cache_step(c, layer, ids, cnt, n, pids, ppop, np, compute_order, slots, loads, max_loads,
+                                  stats);
+}
+
+extern "C" fate_status fate_expert_cache_step_layers(fate_cache* c, int layer_begin, int layer_end,
+                                                     const int32_t* counts, const int32_t* pred_pop,
+                                                     fate_cache_stats* stats_sum) {
+    if (!c || !counts || !stats_sum || layer_begin < 0 || layer_end > c->num_layers || layer_begin > layer_end) {
+        fate::set_error("fate_expert_cache_step_layers: bad argument");
+        return FATE_EINVAL;
+    }
+    for (int l = layer_begin; l < layer_end; ++l)
+        if (!c->full[l]) {
+            fate::set_error("layer %d is not fully cached: step it on its own", l);
+            return FATE_ENOTRESIDENT;
+        }
+    fate_cache_stats sum{};
+    int32_t order[256], slots[256];
+    for (int l = layer_begin; l < layer_end; ++l) {
+        fate_cache_stats st{};
+        const size_t o = (size_t)(l - layer_begin) * c->E;
+        fate_status s = fate_expert_cache_step_dense(c, l, counts + o, pred_pop ? pred_pop + o : nullptr, order,
+                                                     slots, nullptr, nullptr, 0, &st);
+        if (s != FATE_OK) return s;
+        sum.n_hit_cache += st.n_hit_cache; sum.n_hit_prefetch += st.n_hit_prefetch; sum.n_miss += st.n_miss;
+        sum.pair_hits += st.pair_hits; sum.pair_misses += st.pair_misses;
+        sum.n_prefetch_issued += st.n_prefetch_issued; sum.n_prefetch_dropped += st.n_prefetch_dropped;
+        sum.n_wasted += st.n_wasted; sum.n_evicted += st.n_evicted; sum.n_loads += st.n_loads;
+    }
+    *stats_sum = sum;
+    return FATE_OK;
+}

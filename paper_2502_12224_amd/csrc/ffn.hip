@@ -25,6 +25,7 @@ static fate_status check_desc(const fate_ffn_desc* d) {
             FATE_FAIL(FATE_ESHAPE, "I_shared_max = %d / H must be multiples of 64 and of the shared group", d->I_shared_max);
     }
     if (d->mode < 0 || d->mode > 2) FATE_FAIL(FATE_EINVAL, "mode = %d", d->mode);
+    if (d->phases < 0 || d->phases > 3) FATE_FAIL(FATE_EINVAL, "phases = %d", d->phases);
     if ((long long)d->N * d->k > 0x3fffffffLL) FATE_FAIL(FATE_ESHAPE, "N*k too large");
     return FATE_OK;
 }
@@ -60,8 +61,8 @@ extern "C" fate_status fate_moe_ffn_q_workspace(const fate_ffn_desc* d, size_t* 
 
 extern "C" fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, const void* x_bf16,
                                       const fate_qexpert* experts_dev, const int32_t* counts,
-                                      const int32_t* offsets, const int32_t* perm, const int32_t* expert_order,
-                                      const float* topk_w, const fate_qexpert* shared_dev,
+                                      const int32_t* offsets, const int32_t* perm, const int32_t* inv_perm,
+                                      const int32_t* expert_order, const float* topk_w, const fate_qexpert* shared_dev,
                                       const void* shared_gate_bf16, void* y, void* workspace,
                                       size_t workspace_bytes) {
     fate_status s = check_desc(d);
@@ -70,8 +71,8 @@ extern "C" fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, cons
     FATE_CHECK_PTR(x_bf16);
     FATE_CHECK_PTR(y);
     FATE_CHECK_PTR_OPT(shared_gate_bf16);
-    if (!experts_dev || !counts || !offsets || !perm || !expert_order || !topk_w)
-        FATE_FAIL(FATE_EINVAL, "experts, counts, offsets, perm, expert_order and topk_w must not be NULL");
+    if (!experts_dev || !counts || !offsets || !perm || !inv_perm || !expert_order || !topk_w)
+        FATE_FAIL(FATE_EINVAL, "experts, counts, offsets, perm, inv_perm, expert_order and topk_w must not be NULL");
     if (d->n_shared && !shared_dev) FATE_FAIL(FATE_EINVAL, "shared_dev is NULL with n_shared = %d", d->n_shared);
     FfnWorkspace w;
     carve(*d, workspace, &w);
@@ -83,7 +84,7 @@ extern "C" fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, cons
     a.x = static_cast<const uint16_t*>(x_bf16);
     a.N = d->N; a.H = d->H; a.E = d->E; a.k = d->k;
     a.experts = experts_dev; a.shared = shared_dev; a.n_shared = d->n_shared;
-    a.counts = counts; a.offsets = offsets; a.perm = perm; a.order = expert_order; a.topk_w = topk_w;
+    a.counts = counts; a.offsets = offsets; a.perm = perm; a.inv_perm = inv_perm; a.order = expert_order; a.topk_w = topk_w;
     a.shared_gate = static_cast<const uint16_t*>(shared_gate_bf16);
     a.bits_r = d->bits; a.group_r = d->group;
     a.bits_s = d->n_shared ? d->shared_bits : d->bits; a.group_s = d->n_shared ? d->shared_group : d->group;

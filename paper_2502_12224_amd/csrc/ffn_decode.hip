@@ -340,9 +340,10 @@ fate_status launch_ffn_decode(hipStream_t st, const fate_ffn_desc& d, DecodeArgs
     const int nrb = d.H / 32;
     const int grid_down = a.nact * nrb * a.nchunk_r + d.n_shared * nrb * a.nchunk_s;
     const size_t lu = lds_up(TT), ld = lds_down(TT);
+    const bool do_up = d.phases != 2, do_down = d.phases != 1;
 #define FATE_LAUNCH_DECODE(TTV)                                                   \
-    ffn_up_decode_kernel<TTV><<<grid_up, 256, lu, st>>>(a);                      \
-    ffn_down_decode_kernel<TTV><<<grid_down, 256, ld, st>>>(a);
+    if (do_up) ffn_up_decode_kernel<TTV><<<grid_up, 256, lu, st>>>(a);           \
+    if (do_down) ffn_down_decode_kernel<TTV><<<grid_down, 256, ld, st>>>(a);
     switch (TT) {
         case 8: FATE_LAUNCH_DECODE(8) break;
         case 4: FATE_LAUNCH_DECODE(4) break;
@@ -351,7 +352,7 @@ fate_status launch_ffn_decode(hipStream_t st, const fate_ffn_desc& d, DecodeArgs
     }
 #undef FATE_LAUNCH_DECODE
     FATE_HIP(hipGetLastError());
-    if (!d.y_is_fp32) {
+    if (!d.y_is_fp32 && do_down) {
         const long long n = (long long)d.N * d.H;
         f32_to_bf16_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(a.y, static_cast<uint16_t*>(y_out), n);
         FATE_HIP(hipGetLastError());

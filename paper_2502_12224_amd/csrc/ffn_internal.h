@@ -14,6 +14,7 @@ struct DecodeArgs {
     const int32_t* counts;
     const int32_t* offsets;
     const int32_t* perm;
+    const int32_t* inv_perm;
     const int32_t* order;
     const float* topk_w;
     const uint16_t* shared_gate;

@@ -67,9 +67,9 @@ def test_argument_validation_without_gpu():
     assert L.fate_moe_ffn_q_workspace(C.byref(bad), C.byref(nb)) == 1
     bad = B.make_ffn_desc(4, 2048, 60, 4, 1400, 4, 128)
     assert L.fate_moe_ffn_q_workspace(C.byref(bad), C.byref(nb)) == 2
-    assert L.fate_moe_ffn_q(z, C.byref(d), p16, p16, p16, p16, p16, p16, p16, p16, z, p16, p16, C.c_size_t(8)) == 4
+    assert L.fate_moe_ffn_q(z, C.byref(d), p16, p16, p16, p16, p16, p16, p16, p16, p16, z, p16, p16, C.c_size_t(8)) == 4
     d0 = B.make_ffn_desc(0, 2048, 60, 4, 1408, 4, 128)
-    assert L.fate_moe_ffn_q(z, C.byref(d0), z, z, z, z, z, z, z, z, z, z, z, C.c_size_t(0)) == 0
+    assert L.fate_moe_ffn_q(z, C.byref(d0), z, z, z, z, z, z, z, z, z, z, z, z, C.c_size_t(0)) == 0
 
 
 def test_closed_forms_match_oracle():

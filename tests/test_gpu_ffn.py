@@ -62,7 +62,7 @@ def _layer_case(name, N, layer=0, mode=0, y_is_fp32=True, seed_step=0):
     torch.cuda.synchronize()
     used = sorted(set(ids.cpu().numpy().ravel().tolist()))
     L = GpuLayer(cfg, layer, experts=used)
-    y, ws = L.ffn(x, counts, offsets, perm, order, w, mode=mode, y_is_fp32=y_is_fp32)
+    y, ws = L.ffn(x, counts, offsets, perm, inv, order, w, mode=mode, y_is_fp32=y_is_fp32)
     assert int(ws[:4].view(torch.int32)[0]) == 0
     # the oracle gets the same x, the GPU's routing (checked elsewhere) and the same stored weights
     experts = {e: oracle_expert(L.host[e]) for e in used}
@@ -96,5 +96,5 @@ def test_ffn_flags_missing_expert():
     counts, offsets, perm, inv, order = gpu_permute(ids, cfg.E)
     used = sorted(set(ids.cpu().numpy().ravel().tolist()))
     L = GpuLayer(cfg, 0, experts=used[1:])        # one activated expert is not on the device
-    y, ws = L.ffn(x, counts, offsets, perm, order, w, mode=1)
+    y, ws = L.ffn(x, counts, offsets, perm, inv, order, w, mode=1)
     assert int(ws[:4].view(torch.int32)[0]) != 0
