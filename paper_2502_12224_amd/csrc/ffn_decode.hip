@@ -9,6 +9,9 @@
 //  down: a workgroup owns 32 output rows of W2 of one expert and a chunk of
 //        the reduction dimension, and adds weight * (W2 h) into y (fp32
 //        atomics; at most a few contributions per element).
+// Every wave requests its first D weight tiles before anything else and keeps
+// D tiles per matrix in flight (register ring), so the HBM stream starts
+// while the activations are still being staged in LDS.
 // Codes are widened in registers (qformat.h); the per-group fp16 scale is
 // applied to the fp32 group partial sum, so each weight enters exactly.
 #include <hip/hip_fp16.h>
@@ -18,121 +21,168 @@
 
 namespace fate {
 
+constexpr int kRingUp = 6;     // weight tiles in flight per matrix per wave (two matrices)
+constexpr int kRingDown = 8;   // same for the single-matrix down kernel
+
+// pointers into expert weights come out of a table in memory; telling the
+// compiler they are global (not generic) pointers gives global_load, not flat_load
+#if defined(__HIP_DEVICE_COMPILE__)
+#define FATE_GLOBAL __attribute__((address_space(1)))
+#else
+#define FATE_GLOBAL
+#endif
+typedef const FATE_GLOBAL uint4* gu4_t;
+typedef const FATE_GLOBAL uint16_t* gu16_t;
+template <class T>
+__device__ __forceinline__ const FATE_GLOBAL T* as_global(const void* p) {
+    return (const FATE_GLOBAL T*)(uintptr_t)p;
+}
+__device__ __forceinline__ float half_bits_to_float(uint32_t b) { return __half2float(__ushort_as_half((unsigned short)b)); }
+
+template <int NMAT, int D>
+struct TileRing {
+    uint4 raw[NMAT][D];
+    uint32_t sc[NMAT][D];   // fp16 bits, one full register each (no 16-bit merges on arrival)
+    int pf_g, pf_tl;   // group / position-in-group of the next tile to request
+};
+
+// request the first D tiles of [g_beg*tpg, g_end*tpg)
+template <int NMAT, int D>
+__device__ __forceinline__ void ring_start(TileRing<NMAT, D>& r, const gu4_t* wt, const gu16_t* sc,
+                                           int g_beg, int g_end, int tpg) {
+    const int tbeg = g_beg * tpg, tend = g_end * tpg;
+    int g = g_beg, tl = 0;
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+        if (tbeg + j < tend) {
+#pragma unroll
+            for (int i = 0; i < NMAT; ++i) {
+                r.raw[i][j] = wt[i][(size_t)(tbeg + j) * 64];
+                r.sc[i][j] = sc[i][g];
+            }
+        }
+        if (++tl == tpg) { tl = 0; ++g; }
+    }
+    r.pf_g = g;
+    r.pf_tl = tl;
+}
+
 // One wave accumulates, for up to TT activation rows held in LDS, the dot
 // products of NMAT weight row-blocks (one row per lane pair) over the groups
-// [g_beg, g_end).  wt[i]: tile pointer of the row-block, already offset by the
-// lane; sc[i]: scale row of this lane's weight row.  xs: activations as
-// dwords (pairs), row stride ldx_dw, column 0 of xs = absolute column k_base.
-// xgs[(t*G + g)*2 + half]: sum of the activations this lane half multiplies
-// in group g (absolute group index minus g_base).
-template <int BITS, bool F16, int TT, int NMAT>
-__device__ __forceinline__ void gemv_rowblock(const uint4* const* wt, const __half* const* sc, int g_beg,
-                                              int g_end, int tpg, const uint32_t* xs, int ldx_dw, int k_base,
-                                              const float* xgs, int G, int g_base, int nt,
-                                              float (&out)[NMAT][TT]) {
+// [g_beg, g_end); ring_start must have been called with the same range.
+// xs: activations as dwords (pairs), row stride ldx_dw; xs16: per row, sums of
+// each run of 16 activations; column 0 of both = absolute column k_base.
+template <int BITS, bool F16, int TT, int NMAT, int D>
+__device__ __forceinline__ void ring_run(TileRing<NMAT, D>& r, const gu4_t* wt, const gu16_t* sc,
+                                         int g_beg, int g_end, int tpg, const uint32_t* xs, int ldx_dw,
+                                         int k_base, const float* xs16, int ld16, int nt,
+                                         float (&out)[NMAT][TT]) {
     constexpr int KT = QFmt<BITS>::KT, NP = QFmt<BITS>::NP;
     constexpr float OFF = q_offset<BITS, F16>();
     const int half = (threadIdx.x & 63) >> 5;
-    int tile = g_beg * tpg;
-    const int tend = g_end * tpg;
-    uint4 nxt[NMAT];
+    const int tbeg = g_beg * tpg, tend = g_end * tpg;
+    float ga[NMAT][TT], gx[TT];
 #pragma unroll
-    for (int i = 0; i < NMAT; ++i) nxt[i] = (tile < tend) ? wt[i][(size_t)tile * 64] : make_uint4(0, 0, 0, 0);
-    for (int g = g_beg; g < g_end; ++g) {
-        float ga[NMAT][TT];
-        float sg[NMAT];
+    for (int t = 0; t < TT; ++t) {
+        gx[t] = 0.f;
 #pragma unroll
-        for (int i = 0; i < NMAT; ++i) {
-            sg[i] = __half2float(sc[i][g]);
+        for (int i = 0; i < NMAT; ++i) ga[i][t] = 0.f;
+    }
+    int tl = 0;
+    for (int base = tbeg; base < tend; base += D) {
 #pragma unroll
-            for (int t = 0; t < TT; ++t) ga[i][t] = 0.f;
-        }
-        for (int tl = 0; tl < tpg; ++tl, ++tile) {
-            uint32_t p[NMAT][NP];
+        for (int j = 0; j < D; ++j) {
+            const int tile = base + j;
+            if (tile < tend) {
+                uint32_t p[NMAT][NP];
+                float s[NMAT];
 #pragma unroll
-            for (int i = 0; i < NMAT; ++i) {
-                uint4 raw = nxt[i];
-                if (tile + 1 < tend) nxt[i] = wt[i][(size_t)(tile + 1) * 64];
-                unpack_pairs<BITS, F16>(raw, p[i]);
-            }
-            const int xoff = (tile * KT - k_base + half * (KT / 2)) >> 1;
+                for (int i = 0; i < NMAT; ++i) {
+                    unpack_pairs<BITS, F16>(r.raw[i][j], p[i]);
+                    s[i] = half_bits_to_float(r.sc[i][j]);
+                }
+                if (tile + D < tend) {
 #pragma unroll
-            for (int t = 0; t < TT; ++t) {
-                if (t < nt) {
-                    const uint4* xr = reinterpret_cast<const uint4*>(xs + t * ldx_dw + xoff);
+                    for (int i = 0; i < NMAT; ++i) {
+                        r.raw[i][j] = wt[i][(size_t)(tile + D) * 64];
+                        r.sc[i][j] = sc[i][r.pf_g];
+                    }
+                }
+                if (++r.pf_tl == tpg) { r.pf_tl = 0; ++r.pf_g; }
+                const int kloc = tile * KT - k_base + half * (KT / 2);
 #pragma unroll
-                    for (int q = 0; q < NP / 4; ++q) {
-                        uint4 xv = xr[q];
+                for (int t = 0; t < TT; ++t) {
+                    if (t < nt) {
+                        const uint4* xr = reinterpret_cast<const uint4*>(xs + t * ldx_dw + (kloc >> 1));
+#pragma unroll
+                        for (int q = 0; q < NP / 4; ++q) {
+                            uint4 xv = xr[q];
+#pragma unroll
+                            for (int i = 0; i < NMAT; ++i) {
+                                ga[i][t] = dot2<F16>(xv.x, p[i][4 * q + 0], ga[i][t]);
+                                ga[i][t] = dot2<F16>(xv.y, p[i][4 * q + 1], ga[i][t]);
+                                ga[i][t] = dot2<F16>(xv.z, p[i][4 * q + 2], ga[i][t]);
+                                ga[i][t] = dot2<F16>(xv.w, p[i][4 * q + 3], ga[i][t]);
+                            }
+                        }
+                        const float* px = xs16 + t * ld16 + (kloc >> 4);
+                        if constexpr (BITS == 4) gx[t] += px[0] + px[1]; else gx[t] += px[0];
+                    }
+                }
+                if (++tl == tpg) {
+                    tl = 0;
+#pragma unroll
+                    for (int t = 0; t < TT; ++t) {
 #pragma unroll
                         for (int i = 0; i < NMAT; ++i) {
-                            ga[i][t] = dot2<F16>(xv.x, p[i][4 * q + 0], ga[i][t]);
-                            ga[i][t] = dot2<F16>(xv.y, p[i][4 * q + 1], ga[i][t]);
-                            ga[i][t] = dot2<F16>(xv.z, p[i][4 * q + 2], ga[i][t]);
-                            ga[i][t] = dot2<F16>(xv.w, p[i][4 * q + 3], ga[i][t]);
+                            out[i][t] = fmaf(s[i], fmaf(-OFF, gx[t], ga[i][t]), out[i][t]);
+                            ga[i][t] = 0.f;
                         }
+                        gx[t] = 0.f;
                     }
                 }
             }
         }
-#pragma unroll
-        for (int t = 0; t < TT; ++t) {
-            if (t < nt) {
-                float xsum = xgs[(t * G + (g - g_base)) * 2 + half];
-#pragma unroll
-                for (int i = 0; i < NMAT; ++i) out[i][t] = fmaf(sg[i], fmaf(-OFF, xsum, ga[i][t]), out[i][t]);
-            }
-        }
     }
 }
 
-// sums of 16-bit activations over the column segments a lane half multiplies
-template <bool F16>
-__device__ __forceinline__ void group_half_sums(const uint32_t* xs, int ldx_dw, int nt, int G, int group,
-                                                int KT, float* xgs) {
-    const int tpg = group / KT, seg_dw = KT / 4;   // KT/2 columns = KT/4 dwords
-    for (int idx = threadIdx.x; idx < nt * G * 2; idx += blockDim.x) {
-        const int half = idx & 1, g = (idx >> 1) % G, t = (idx >> 1) / G;
-        float s = 0.f;
-        for (int tl = 0; tl < tpg; ++tl) {
-            const uint32_t* px = xs + t * ldx_dw + ((g * group + tl * KT + half * (KT / 2)) >> 1);
-            for (int j = 0; j < seg_dw; ++j) {
-                uint32_t v = px[j];
-                if constexpr (F16) {
-                    __half2 hv = *reinterpret_cast<const __half2*>(&v);
-                    s += __low2float(hv) + __high2float(hv);
-                } else {
-                    s += bf16_lo(v) + bf16_hi(v);
-                }
-            }
-        }
-        xgs[idx] = s;   // idx == (t*G + g)*2 + half
-    }
+__device__ __forceinline__ float sum8_bf16(const uint4& v) {
+    return ((bf16_lo(v.x) + bf16_hi(v.x)) + (bf16_lo(v.y) + bf16_hi(v.y))) +
+           ((bf16_lo(v.z) + bf16_hi(v.z)) + (bf16_lo(v.w) + bf16_hi(v.w)));
+}
+__device__ __forceinline__ float sum8_f16(const uint4& v) {
+    const __half2* h = reinterpret_cast<const __half2*>(&v);
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s += __low2float(h[i]) + __high2float(h[i]);
+    return s;
 }
 
 template <int TT>
-__global__ __launch_bounds__(256) void ffn_up_decode_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void ffn_up_decode_kernel(DecodeArgs a) {
     extern __shared__ uint4 smem[];
     __shared__ float red[2][4][TT][32];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    {   // clear this block's slice of y
-        const long long total = (long long)a.N * a.H;
-        const long long per = (total + gridDim.x - 1) / gridDim.x;
-        const long long b0 = (long long)blockIdx.x * per;
-        const long long b1 = b0 + per < total ? b0 + per : total;
-        for (long long i = b0 + tid; i < b1; i += 256) a.y[i] = 0.f;
-    }
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+#ifdef FATE_PROBE
+    unsigned long long ts[8];
+    ts[0] = wall_clock64();
+#define FATE_TS(i) ts[i] = wall_clock64()
+#else
+#define FATE_TS(i)
+#endif
     int b = blockIdx.x;
     const int nrout = a.nact * a.rb_r;
     const fate_qexpert* ex;
     int rb, T, sbeg = 0, bits, group, ldh;
     __half* hbuf;
     const bool is_shared = b >= nrout;
+    bool live = true;
     if (!is_shared) {
         const int slot = b / a.rb_r;
         rb = b % a.rb_r;
         const int e = a.order[slot];
         T = a.counts[e];
-        if (T == 0) return;
+        live = T > 0;
         ex = a.experts + e;
         sbeg = a.offsets[e];
         bits = a.bits_r; group = a.group_r;
@@ -146,44 +196,71 @@ __global__ __launch_bounds__(256) void ffn_up_decode_kernel(DecodeArgs a) {
         bits = a.bits_s; group = a.group_s;
         hbuf = a.h_s + (size_t)s * a.N * a.ldh_s; ldh = a.ldh_s;
     }
-    const int I = ex->I;
-    if (rb * 32 >= I) return;
-    const uint4* w1 = static_cast<const uint4*>(ex->w1);
-    const uint4* w3 = static_cast<const uint4*>(ex->w3);
-    if (w1 == nullptr || w3 == nullptr) {
-        if (tid == 0) atomicOr(a.status, 1);
-        return;
+    gu4_t w1 = nullptr;
+    gu4_t w3 = nullptr;
+    if (live) {
+        live = rb * 32 < ex->I;
+        w1 = as_global<uint4>(ex->w1);
+        w3 = as_global<uint4>(ex->w3);
+        if (live && (w1 == nullptr || w3 == nullptr)) {
+            if (tid == 0) atomicOr(a.status, 1);
+            live = false;
+        }
     }
-    const int H = a.H, nvec = H >> 3, G = H / group;
+    const int H = a.H, nvec = H >> 3, G = H / group, ld16 = H >> 4;
     const int KT = bits == 4 ? 64 : 32;
     const int tiles_k = H / KT, tpg = group / KT;
     const int n = lane & 31;
-    const uint4* wt[2] = {w1 + (size_t)rb * tiles_k * 64 + lane, w3 + (size_t)rb * tiles_k * 64 + lane};
-    const __half* sc[2] = {static_cast<const __half*>(ex->s1) + (size_t)(rb * 32 + n) * G,
-                           static_cast<const __half*>(ex->s3) + (size_t)(rb * 32 + n) * G};
+    gu4_t wt[2];
+    gu16_t sc[2];
     const int g_beg = G * wave / 4, g_end = G * (wave + 1) / 4;
+    TileRing<2, kRingUp> ring;
+    if (live) {
+        wt[0] = w1 + (size_t)rb * tiles_k * 64 + lane;
+        wt[1] = w3 + (size_t)rb * tiles_k * 64 + lane;
+        sc[0] = as_global<uint16_t>(ex->s1) + (size_t)(rb * 32 + n) * G;
+        sc[1] = as_global<uint16_t>(ex->s3) + (size_t)(rb * 32 + n) * G;
+        FATE_TS(1);
+        ring_start<2, kRingUp>(ring, wt, sc, g_beg, g_end, tpg);
+    }
+    FATE_TS(2);
+    {   // clear this block's slice of y
+        const long long total = (long long)a.N * a.H;
+        const long long per = (total + gridDim.x - 1) / gridDim.x;
+        const long long b0 = (long long)blockIdx.x * per;
+        const long long b1 = b0 + per < total ? b0 + per : total;
+        for (long long i = b0 + tid; i < b1; i += 256) a.y[i] = 0.f;
+    }
+    if (!live) return;
     uint32_t* xs = reinterpret_cast<uint32_t*>(smem);
-    float* xgs = reinterpret_cast<float*>(smem + (size_t)TT * nvec);
+    float* xs16 = reinterpret_cast<float*>(smem + (size_t)TT * nvec);
     const uint4* xg = reinterpret_cast<const uint4*>(a.x);
 
     for (int t0 = 0; t0 < T; t0 += TT) {
         const int nt = min(TT, T - t0);
-        __syncthreads();
+        if (t0 > 0) {
+            __syncthreads();
+            ring_start<2, kRingUp>(ring, wt, sc, g_beg, g_end, tpg);
+        }
         for (int idx = tid; idx < nt * nvec; idx += 256) {
             const int t = idx / nvec, c = idx - t * nvec;
             const int tok = is_shared ? t0 + t : a.perm[sbeg + t0 + t] / a.k;
-            smem[t * nvec + c] = xg[(size_t)tok * nvec + c];
+            const uint4 v = xg[(size_t)tok * nvec + c];
+            smem[t * nvec + c] = v;
+            float s = sum8_bf16(v);
+            s += __shfl_xor(s, 1, 64);
+            if (!(c & 1)) xs16[t * ld16 + (c >> 1)] = s;
         }
         __syncthreads();
-        group_half_sums<false>(xs, H >> 1, nt, G, group, KT, xgs);
-        __syncthreads();
+        FATE_TS(3);
         float out[2][TT];
 #pragma unroll
         for (int t = 0; t < TT; ++t) out[0][t] = out[1][t] = 0.f;
         if (bits == 4)
-            gemv_rowblock<4, false, TT, 2>(wt, sc, g_beg, g_end, tpg, xs, H >> 1, 0, xgs, G, 0, nt, out);
+            ring_run<4, false, TT, 2, kRingUp>(ring, wt, sc, g_beg, g_end, tpg, xs, H >> 1, 0, xs16, ld16, nt, out);
         else
-            gemv_rowblock<8, false, TT, 2>(wt, sc, g_beg, g_end, tpg, xs, H >> 1, 0, xgs, G, 0, nt, out);
+            ring_run<8, false, TT, 2, kRingUp>(ring, wt, sc, g_beg, g_end, tpg, xs, H >> 1, 0, xs16, ld16, nt, out);
+        FATE_TS(4);
 #pragma unroll
         for (int t = 0; t < TT; ++t) {
             float v1 = out[0][t] + __shfl_xor(out[0][t], 32, 64);
@@ -198,15 +275,23 @@ __global__ __launch_bounds__(256) void ffn_up_decode_kernel(DecodeArgs a) {
             const float hv = a1 / (1.0f + expf(-a1)) * a3;
             hbuf[(size_t)(t0 + t) * ldh + rb * 32 + nn] = __float2half(hv);
         }
+#ifdef FATE_PROBE
+        FATE_TS(5);
+        if (tid == 0 && (blockIdx.x == 0 || blockIdx.x == nrout || blockIdx.x == gridDim.x - 1)) {
+            unsigned long long* o = reinterpret_cast<unsigned long long*>(a.status) + 8 +
+                                    (blockIdx.x == 0 ? 0 : blockIdx.x == nrout ? 8 : 16);
+            for (int i = 0; i < 6; ++i) o[i] = ts[i];
+        }
+#endif
     }
 }
 
 template <int TT>
-__global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void ffn_down_decode_kernel(DecodeArgs a) {
     extern __shared__ uint4 smem[];
     __shared__ float red[4][TT][32];
     __shared__ float sgate[TT];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nrb = a.H >> 5;
     int b = blockIdx.x;
     const int nrout = a.nact * nrb * a.nchunk_r;
@@ -238,26 +323,34 @@ __global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
     const int I = ex->I, G = I / group;
     const int gb = ch * cg, ge = min(G, gb + cg);
     if (gb >= ge) return;
-    const uint4* w2 = static_cast<const uint4*>(ex->w2);
+    gu4_t w2 = as_global<uint4>(ex->w2);
     if (w2 == nullptr) return;   // flagged by the up kernel
     const int KT = bits == 4 ? 64 : 32;
     const int tiles_k = I / KT, tpg = group / KT;
     const int n = lane & 31;
-    const uint4* wt[1] = {w2 + (size_t)rb * tiles_k * 64 + lane};
-    const __half* sc[1] = {static_cast<const __half*>(ex->s2) + (size_t)(rb * 32 + n) * G};
+    gu4_t wt[1] = {w2 + (size_t)rb * tiles_k * 64 + lane};
+    gu16_t sc[1] = {as_global<uint16_t>(ex->s2) + (size_t)(rb * 32 + n) * G};
     const int ng = ge - gb;
     const int g_beg = gb + ng * wave / 4, g_end = gb + ng * (wave + 1) / 4;
-    const int Kc = ng * group, kvec = Kc >> 3, k_base = gb * group;
+    TileRing<1, kRingDown> ring;
+    ring_start<1, kRingDown>(ring, wt, sc, g_beg, g_end, tpg);
+    const int Kc = ng * group, kvec = Kc >> 3, k_base = gb * group, ld16 = Kc >> 4;
     uint32_t* xs = reinterpret_cast<uint32_t*>(smem);
-    float* xgs = reinterpret_cast<float*>(smem + (size_t)TT * kvec);
+    float* xs16 = reinterpret_cast<float*>(smem + (size_t)TT * kvec);
 
     for (int t0 = 0; t0 < T; t0 += TT) {
         const int nt = min(TT, T - t0);
-        __syncthreads();
+        if (t0 > 0) {
+            __syncthreads();
+            ring_start<1, kRingDown>(ring, wt, sc, g_beg, g_end, tpg);
+        }
         for (int idx = tid; idx < nt * kvec; idx += 256) {
             const int t = idx / kvec, c = idx - t * kvec;
-            smem[t * kvec + c] =
-                *reinterpret_cast<const uint4*>(hbuf + (size_t)(t0 + t) * ldh + k_base + c * 8);
+            const uint4 v = *reinterpret_cast<const uint4*>(hbuf + (size_t)(t0 + t) * ldh + k_base + c * 8);
+            smem[t * kvec + c] = v;
+            float s = sum8_f16(v);
+            s += __shfl_xor(s, 1, 64);
+            if (!(c & 1)) xs16[t * ld16 + (c >> 1)] = s;
         }
         if (is_shared && a.shared_gate != nullptr) {
             const uint4* sgv = reinterpret_cast<const uint4*>(a.shared_gate);
@@ -277,15 +370,13 @@ __global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
             }
         }
         __syncthreads();
-        group_half_sums<true>(xs, Kc >> 1, nt, ng, group, KT, xgs);
-        __syncthreads();
         float out[1][TT];
 #pragma unroll
         for (int t = 0; t < TT; ++t) out[0][t] = 0.f;
         if (bits == 4)
-            gemv_rowblock<4, true, TT, 1>(wt, sc, g_beg, g_end, tpg, xs, Kc >> 1, k_base, xgs, ng, gb, nt, out);
+            ring_run<4, true, TT, 1, kRingDown>(ring, wt, sc, g_beg, g_end, tpg, xs, Kc >> 1, k_base, xs16, ld16, nt, out);
         else
-            gemv_rowblock<8, true, TT, 1>(wt, sc, g_beg, g_end, tpg, xs, Kc >> 1, k_base, xgs, ng, gb, nt, out);
+            ring_run<8, true, TT, 1, kRingDown>(ring, wt, sc, g_beg, g_end, tpg, xs, Kc >> 1, k_base, xs16, ld16, nt, out);
 #pragma unroll
         for (int t = 0; t < TT; ++t) {
             float v = out[0][t] + __shfl_xor(out[0][t], 32, 64);
@@ -317,18 +408,15 @@ __global__ void f32_to_bf16_kernel(const float* __restrict__ src, uint16_t* __re
 
 fate_status launch_ffn_decode(hipStream_t st, const fate_ffn_desc& d, DecodeArgs a, void* y_out) {
     int TT = d.N <= 1 ? 1 : d.N <= 2 ? 2 : d.N <= 4 ? 4 : 8;
-    // LDS of the up kernel: TT rows of x (bf16) + group sums; of the down kernel: TT rows of an h chunk
-    auto lds_up = [&](int tt) {
-        size_t g = (size_t)d.H / (size_t)(d.n_shared ? min(d.group, d.shared_group) : d.group);
-        return (size_t)tt * d.H * 2 + (size_t)tt * g * 2 * 4;
-    };
+    // LDS of the up kernel: TT rows of x (bf16) + their 16-wide sums; of the down kernel: TT rows of an h chunk
+    auto lds_up = [&](int tt) { return (size_t)tt * d.H * 2 + (size_t)tt * (d.H / 16) * 4; };
     const int Gr = d.I_max / d.group, Gs = d.n_shared ? d.I_shared_max / d.shared_group : 0;
     a.nchunk_r = (Gr + 15) / 16; a.cg_r = (Gr + a.nchunk_r - 1) / a.nchunk_r;
     a.nchunk_s = Gs ? (Gs + 15) / 16 : 1; a.cg_s = Gs ? (Gs + a.nchunk_s - 1) / a.nchunk_s : 1;
     auto lds_down = [&](int tt) {
         size_t kr = (size_t)a.cg_r * d.group, ks = d.n_shared ? (size_t)a.cg_s * d.shared_group : 0;
         size_t kc = kr > ks ? kr : ks;
-        return (size_t)tt * kc * 2 + (size_t)tt * 16 * 2 * 4 + 256;
+        return (size_t)tt * kc * 2 + (size_t)tt * (kc / 16) * 4;
     };
     while (TT > 1 && (lds_up(TT) > 40960 || lds_down(TT) > 40960)) TT >>= 1;
     if (lds_up(TT) > 40960 || lds_down(TT) > 40960)

@@ -1,24 +1,35 @@
 // Device-side building blocks of routing: wave-level softmax + top-m
-// selection, and the block-level stable token-to-expert permutation.
+// selection, and the stable token-to-expert permutation (one-wave form for
+// up to 64 pairs, workgroup form for any number).
 #pragma once
 #include "common.h"
 
 namespace fate {
 
+constexpr int kVPL = kMaxE / 64;   // values per lane when a wave holds E <= 256 entries
+
+__device__ __forceinline__ float lane_bcast(float v, int src) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src));
+}
+__device__ __forceinline__ int lane_bcast(int v, int src) { return __builtin_amdgcn_readlane(v, src); }
+
 // One wavefront turns E logits (z, readable by every lane) into the softmax
 // over all experts and the m largest entries, ordered by logit descending
-// with ties to the lower id.  Lane j < m ends up with the j-th selection.
-// ids_out/w_out may point to global or LDS memory.  pop (optional) receives
-// +1 per selected expert.  renorm != 0 divides the m weights by their sum.
-__device__ __forceinline__ void wave_softmax_topm(const float* z, int E, int m, int renorm,
-                                                  int32_t* ids_out, float* w_out, float* probs_out,
-                                                  int32_t* pop) {
+// with ties to the lower id.  Selection is by rank: every entry counts the
+// entries that precede it in that order (the wave broadcasts one entry at a
+// time), and the entries of rank < m write themselves to position rank.
+// NS = ceil(E/64) values per lane.  ids_out/w_out may point to global or LDS
+// memory.  pop (optional) receives +1 per selected expert.  renorm != 0
+// divides the m weights by their sum.
+template <int NS>
+__device__ __forceinline__ void wave_softmax_topm_ns(const float* z, int E, int m, int renorm,
+                                                     int32_t* ids_out, float* w_out, float* probs_out,
+                                                     int32_t* pop) {
     const int lane = threadIdx.x & 63;
-    constexpr int VPL = kMaxE / 64;
-    float v[VPL];
+    float v[NS];
     float lmax = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < VPL; ++i) {
+    for (int i = 0; i < NS; ++i) {
         int e = lane + 64 * i;
         float t = (e < E) ? z[e] : -INFINITY;
         if (t != t) t = -INFINITY;   // NaN logits are treated as -inf
@@ -26,47 +37,130 @@ __device__ __forceinline__ void wave_softmax_topm(const float* z, int E, int m, 
         lmax = fmaxf(lmax, t);
     }
     const float zmax = wave_max(lmax);
+    float p[NS];
     float lsum = 0.f;
 #pragma unroll
-    for (int i = 0; i < VPL; ++i) lsum += (lane + 64 * i < E) ? expf(v[i] - zmax) : 0.f;
+    for (int i = 0; i < NS; ++i) {
+        p[i] = (lane + 64 * i < E) ? __expf(v[i] - zmax) : 0.f;
+        lsum += p[i];
+    }
     const float inv = 1.0f / wave_sum(lsum);
-    if (probs_out) {
+    int rank[NS];
 #pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            int e = lane + 64 * i;
-            if (e < E) probs_out[e] = expf(v[i] - zmax) * inv;
+    for (int i = 0; i < NS; ++i) {
+        p[i] *= inv;
+        rank[i] = 0;
+        if (probs_out && lane + 64 * i < E) probs_out[lane + 64 * i] = p[i];
+    }
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        const int lim = min(64, E - 64 * s);
+        for (int src = 0; src < lim; ++src) {
+            const float zj = lane_bcast(v[s], src);
+            const int ej = src + 64 * s;
+#pragma unroll
+            for (int i = 0; i < NS; ++i) rank[i] += (zj > v[i]) || (zj == v[i] && ej < lane + 64 * i);
         }
     }
-    unsigned taken = 0;
-    int my_id = 0;
-    float my_w = 0.f;
-    float wsum = 0.f;
-    for (int j = 0; j < m; ++j) {
-        float bv = -INFINITY;
-        int bi = 0x7fffffff;
+    float wsel = 0.f;
 #pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            int e = lane + 64 * i;
-            bool ok = (e < E) && !((taken >> i) & 1u);
-            if (ok && (bi == 0x7fffffff || v[i] > bv)) { bv = v[i]; bi = e; }
-        }
+    for (int i = 0; i < NS; ++i)
+        if (rank[i] < m && lane + 64 * i < E) wsel += p[i];
+    const float scale = renorm ? 1.0f / wave_sum(wsel) : 1.0f;
 #pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) {
-            float ov = __shfl_xor(bv, o, 64);
-            int oi = __shfl_xor(bi, o, 64);
-            if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
+    for (int i = 0; i < NS; ++i) {
+        const int e = lane + 64 * i;
+        if (e < E && rank[i] < m) {
+            ids_out[rank[i]] = e;
+            w_out[rank[i]] = p[i] * scale;
+            if (pop) atomicAdd(&pop[e], 1);
         }
-        if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
-        float wj = expf(bv - zmax) * inv;
-        wsum += wj;
-        if (lane == j) { my_id = bi; my_w = wj; }
     }
-    if (renorm) my_w = my_w / wsum;
-    if (lane < m) {
-        ids_out[lane] = my_id;
-        w_out[lane] = my_w;
-        if (pop) atomicAdd(&pop[my_id], 1);
+}
+
+__device__ __forceinline__ void wave_softmax_topm(const float* z, int E, int m, int renorm,
+                                                  int32_t* ids_out, float* w_out, float* probs_out,
+                                                  int32_t* pop) {
+    if (E <= 64) wave_softmax_topm_ns<1>(z, E, m, renorm, ids_out, w_out, probs_out, pop);
+    else if (E <= 128) wave_softmax_topm_ns<2>(z, E, m, renorm, ids_out, w_out, probs_out, pop);
+    else wave_softmax_topm_ns<4>(z, E, m, renorm, ids_out, w_out, probs_out, pop);
+}
+
+// Stable grouping of P <= 64 pair indices by expert id, by ONE wavefront, in
+// registers.  Same outputs as block_permute.  Every lane of the wave calls it.
+template <int NS>
+__device__ __forceinline__ void wave_permute_small_ns(const int32_t* ids, int P, int E, int32_t* counts,
+                                                      int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                                                      int32_t* order) {
+    const int lane = threadIdx.x & 63;
+    const int ei = (lane < P) ? ids[lane] : -1;
+    const bool valid = lane < P && ei >= 0 && ei < E;
+    const int key = valid ? ei : -1;
+    int cnt[NS], off[NS], rk[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) cnt[s] = rk[s] = 0;
+    int before = 0;   // earlier pairs of the same expert
+    for (int src = 0; src < P; ++src) {
+        const int ej = lane_bcast(key, src);
+        before += (ej == key) && (src < lane);
+#pragma unroll
+        for (int s = 0; s < NS; ++s) cnt[s] += (ej == lane + 64 * s);
     }
+    int base = 0;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        // inclusive scan over the 64 lanes: DPP shifts inside rows of 16, then row carries
+        int inc = cnt[s];
+        inc += __builtin_amdgcn_update_dpp(0, inc, 0x111, 0xf, 0xf, true);   // row_shr:1
+        inc += __builtin_amdgcn_update_dpp(0, inc, 0x112, 0xf, 0xf, true);   // row_shr:2
+        inc += __builtin_amdgcn_update_dpp(0, inc, 0x114, 0xf, 0xf, true);   // row_shr:4
+        inc += __builtin_amdgcn_update_dpp(0, inc, 0x118, 0xf, 0xf, true);   // row_shr:8
+        const int r0 = lane_bcast(inc, 15), r1 = lane_bcast(inc, 31), r2 = lane_bcast(inc, 47),
+                  r3 = lane_bcast(inc, 63);
+        const int row = lane >> 4;
+        inc += (row > 0 ? r0 : 0) + (row > 1 ? r1 : 0) + (row > 2 ? r2 : 0);
+        off[s] = base + inc - cnt[s];
+        base += r0 + r1 + r2 + r3;
+        const int e = lane + 64 * s;
+        if (e < E) {
+            counts[e] = cnt[s];
+            offsets[e] = off[s];
+        }
+    }
+    if (lane == 0) offsets[E] = base;
+    int myoff = 0;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        int t = __shfl(off[s], ei & 63, 64);
+        if (valid && (ei >> 6) == s) myoff = t;
+    }
+    if (valid) {
+        perm[myoff + before] = lane;
+        inv_perm[lane] = myoff + before;
+    } else if (lane < P) {
+        inv_perm[lane] = -1;
+    }
+#pragma unroll
+    for (int s2 = 0; s2 < NS; ++s2) {
+        const int lim = min(64, E - 64 * s2);
+        for (int src = 0; src < lim; ++src) {
+            const int cj = lane_bcast(cnt[s2], src);
+            const int ej = src + 64 * s2;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) rk[s] += (cj > cnt[s]) || (cj == cnt[s] && ej < lane + 64 * s);
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+        if (lane + 64 * s < E) order[rk[s]] = lane + 64 * s;
+}
+
+__device__ __forceinline__ void wave_permute_small(const int32_t* ids, int P, int E, int32_t* counts,
+                                                   int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                                                   int32_t* order) {
+    if (E <= 64) wave_permute_small_ns<1>(ids, P, E, counts, offsets, perm, inv_perm, order);
+    else if (E <= 128) wave_permute_small_ns<2>(ids, P, E, counts, offsets, perm, inv_perm, order);
+    else wave_permute_small_ns<4>(ids, P, E, counts, offsets, perm, inv_perm, order);
 }
 
 // Per-lane mask of the lanes in this wave that hold the same key (valid lanes only).
@@ -88,7 +182,7 @@ constexpr int kPermSmemInts = (kPermMaxWaves + 2) * kMaxE;
 // Every thread of the block must call it.
 __device__ inline void block_permute(const int32_t* ids, int P, int E, int32_t* counts, int32_t* offsets,
                                      int32_t* perm, int32_t* inv_perm, int32_t* order, volatile int32_t* sm) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nthreads = blockDim.x, nw = nthreads >> 6;
     volatile int32_t* wc = sm;                 // [nw][E] per-wave counts, then running bases
     volatile int32_t* tot = sm + nw * E;       // [E] totals
