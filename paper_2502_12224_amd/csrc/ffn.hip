@@ -38,10 +38,18 @@ static void carve(const fate_ffn_desc& d, void* base, FfnWorkspace* w) {
     off += align_up((size_t)d.N * d.k * d.I_max * 2, 256);
     w->h_s = reinterpret_cast<__half*>(p + off);
     off += align_up((size_t)d.n_shared * d.N * (d.n_shared ? d.I_shared_max : 0) * 2, 256);
+    const bool mfma = d.mode == 2 || (d.mode == 0 && d.N > 16);
     w->ybuf = reinterpret_cast<float*>(p + off);
-    if (!d.y_is_fp32) off += align_up((size_t)d.N * d.H * 4, 256);
-    w->sgate = reinterpret_cast<float*>(p + off);
-    off += align_up((size_t)d.N * 4, 256);
+    if (!d.y_is_fp32 && !mfma) off += align_up((size_t)d.N * d.H * 4, 256);
+    if (mfma) {
+        const size_t nseg1 = (size_t)d.E + d.n_shared + 1;
+        w->ms.xh = reinterpret_cast<__half*>(p + off); off += align_up((size_t)d.N * d.H * 2, 256);
+        w->ms.sgate = reinterpret_cast<float*>(p + off); off += align_up((size_t)d.N * 4, 256);
+        w->ms.tab_up = reinterpret_cast<int32_t*>(p + off); off += align_up(nseg1 * 4, 256);
+        w->ms.tab_down = reinterpret_cast<int32_t*>(p + off); off += align_up(nseg1 * 4, 256);
+        w->ms.yp_r = reinterpret_cast<__half*>(p + off); off += align_up((size_t)d.N * d.k * d.H * 2, 256);
+        w->ms.yp_s = reinterpret_cast<__half*>(p + off); off += align_up((size_t)d.n_shared * d.N * d.H * 2, 256);
+    }
     w->bytes = off + 256;
 }
 
@@ -95,5 +103,5 @@ extern "C" fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, cons
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int mode = d->mode ? d->mode : (d->N <= 16 ? 1 : 2);
     if (mode == 1) return launch_ffn_decode(st, *d, a, y);
-    return launch_ffn_mfma(st, *d, a, w.sgate, y);
+    return launch_ffn_mfma(st, *d, a, w.ms, y);
 }

@@ -28,16 +28,26 @@ struct DecodeArgs {
     int nchunk_r, nchunk_s, cg_r, cg_s;   // reduction chunks of the down kernel
 };
 
+struct MfmaScratch {
+    __half* xh;        // [N,H] fp16 copy of x
+    float* sgate;      // [N] shared gate values
+    int32_t* tab_up;   // [E + n_shared + 1] tile prefix sums of the up GEMM
+    int32_t* tab_down; // same for the down GEMM
+    __half* yp_r;      // [P,H] per-pair outputs of the down GEMM
+    __half* yp_s;      // [n_shared*N,H]
+};
+
 struct FfnWorkspace {
     int32_t* status;
     __half* h_r;
     __half* h_s;
-    float* ybuf;     // only when the output is bf16
-    float* sgate;    // [N] shared gate values (MFMA path)
+    float* ybuf;     // decode path, only when the output is bf16
+    MfmaScratch ms;  // MFMA path only
     size_t bytes;
 };
 
 fate_status launch_ffn_decode(hipStream_t st, const fate_ffn_desc& d, DecodeArgs a, void* y_out);
-fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs a, float* sgate, void* y_out);
+fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs a, const MfmaScratch& ms,
+                            void* y_out);
 
 }  // namespace fate

@@ -98,3 +98,52 @@ def test_ffn_flags_missing_expert():
     L = GpuLayer(cfg, 0, experts=used[1:])        # one activated expert is not on the device
     y, ws = L.ffn(x, counts, offsets, perm, inv, order, w, mode=1)
     assert int(ws[:4].view(torch.int32)[0]) != 0
+
+
+def _mfma_case(name, N, rows=None, layer=0, y_is_fp32=True):
+    """MFMA path on N tokens; oracle on `rows` (all rows if None)."""
+    cfg = SHAPES[name]
+    x = gen_hidden(cfg, N, device=DEV)
+    Wg, b = gen_gate(cfg, layer, device=DEV)
+    ids, w, _ = gpu_route(x, Wg, b, cfg.k, cfg.renorm, want_probs=False)
+    counts, offsets, perm, inv, order = gpu_permute(ids, cfg.E)
+    torch.cuda.synchronize()
+    used = sorted(set(ids.cpu().numpy().ravel().tolist()))
+    L = GpuLayer(cfg, layer, experts=used)
+    y, ws = L.ffn(x, counts, offsets, perm, inv, order, w, mode=2, y_is_fp32=y_is_fp32)
+    assert int(ws[:4].view(torch.int32)[0]) == 0
+    rows = list(range(N)) if rows is None else rows
+    ids_h = ids.cpu().numpy()
+    need = sorted(set(ids_h[rows].ravel().tolist()))
+    experts = {e: oracle_expert(L.host[e]) for e in need}
+    shared = [oracle_expert(ex) for ex in L.shared_host]
+    sg = None if L.shared_gate is None else f32(L.shared_gate)
+    y_ref = O.moe_ffn_rows(f32(x), ids_h, w.cpu().numpy().astype(np.float64), experts, shared, sg, rows=rows)
+    yg = f32(y)
+    assert np.isfinite(yg).all()
+    return yg[rows], y_ref, counts.cpu().numpy()
+
+
+@pytest.mark.parametrize("name,N,rows", [
+    ("tiny", 16, None), ("tiny", 200, None), ("tiny", 1, None), ("tiny", 129, None),
+    ("qwen_prefill", 48, [0, 7, 47]), ("deepseek", 40, [1, 20, 39]), ("mixtral", 20, [3, 11]),
+])
+def test_ffn_mfma_matches_oracle(name, N, rows):
+    y, y_ref, counts = _mfma_case(name, N, rows)
+    err = ffn_rel_err(y, y_ref)
+    print(f"{name} N={N}: max row err {err.max():.2e}, busiest expert {counts.max()} rows")
+    assert err.max() <= TOL, err
+
+
+def test_ffn_mfma_bf16_output():
+    y, y_ref, _ = _mfma_case("tiny", 70, None, y_is_fp32=False)
+    assert ffn_rel_err(y, y_ref).max() <= 2 ** -8 + TOL
+
+
+def test_ffn_mfma_full_size_sampled_rows():
+    """Qwen-shaped prefill at N = 2048 (Zipf-skewed routing), oracle on sampled token rows."""
+    rows = [0, 511, 1024, 2047]
+    y, y_ref, counts = _mfma_case("qwen_prefill", 2048, rows)
+    err = ffn_rel_err(y, y_ref)
+    print(f"N=2048: max row err {err.max():.2e}; expert rows min/max {counts.min()}/{counts.max()}")
+    assert counts.sum() == 2048 * 4 and err.max() <= TOL, err
