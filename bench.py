@@ -239,14 +239,151 @@ def bench_decode(args):
     print(json.dumps(out), flush=True)
 
 
+PREFILL_WORKLOADS = {
+    # name: (shape, tokens, description)
+    "qwen_prefill512": ("qwen_prefill", 512, "configs[2]: Qwen1.5-MoE-shaped prefill, 512 tokens, Zipf(1.1) routing"),
+    "qwen_prefill2048": ("qwen_prefill", 2048, "configs[2]: Qwen1.5-MoE-shaped prefill, 2048 tokens, Zipf(1.1) routing"),
+    "deepseek_prefill1024": ("deepseek", 1024, "configs[3]: DeepSeek-MoE-16B-shaped prefill, 1024 tokens, all experts resident"),
+    "mixtral_prefill2048": ("mixtral", 2048, "configs[4]: Mixtral-8x7B-shaped prefill, 2048 tokens, all experts resident"),
+}
+
+
+def bench_prefill(args):
+    """One step = one prefill pass of N tokens through every layer of the stack
+    (routing, prediction, permutation, MFMA expert FFN, cache accounting)."""
+    import numpy as np
+    import torch
+    import paper_2502_12224_amd.binding as B
+    from paper_2502_12224_amd.stack import LayerBuffers, MoEStack, layer_forward
+    from workloads import SHAPES
+
+    shape, N, desc = PREFILL_WORKLOADS[args.workload]
+    cfg = SHAPES[shape]
+    dev = "cuda"
+    L = args.layers or cfg.layers
+    E, H = cfg.E, cfg.H
+    t0 = time.time()
+    log(f"[bench] {args.workload}: generating {L} layers on the device ...")
+    stack = MoEStack(cfg, dev, layers=L, progress=lambda l: log(f"[bench]   layer {l} packed ({time.time() - t0:.0f}s)"))
+    log(f"[bench] weights resident: {stack.nbytes() / 1e9:.2f} GB")
+    xs, true_ids, pred_ids = stack.chain(N, 1)          # gate inputs of every layer (untimed chain)
+    torch.cuda.synchronize()
+    t_ids, p_ids = true_ids.cpu().numpy()[0], pred_ids.cpu().numpy()[0]
+    set_acc = np.mean([len(set(p_ids[l].ravel()) & set(t_ids[l + 1].ravel())) / len(set(t_ids[l + 1].ravel()))
+                       for l in range(L - 1)]) if L > 1 else None
+    tok_acc = np.mean([np.mean([len(set(p_ids[l, t, :cfg.k]) & set(t_ids[l + 1, t])) / cfg.k for t in range(N)])
+                       for l in range(L - 1)]) if L > 1 else None
+    active = float(np.mean([len(set(t_ids[l].ravel())) for l in range(L)]))
+
+    bufs = [LayerBuffers(cfg, N, dev, mode=2) for _ in range(L)]
+    counts_all = torch.zeros(L, E, dtype=torch.int32, device=dev)
+    pop_all = torch.zeros(L, E, dtype=torch.int32, device=dev)
+    for l, b in enumerate(bufs):
+        b.counts = counts_all[l]
+        b.pred_pop = pop_all[l]
+    x_in = xs[0]
+
+    def enqueue_pass():
+        for l in range(L):
+            layer_forward(cfg, stack.layers[l], stack.layers[l + 1] if l + 1 < L else None, x_in[l], bufs[l])
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        enqueue_pass()
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            enqueue_pass()
+    torch.cuda.synchronize()
+    lib = B.lib()
+    cache = lib.fate_cache_create(L, E, L * E, cfg.L_shallow, 0, 0, B.COPY_FN(0), None)
+    stats = B.fate_cache_stats()
+    host_counts = torch.zeros(2, L, E, dtype=torch.int32).pin_memory()
+    hits = misses = 0
+
+    def one_pass():
+        nonlocal hits, misses
+        graph.replay()
+        host_counts[0].copy_(counts_all, non_blocking=True)
+        host_counts[1].copy_(pop_all, non_blocking=True)
+        torch.cuda.current_stream().synchronize()
+        rc = lib.fate_expert_cache_step_layers(cache, 0, L, C.c_void_p(host_counts[0].data_ptr()),
+                                               C.c_void_p(host_counts[1].data_ptr()), C.byref(stats))
+        assert rc == 0, lib.fate_last_error()
+        hits += stats.n_hit_cache + stats.n_hit_prefetch
+        misses += stats.n_miss
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        one_pass()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed * 1e3 / args.steps
+    tok_s = args.steps * N / elapsed
+    log(f"[bench] {args.steps} passes of {N} tokens x {L} layers in {elapsed * 1e3:.1f} ms -> {tok_s:.0f} tok/s")
+
+    # roofline of the dominant kernel: the up/gate grouped GEMM (2/3 of the FLOPs)
+    up_flops = 4.0 * H * (N * cfg.k * cfg.I + N * cfg.n_shared * (cfg.I_shared or 0))
+    layer_flops = 1.5 * up_flops
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    times = []
+    for phase in (1, 0):
+        reps = 3
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            for l in range(L):
+                bufs[l].desc.phases = phase
+                B.fate_moe_ffn_q(bufs[l].desc, x_in[l], stack.layers[l].table, bufs[l].counts, bufs[l].offsets,
+                                 bufs[l].perm, bufs[l].inv_perm, bufs[l].order, bufs[l].w,
+                                 stack.layers[l].shared_table, stack.layers[l].shared_gate, bufs[l].y, bufs[l].ffn_ws)
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1) * 1e3 / (reps * L))
+    for b in bufs:
+        b.desc.phases = 0
+    up_us, ffn_us = times
+    achieved = up_flops / (up_us * 1e-6) / 1e12
+    log(f"[bench] prep+up GEMM {up_us:.1f} us/layer ({achieved:.0f} TFLOP/s), whole FFN {ffn_us:.1f} us/layer "
+        f"({layer_flops / (ffn_us * 1e-6) / 1e12:.0f} TFLOP/s)")
+
+    out = {
+        "metric": "MoE-layer tokens/s (decode b=1, prefill 512) + % HBM / MFMA roofline",
+        "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int4/int8 weights dequantised to fp16, fp16 MFMA, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": desc, "step": f"one prefill pass of {N} tokens through {L} MoE layers",
+                   "layers": L, "tokens": N, "layer_us": ms_per_step * 1e3 / L,
+                   "layer_useful_GFLOP": layer_flops / 1e9, "ffn_call_us": ffn_us,
+                   "ffn_mfma_frac": layer_flops / (ffn_us * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS,
+                   "experts_active_per_layer": active, "prefill_set_accuracy": set_acc,
+                   "prediction_accuracy_topk_per_token": tok_acc,
+                   "cache_hit_rate": hits / max(1, hits + misses)},
+        "roofline": {"bound": "mfma", "kernel": "prefill_prep_kernel + grouped_gemm_kernel<2>", "achieved": achieved,
+                     "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_PEAK_TFLOPS,
+                     "traffic": None, "flops_per_launch": up_flops, "us_per_launch": up_us},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--layers", type=int, default=0, help="prefill workloads: use only the first LAYERS layers")
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=256)
-    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--steps", type=int, default=None, help="default 256 (decode) / 10 (prefill)")
+    ap.add_argument("--warmup", type=int, default=None, help="default 32 (decode) / 2 (prefill)")
     ap.add_argument("--workload", default="qwen_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
+    decode = args.workload == "qwen_decode"
+    if args.steps is None:
+        args.steps = 256 if decode else 10
+    if args.warmup is None:
+        args.warmup = 32 if decode else 2
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); the multi-GPU sharding is design-only.",
               file=sys.stderr)
@@ -257,9 +394,12 @@ def main():
         sys.exit(3)
     if args.workload == "qwen_decode":
         bench_decode(args)
-    else:
-        from paper_2502_12224_amd.bench_prefill import bench_prefill
+    elif args.workload in PREFILL_WORKLOADS:
         bench_prefill(args)
+    else:
+        print(f"bench.py: unknown workload {args.workload}; choose qwen_decode or one of "
+              f"{sorted(PREFILL_WORKLOADS)}", file=sys.stderr)
+        sys.exit(2)
 
 
 if __name__ == "__main__":

@@ -165,6 +165,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
     const int G = K / group, tiles_k = K / KT, nchunk = K / kKC;
     const int wrow0 = nblk * kBN + wave * 32;              // first weight row of this wave
     const bool wlive = wrow0 < Nout;
+    const int nmt = (min(kBM, T - row0) + 31) >> 5;        // 32-row tiles of this block that hold rows
     gu4p_t wt[NMAT];
     gu16p_t sc[NMAT];
     {
@@ -225,6 +226,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
         if (wlive) {
 #pragma unroll
             for (int mt = 0; mt < kBM / 32; ++mt) {
+                if (mt < nmt) {
 #pragma unroll
                 for (int tl = 0; tl < TPC; ++tl)
 #pragma unroll
@@ -236,6 +238,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
                             acc[i][mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, b[i][tl * SPT + d], acc[i][mt],
                                                                                 0, 0, 0);
                     }
+                }
             }
         }
     }
