@@ -293,11 +293,10 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
         return;
     }
     for (int r = threadIdx.x; r < kBM; r += 256) {
-        int ar = -1;
-        if (row0 + r < T) {
-            if (a.mode == 0) ar = is_shared ? row0 + r : a.perm[sbeg + row0 + r] / a.k;
-            else ar = is_shared ? (seg - a.E) * a.N + row0 + r : sbeg + row0 + r;
-        }
+        const int rr = row0 + r < T ? row0 + r : row0;
+        int ar;
+        if (a.mode == 0) ar = is_shared ? rr : a.perm[sbeg + rr] / a.k;
+        else ar = is_shared ? (seg - a.E) * a.N + rr : sbeg + rr;
         arow[r] = ar;
     }
     __syncthreads();
