@@ -117,3 +117,139 @@ class MoEStack:
             true_ids.append(torch.stack(t_s))
             pred_ids.append(torch.stack(p_s))
         return torch.stack(xs), torch.stack(true_ids), torch.stack(pred_ids)
+
+
+def _align(v, a=256):
+    return (v + a - 1) // a * a
+
+
+class OffloadedStack:
+    """Stack whose routed experts live in a pinned host pool; a device slot
+    pool holds the cached / staged ones.  Drives fate_expert_cache_step with
+    the built-in HIP copy engine (side stream) around the per-layer calls."""
+
+    def __init__(self, cfg: MoEShape, cache_total, n_max, staging_slots, device="cuda", layers=None,
+                 L_shallow=None):
+        self.cfg, self.device = cfg, device
+        self.nl = cfg.layers if layers is None else layers
+        L, E = self.nl, cfg.E
+        lib = B.lib()
+        self.lib = lib
+        # slot layout: the six arrays of one expert, 256-byte aligned
+        wb = cfg.I * cfg.H * cfg.bits // 8
+        sb = cfg.I * cfg.H // cfg.group * 2
+        off, offs = 0, {}
+        for name, nb in (("w1", wb), ("w3", wb), ("w2", wb), ("s1", sb), ("s3", sb), ("s2", sb)):
+            offs[name] = off
+            off = _align(off + nb)
+        self.slot_bytes = off
+        self.layout = B.fate_slot_layout(self.slot_bytes, offs["w1"], offs["w3"], offs["w2"], offs["s1"], offs["s3"],
+                                         offs["s2"], cfg.bits, cfg.group, cfg.I)
+        # dense parts stay on the device: gates, shared experts
+        self.gates, self.shared, self.shared_tables, self.shared_gates = [], [], [], []
+        self.host_pool = torch.empty(L * E, self.slot_bytes, dtype=torch.uint8).pin_memory()
+        stage = torch.zeros(self.slot_bytes, dtype=torch.uint8, device=device)
+        for l in range(L):
+            self.gates.append(gen_gate(cfg, l, device))
+            self.shared_gates.append(gen_shared_gate(cfg, l, device))
+            sh = [B.PackedExpert(gen_expert(cfg, l, s, shared=True, device=device), device) for s in range(cfg.n_shared)]
+            self.shared.append(sh)
+            self.shared_tables.append(B.expert_table([p.struct() for p in sh], device) if cfg.n_shared else None)
+            for e in range(E):
+                pe = B.PackedExpert(gen_expert(cfg, l, e, device=device), device)
+                for name in offs:
+                    t = pe.t[name].reshape(-1).view(torch.uint8)
+                    stage[offs[name]:offs[name] + t.numel()] = t
+                self.host_pool[l * E + e].copy_(stage)
+        torch.cuda.synchronize()
+        self.copy_stream = torch.cuda.Stream()
+        self.compute_stream = torch.cuda.current_stream()
+        caps = (C.c_int32 * L)()
+        Ls = cfg.L_shallow if L_shallow is None else L_shallow
+        lib.fate_cache_layer_capacities(L, E, cache_total, Ls, caps)
+        self.caps = list(caps)
+        self.total_slots = sum(self.caps) + staging_slots
+        self.slot_pool = torch.zeros(self.total_slots, self.slot_bytes, dtype=torch.uint8, device=device)
+        self.table = torch.zeros(L * E * C.sizeof(B.fate_qexpert), dtype=torch.uint8, device=device)
+        self.engine = lib.fate_hip_engine_create(L, E, self.total_slots, C.byref(self.layout),
+                                                 C.c_void_p(self.slot_pool.data_ptr()),
+                                                 C.c_void_p(self.host_pool.data_ptr()),
+                                                 C.c_void_p(self.table.data_ptr()),
+                                                 C.c_void_p(self.copy_stream.cuda_stream),
+                                                 C.c_void_p(self.compute_stream.cuda_stream))
+        if not self.engine:
+            raise B.FateError(6, lib.fate_last_error().decode())
+        self._copy_fn = B.COPY_FN(("fate_hip_engine_copy", lib))
+        self.cache = lib.fate_cache_create(L, E, cache_total, Ls, n_max, staging_slots, self._copy_fn,
+                                           C.c_void_p(self.engine))
+        assert lib.fate_cache_total_slots(self.cache) == self.total_slots
+        for l in range(L):
+            for e in range(E):
+                s = lib.fate_cache_slot_of(self.cache, l, e)
+                if s >= 0:
+                    B._check(lib.fate_hip_engine_preload(self.engine, l, e, s))
+        self.done_event = torch.cuda.Event()
+        self.have_done = False
+        self.stats = dict(hit_cache=0, hit_prefetch=0, miss=0, pair_hits=0, pair_misses=0, prefetch=0, wasted=0,
+                          evicted=0)
+        self.trace = []          # per step: (layer, compute_order, loads) for checks against the oracle
+        self.keep_trace = False
+        self._h_counts = torch.zeros(2, E, dtype=torch.int32).pin_memory()
+        self._order = (C.c_int32 * E)()
+        self._slots = (C.c_int32 * E)()
+        self._loads = (B.fate_cache_load * 512)()
+        self._st = B.fate_cache_stats()
+        self._nact = C.c_int32(0)
+
+    def table_for(self, l):
+        return self.table[l * self.cfg.E * C.sizeof(B.fate_qexpert):]
+
+    def layer(self, l, x, buf: LayerBuffers):
+        """Route, predict, permute, cache step (with copies), FFN for layer l."""
+        cfg, lib = self.cfg, self.lib
+        nxt = l + 1 < self.nl
+        Wg, bias = self.gates[l]
+        Wg2, bias2 = self.gates[l + 1] if nxt else (None, None)
+        if buf.fused_ok:
+            B.fate_route_fused(x, Wg, bias, Wg2, bias2, cfg.k, cfg.m, cfg.renorm, buf.ids, buf.w, buf.pred_ids,
+                               buf.pred_w, buf.pred_pop, buf.counts, buf.offsets, buf.perm, buf.inv_perm, buf.order,
+                               buf.route_ws)
+        else:
+            B.fate_gate_route(x, Wg, bias, cfg.k, cfg.renorm, buf.ids, buf.w, None)
+            if nxt:
+                B.fate_cross_layer_predict(x, Wg2, bias2, cfg.k, cfg.m, buf.pred_ids, buf.pred_w, buf.pred_pop)
+            B.fate_permute(buf.ids, cfg.E, buf.counts, buf.offsets, buf.perm, buf.inv_perm, buf.order)
+        # the host needs the routing result to check residency (the one device -> host hop per layer)
+        self._h_counts[0].copy_(buf.counts, non_blocking=True)
+        if nxt:
+            self._h_counts[1].copy_(buf.pred_pop, non_blocking=True)
+        torch.cuda.current_stream().synchronize()
+        B._check(lib.fate_hip_engine_begin_step(self.engine, C.c_void_p(self.done_event.cuda_event)
+                                                if self.have_done else None))
+        st = self._st
+        B._check(lib.fate_expert_cache_step_dense(self.cache, l, C.c_void_p(self._h_counts[0].data_ptr()),
+                                                  C.c_void_p(self._h_counts[1].data_ptr()) if nxt else None,
+                                                  self._order, self._slots, C.byref(self._nact), self._loads, 512,
+                                                  C.byref(st)))
+        n = self._nact.value
+        B._check(lib.fate_hip_engine_wait_ready(self.engine, self._slots, n))
+        s = self.stats
+        s["hit_cache"] += st.n_hit_cache; s["hit_prefetch"] += st.n_hit_prefetch; s["miss"] += st.n_miss
+        s["pair_hits"] += st.pair_hits; s["pair_misses"] += st.pair_misses; s["prefetch"] += st.n_prefetch_issued
+        s["wasted"] += st.n_wasted; s["evicted"] += st.n_evicted
+        if self.keep_trace:
+            self.trace.append((l, list(self._order[:n]), [(ld.layer, ld.expert, ld.slot, bool(ld.demand))
+                                                          for ld in self._loads[:min(st.n_loads, 512)]]))
+        B.fate_moe_ffn_q(buf.desc, x, self.table_for(l), buf.counts, buf.offsets, buf.perm, buf.inv_perm, buf.order,
+                         buf.w, self.shared_tables[l], self.shared_gates[l], buf.y, buf.ffn_ws)
+        self.done_event.record()
+        self.have_done = True
+        return buf.y
+
+    def bytes_copied(self):
+        return self.lib.fate_hip_engine_bytes_copied(self.engine)
+
+    def close(self):
+        torch.cuda.synchronize()
+        self.lib.fate_cache_destroy(self.cache)
+        self.lib.fate_hip_engine_destroy(self.engine)
