@@ -10,6 +10,10 @@ Workloads (all synthetic, seeded):
                          quantised expert FFN, and the cache step.
   qwen_prefill512 / qwen_prefill2048 / deepseek_prefill1024 / mixtral_prefill2048
                          one prefill pass of N tokens through the stack's layers.
+  deepseek_offload / mixtral_offload
+                         experts in pinned host memory, a fraction cached on the
+                         device: one prefill pass, then decode steps with the cache
+                         step issuing H2D copies on a side stream.
 Prints one JSON line (see the design doc for the fields).
 """
 import argparse
@@ -370,6 +374,121 @@ def bench_prefill(args):
     print(json.dumps(out), flush=True)
 
 
+OFFLOAD_WORKLOADS = {
+    # name: (shape, prefill tokens, decode batch, decode steps, description)
+    "deepseek_offload": ("deepseek", 1024, 8, 64,
+                         "configs[3]: DeepSeek-MoE-16B-shaped, routed experts in pinned host memory, 30% of them "
+                         "cached on the device (3 shallow layers full); prefill 1024 tokens, then decode batch 8"),
+    "mixtral_offload": ("mixtral", 2048, 1, 128,
+                        "configs[4]: Mixtral-8x7B-shaped, experts in pinned host memory, 25% cached on the device; "
+                        "prefill 2048 tokens, then decode batch 1"),
+}
+
+
+def h2d_peak_gbs(dev):
+    """Pinned host -> device copy rate of this machine (256 MiB, best of 5)."""
+    import torch
+    src = torch.empty(256 << 20, dtype=torch.uint8, pin_memory=True)
+    dst = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    best = 0.0
+    for _ in range(5):
+        e0.record(); dst.copy_(src, non_blocking=True); e1.record(); torch.cuda.synchronize()
+        best = max(best, src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    return best
+
+
+def bench_offload(args):
+    """Offloaded stack: one step = one decode step of the batch through every
+    layer (route, predict, permute, cache step with H2D copies on the side
+    stream, FFN).  The prefill pass that fills the cache is timed separately and
+    reported in config."""
+    import torch
+    import paper_2502_12224_amd.binding as B
+    from paper_2502_12224_amd.stack import LayerBuffers, OffloadedStack
+    from workloads import SHAPES, chain_next_hidden, gen_hidden, unit_rmsnorm_bf16
+
+    shape, Np, Nd, S, desc = OFFLOAD_WORKLOADS[args.workload]
+    cfg = SHAPES[shape]
+    dev = "cuda"
+    L = args.layers or cfg.layers
+    E, H = cfg.E, cfg.H
+    steps = args.steps
+    cache_total = int(cfg.cache_frac * L * E)
+    lib = B.lib()
+    ebytes = expert_bytes(H, cfg.I, cfg.bits, cfg.group)
+    peak = h2d_peak_gbs(dev)
+    t_expert = ebytes / (peak * 1e9)
+    n_max = args.n_max if args.n_max is not None else min(E, Nd * cfg.m)
+    t0 = time.time()
+    log(f"[bench] {args.workload}: {L} layers x {E} experts of {ebytes / 1e6:.2f} MB -> pinned host pool "
+        f"{L * E * ebytes / 1e9:.1f} GB; cache_total {cache_total}, n_max {n_max}, H2D peak {peak:.1f} GB/s")
+    st = OffloadedStack(cfg, cache_total, n_max, staging_slots=2 * E + n_max, device=dev, layers=L,
+                        progress=lambda l: log(f"[bench]   layer {l} in the host pool ({time.time() - t0:.0f}s)"))
+    log(f"[bench] per-layer capacities {st.caps}")
+
+    def run(N, nsteps, first_step, buf):
+        for s in range(nsteps):
+            h = gen_hidden(cfg, N, step=first_step + s, device=dev).to(torch.float32)
+            for l in range(L):
+                x = unit_rmsnorm_bf16(h)
+                y = st.layer(l, x, buf)
+                h = chain_next_hidden(h, y)
+
+    def snapshot():
+        d = dict(st.stats)
+        d["bytes"] = st.bytes_copied()
+        return d
+
+    def phase(N, nsteps, first_step, buf):
+        torch.cuda.synchronize()
+        a = snapshot()
+        t = time.perf_counter()
+        run(N, nsteps, first_step, buf)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t
+        b = snapshot()
+        d = {k: b[k] - a[k] for k in a}
+        hits = d["hit_cache"] + d["hit_prefetch"]
+        return dict(seconds=el, tokens_per_s=N * nsteps / el, hit_rate=hits / max(1, hits + d["miss"]),
+                    hit_rate_cache_only=d["hit_cache"] / max(1, hits + d["miss"]),
+                    pair_hit_rate=d["pair_hits"] / max(1, d["pair_hits"] + d["pair_misses"]),
+                    h2d_GB=d["bytes"] / 1e9, h2d_GBs=d["bytes"] / el / 1e9, prefetch_issued=d["prefetch"],
+                    prefetch_wasted=d["wasted"], demand_loads=d["miss"])
+
+    pbuf = LayerBuffers(cfg, Np, dev)
+    dbuf = LayerBuffers(cfg, Nd, dev)
+    run(Nd, 1, 10_000, dbuf)                 # warm the kernels and the copy path
+    B._check(lib.fate_cache_set_n_max(st.cache, E))      # prefill: every predicted expert, most popular first
+    pre = phase(Np, 1, 20_000, pbuf)
+    B._check(lib.fate_cache_set_n_max(st.cache, n_max))
+    log(f"[bench] prefill {Np} tokens: {pre['seconds'] * 1e3:.1f} ms, {pre['tokens_per_s']:.0f} tok/s, "
+        f"hit rate {pre['hit_rate']:.3f}, H2D {pre['h2d_GB']:.2f} GB at {pre['h2d_GBs']:.1f} GB/s")
+    run(Nd, args.warmup, 0, dbuf)
+    dec = phase(Nd, steps, args.warmup, dbuf)
+    log(f"[bench] decode batch {Nd} x {steps} steps: {dec['tokens_per_s']:.1f} tok/s, hit rate {dec['hit_rate']:.3f} "
+        f"(cache only {dec['hit_rate_cache_only']:.3f}), H2D {dec['h2d_GB']:.2f} GB at {dec['h2d_GBs']:.1f} GB/s")
+    layer_s = dec["seconds"] / (steps * L)
+    n_cal = lib.fate_n_max_from_times(layer_s, 0.0, 0.0, t_expert)
+    out = {
+        "metric": "MoE-layer tokens/s (decode b=1, prefill 512) + % HBM / MFMA roofline",
+        "value": dec["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": dec["seconds"] * 1e3 / steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int4/int8 weights, bf16/fp16 activations, fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": desc, "step": f"one decode step of batch {Nd} through {L} MoE layers, experts offloaded",
+                   "layers": L, "batch": Nd, "cache_total": cache_total, "layer_capacities": st.caps,
+                   "n_max": n_max, "n_max_from_measured_times": n_cal, "t_expert_us": t_expert * 1e6,
+                   "decode": dec, "prefill": dict(tokens=Np, **pre)},
+        "roofline": {"bound": "pcie", "kernel": "side-stream H2D copies of missed / prefetched experts",
+                     "achieved": dec["h2d_GBs"], "peak": peak, "unit": "GB/s", "frac": dec["h2d_GBs"] / peak,
+                     "traffic": None, "peak_source": "256 MiB pinned copy measured in this run"},
+        "cpu_baseline": None,
+    }
+    st.close()
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--layers", type=int, default=0, help="prefill workloads: use only the first LAYERS layers")
@@ -378,10 +497,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=None, help="default 32 (decode) / 2 (prefill)")
     ap.add_argument("--workload", default="qwen_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--n-max", type=int, default=None,
+                    help="offload workloads: cap on prefetched experts per layer (default: batch * m, at most E)")
     args = ap.parse_args()
     decode = args.workload == "qwen_decode"
     if args.steps is None:
-        args.steps = 256 if decode else 10
+        args.steps = 256 if decode else OFFLOAD_WORKLOADS[args.workload][3] if args.workload in OFFLOAD_WORKLOADS else 10
     if args.warmup is None:
         args.warmup = 32 if decode else 2
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -396,9 +517,11 @@ def main():
         bench_decode(args)
     elif args.workload in PREFILL_WORKLOADS:
         bench_prefill(args)
+    elif args.workload in OFFLOAD_WORKLOADS:
+        bench_offload(args)
     else:
         print(f"bench.py: unknown workload {args.workload}; choose qwen_decode or one of "
-              f"{sorted(PREFILL_WORKLOADS)}", file=sys.stderr)
+              f"{sorted(PREFILL_WORKLOADS) + sorted(OFFLOAD_WORKLOADS)}", file=sys.stderr)
         sys.exit(2)
 
 

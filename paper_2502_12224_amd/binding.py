@@ -21,7 +21,7 @@ EXPORTS = [
     "fate_last_error", "fate_version", "fate_gate_route", "fate_cross_layer_predict", "fate_permute",
     "fate_route_fused_workspace", "fate_route_fused", "fate_pack_weight", "fate_moe_ffn_q_workspace",
     "fate_moe_ffn_q", "fate_cache_total_from_budget", "fate_n_max_from_times", "fate_cache_layer_capacities",
-    "fate_cache_create", "fate_cache_destroy", "fate_cache_total_slots", "fate_cache_slot_of",
+    "fate_cache_create", "fate_cache_destroy", "fate_cache_total_slots", "fate_cache_set_n_max", "fate_cache_slot_of",
     "fate_cache_resident", "fate_expert_cache_step", "fate_expert_cache_step_dense",
     "fate_expert_cache_step_layers", "fate_hip_engine_create", "fate_hip_engine_destroy",
     "fate_hip_engine_copy", "fate_hip_engine_begin_step", "fate_hip_engine_wait_ready",
@@ -84,6 +84,7 @@ def lib():
         L.fate_cache_destroy.argtypes = [C.c_void_p]
         L.fate_cache_destroy.restype = None
         L.fate_cache_total_slots.argtypes = [C.c_void_p]
+        L.fate_cache_set_n_max.argtypes = [C.c_void_p, C.c_int]
         L.fate_cache_slot_of.argtypes = [C.c_void_p, C.c_int, C.c_int]
         L.fate_cache_resident.argtypes = [C.c_void_p, C.c_int, C.c_int]
         L.fate_cache_total_from_budget.restype = C.c_int64

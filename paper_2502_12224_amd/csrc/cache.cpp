@@ -212,6 +212,14 @@ extern "C" fate_cache* fate_cache_create(int num_layers, int E, int cache_total,
 
 extern "C" void fate_cache_destroy(fate_cache* c) { delete c; }
 extern "C" int32_t fate_cache_total_slots(const fate_cache* c) { return c ? c->total_slots : -1; }
+extern "C" fate_status fate_cache_set_n_max(fate_cache* c, int n_max) {
+    if (!c || n_max < 0) {
+        fate::set_error("fate_cache_set_n_max: cache %p, n_max %d", (void*)c, n_max);
+        return FATE_EINVAL;
+    }
+    c->n_max = n_max;
+    return FATE_OK;
+}
 extern "C" int32_t fate_cache_slot_of(const fate_cache* c, int layer, int expert) {
     if (!c || layer < 0 || layer >= c->num_layers || expert < 0 || expert >= c->E) return -1;
     return c->slot[layer][expert];

@@ -129,7 +129,7 @@ class OffloadedStack:
     the built-in HIP copy engine (side stream) around the per-layer calls."""
 
     def __init__(self, cfg: MoEShape, cache_total, n_max, staging_slots, device="cuda", layers=None,
-                 L_shallow=None):
+                 L_shallow=None, progress=None):
         self.cfg, self.device = cfg, device
         self.nl = cfg.layers if layers is None else layers
         L, E = self.nl, cfg.E
@@ -147,7 +147,7 @@ class OffloadedStack:
                                          offs["s2"], cfg.bits, cfg.group, cfg.I)
         # dense parts stay on the device: gates, shared experts
         self.gates, self.shared, self.shared_tables, self.shared_gates = [], [], [], []
-        self.host_pool = torch.empty(L * E, self.slot_bytes, dtype=torch.uint8).pin_memory()
+        self.host_pool = torch.empty(L * E, self.slot_bytes, dtype=torch.uint8, pin_memory=True)
         stage = torch.zeros(self.slot_bytes, dtype=torch.uint8, device=device)
         for l in range(L):
             self.gates.append(gen_gate(cfg, l, device))
@@ -161,6 +161,8 @@ class OffloadedStack:
                     t = pe.t[name].reshape(-1).view(torch.uint8)
                     stage[offs[name]:offs[name] + t.numel()] = t
                 self.host_pool[l * E + e].copy_(stage)
+            if progress:
+                progress(l)
         torch.cuda.synchronize()
         self.copy_stream = torch.cuda.Stream()
         self.compute_stream = torch.cuda.current_stream()

@@ -168,6 +168,26 @@ def test_cpp_cache_matches_oracle_on_random_traces(seed):
     cc.close()
 
 
+def test_cache_set_n_max_changes_the_prefetch_cap():
+    # section 4.2: the cap n is re-derived per phase; the C++ cache follows the oracle after a change
+    nl, E = 3, 16
+    ref = OC.CacheOracle(nl, E, 6, 0, 0, 2 * E)
+    cc = _Cache(nl, E, 6, 0, 0, 2 * E)
+    assert B.lib().fate_cache_set_n_max(cc.h, -1) == 1
+    for n_max in (0, 3, 16, 1):
+        ref.n_max = n_max
+        assert B.lib().fate_cache_set_n_max(cc.h, n_max) == 0
+        for l in range(nl):
+            ids, counts = [1, 5, 9], [2, 1, 1]
+            pids, ppop = list(range(4, 12)), [8, 7, 6, 5, 4, 3, 2, 1]
+            r = ref.step(l, ids, counts, pids, ppop)
+            rc, order, slots, loads, st = cc.step(l, ids, counts, pids, ppop)
+            assert rc == 0 and loads == r.loads and order == r.compute_order
+            if l + 1 < nl:
+                assert st.n_prefetch_issued <= n_max
+    cc.close()
+
+
 def test_cache_error_paths():
     # a failing copy is reported and the expert is not marked resident
     cc = _Cache(2, 8, 0, 0, 2, 8, fail_at=1)
