@@ -140,10 +140,17 @@ def test_ffn_mfma_bf16_output():
     assert ffn_rel_err(y, y_ref).max() <= 2 ** -8 + TOL
 
 
-def test_ffn_mfma_full_size_sampled_rows():
-    """Qwen-shaped prefill at N = 2048 (Zipf-skewed routing), oracle on sampled token rows."""
-    rows = [0, 511, 1024, 2047]
-    y, y_ref, counts = _mfma_case("qwen_prefill", 2048, rows)
+@pytest.mark.parametrize("name,N,rows", [
+    ("qwen_prefill", 2048, [0, 511, 1024, 2047]),     # Zipf-skewed routing
+    ("qwen_prefill", 512, [3, 256, 511]),
+    ("deepseek", 1024, [0, 500, 1023]),               # two int8 shared experts beside the int4 routed ones
+    ("mixtral", 2048, [5, 2047]),                     # 90.8 MB experts, I = 14336
+])
+def test_ffn_mfma_full_size_sampled_rows(name, N, rows):
+    """The prefill sizes the bench times, in its launch configuration (auto
+    mode picks the MFMA path); oracle on sampled token rows."""
+    cfg = SHAPES[name]
+    y, y_ref, counts = _mfma_case(name, N, rows)
     err = ffn_rel_err(y, y_ref)
-    print(f"N=2048: max row err {err.max():.2e}; expert rows min/max {counts.min()}/{counts.max()}")
-    assert counts.sum() == 2048 * 4 and err.max() <= TOL, err
+    print(f"{name} N={N}: max row err {err.max():.2e}; expert rows min/max {counts.min()}/{counts.max()}")
+    assert counts.sum() == N * cfg.k and err.max() <= TOL, err

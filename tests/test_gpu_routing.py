@@ -13,7 +13,7 @@ from helpers import DEV, bias_np, check_routing, f32, gpu_permute, gpu_predict, 
 pytestmark = pytest.mark.gpu
 
 CASES = [("tiny", 16), ("qwen", 1), ("qwen", 5), ("qwen", 77), ("qwen_prefill", 512), ("qwen_prefill", 2048),
-         ("deepseek", 8), ("deepseek", 1024), ("mixtral", 1), ("mixtral", 3), ("mixtral", 300)]
+         ("deepseek", 8), ("deepseek", 1024), ("mixtral", 1), ("mixtral", 3), ("mixtral", 300), ("mixtral", 2048)]
 
 
 @pytest.mark.parametrize("name,N", CASES)
