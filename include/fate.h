@@ -185,6 +185,38 @@ fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, const void* x_b
                            void* y, void* workspace, size_t workspace_bytes);
 
 /* ------------------------------------------------------------------------
+ * Whole decode-side MoE layer in one launch (1 <= N <= 8, N*k <= 64):
+ * fate_gate_route + fate_cross_layer_predict + fate_permute +
+ * fate_moe_ffn_q (section 4.1 steps 1-2, 5-6 of one layer), with the same
+ * results as those calls: routing outputs bit for bit, y up to the order of
+ * its fp32 additions.  The weight stream of the shared experts starts while
+ * the gate is still being evaluated, and that of the down projections
+ * before the up projections have finished.
+ *   out: device pointers for every routing output, sized as in the separate
+ *        calls; pred_* may be NULL when Wg_next is NULL (last layer).
+ *   d->mode must be 0 or 1, d->phases 0.
+ *   workspace: fate_moe_layer_decode_workspace bytes, 256-byte aligned,
+ *        zero-filled once by the caller before the first use (each call
+ *        leaves its counters at zero).  Calls that share a workspace must be
+ *        ordered on one stream.  The int32 at byte *status_offset of the
+ *        workspace is the status word: bit 0 = an activated expert had NULL
+ *        weights, bit 1 = a wait inside the kernel ran out (results invalid).
+ * ---------------------------------------------------------------------- */
+typedef struct {
+    int32_t* topk_ids; float* topk_w;
+    int32_t* pred_ids; float* pred_w; int32_t* pred_pop;
+    int32_t* counts; int32_t* offsets; int32_t* perm; int32_t* inv_perm; int32_t* expert_order;
+} fate_route_out;
+
+fate_status fate_moe_layer_decode_workspace(const fate_ffn_desc* d, size_t* bytes, size_t* status_offset);
+fate_status fate_moe_layer_decode(void* stream, const fate_ffn_desc* d, const void* x_bf16,
+                                  const void* Wg_bf16, const float* bias,
+                                  const void* Wg_next_bf16, const float* bias_next, int m, int renorm,
+                                  const fate_route_out* out,
+                                  const fate_qexpert* experts_dev, const fate_qexpert* shared_dev,
+                                  const void* shared_gate_bf16, void* y, void* workspace, size_t workspace_bytes);
+
+/* ------------------------------------------------------------------------
  * Expert cache (paper section 4.4: memory budget -> cache_total; boundary L;
  * shallow layers cached fully, the rest split evenly over deep layers; ARC
  * per layer.  Section 4.1 steps 3-4, 7-8: residency check, transfer of

@@ -59,6 +59,31 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
 // Wave-wide all-reduce on the data-parallel-primitive (DPP) path: four
 // exchange steps inside each row of 16 lanes (no LDS crossbar), then the four
 // row results are combined through scalar lane reads.  Result is uniform.
+// ---- data handed between workgroups of one launch ---------------------------
+// Relaxed atomics at device scope: the accesses go past the per-XCD L2 to the
+// point where all compute dies agree, so no cache-wide write-back or
+// invalidate is needed around them.  Ordering comes from the producer waiting
+// for its stores (a workgroup barrier does that) before it bumps a counter,
+// and from the consumer reading the counter before the data.
+__device__ __forceinline__ void st_dev(int32_t* p, int32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(uint32_t* p, uint32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int32_t ld_dev(const int32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long ld_dev(const unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));

@@ -1,0 +1,170 @@
+// Device code shared by the decode-side FFN kernels: a register ring of
+// weight tiles per wave and the matrix-core inner loop that consumes it.
+//
+// The multiply-adds run on the matrix cores although only 1..8 of the 32
+// token columns of a 32x32x16 product are in use: widening the codes already
+// takes most of the vector-ALU issue slots a wave has per byte streamed, and
+// the matrix pipe runs beside it.  Operands: A = activations (fp16, a lane's
+// row is a token, rows past the last token read a zero row in LDS), B = the
+// lane's own 8 codes widened to fp16 integers (exact), so D[token][row] lands
+// in the lane that owns the row's scale.  One accumulator per quantisation
+// group, started from zero; the group's fp16 scale multiplies the fp32 group
+// sum, so each weight enters exactly.
+#pragma once
+#include <hip/hip_fp16.h>
+#include "common.h"
+#include "qformat.h"
+
+namespace fate {
+
+constexpr int kTokPass = 8;    // tokens per pass over an expert's weights
+constexpr int kLdsPad = 8;     // halves of padding per LDS activation row (bank spread)
+
+// pointers into expert weights come out of a table in memory; telling the
+// compiler they are global (not generic) pointers gives global_load, not flat_load
+#if defined(__HIP_DEVICE_COMPILE__)
+#define FATE_GLOBAL __attribute__((address_space(1)))
+#else
+#define FATE_GLOBAL
+#endif
+typedef const FATE_GLOBAL uint4* gu4_t;
+typedef const FATE_GLOBAL uint16_t* gu16_t;
+template <class T>
+__device__ __forceinline__ const FATE_GLOBAL T* as_global(const void* p) {
+    return (const FATE_GLOBAL T*)(uintptr_t)p;
+}
+__device__ __forceinline__ float half_bits_to_float(uint32_t b) {
+    return __half2float(__ushort_as_half((unsigned short)b));
+}
+
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+__device__ __forceinline__ f32x16_t f32x16_zero() {
+    return f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+}
+
+// bf16 x 8 -> fp16 x 8 (round to nearest even)
+__device__ __forceinline__ uint4 bf16x8_to_f16x8(const uint4& v) {
+    const uint32_t r[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const __half lo = __float2half_rn(bf16_lo(r[i]));
+        const __half hi = __float2half_rn(bf16_hi(r[i]));
+        o[i] = (uint32_t)__half_as_ushort(lo) | ((uint32_t)__half_as_ushort(hi) << 16);
+    }
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+template <int NMAT, int D, int TPG>
+struct TileRing {
+    uint4 raw[NMAT][D];
+    uint32_t sc[NMAT][D / TPG];   // fp16 bits of the group scale, one full register each
+};
+
+// request the first D tiles of the groups [g_beg, g_end) (TPG tiles per group)
+template <int NMAT, int D, int TPG>
+__device__ __forceinline__ void ring_start(TileRing<NMAT, D, TPG>& r, const gu4_t* wt, const gu16_t* sc,
+                                           int g_beg, int g_end) {
+    const int tbeg = g_beg * TPG, tend = g_end * TPG;
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+        if (tbeg + j < tend) {
+#pragma unroll
+            for (int i = 0; i < NMAT; ++i) {
+                r.raw[i][j] = wt[i][(size_t)(tbeg + j) * 64];
+                if (j % TPG == 0) r.sc[i][j / TPG] = sc[i][g_beg + j / TPG];
+            }
+        }
+    }
+}
+
+// One wave accumulates, for the (up to 8) activation rows staged in LDS, the
+// products with NMAT weight row-blocks over the groups [g_beg, g_end);
+// ring_start must have been called with the same range.  xa: this lane's
+// activation row in LDS (fp16), already offset by its half of a tile; its
+// column 0 is absolute column k_base.  out[i][j]: row n of matrix i, token
+// 4*half + j.
+template <int BITS, int TPG, int NMAT, int D>
+__device__ __forceinline__ void ring_run(TileRing<NMAT, D, TPG>& r, const gu4_t* wt, const gu16_t* sc,
+                                         int g_beg, int g_end, const _Float16* xa, int k_base,
+                                         float (&out)[NMAT][4]) {
+    constexpr int KT = QFmt<BITS>::KT, S = QFmt<BITS>::MSTEPS;
+    static_assert(D % TPG == 0, "ring depth must hold whole groups");
+    const int tbeg = g_beg * TPG, tend = g_end * TPG;
+    const f32x16_t zero = f32x16_zero();
+    for (int base = tbeg; base < tend; base += D) {
+#pragma unroll
+        for (int jg = 0; jg < D / TPG; ++jg) {
+            if (base + jg * TPG < tend) {
+                f32x16_t acc[NMAT];
+                float s[NMAT];
+#pragma unroll
+                for (int i = 0; i < NMAT; ++i) s[i] = half_bits_to_float(r.sc[i][jg]);
+                const int gnext = base / TPG + jg + D / TPG;
+                if (gnext < g_end) {
+#pragma unroll
+                    for (int i = 0; i < NMAT; ++i) r.sc[i][jg] = sc[i][gnext];
+                }
+#pragma unroll
+                for (int tl = 0; tl < TPG; ++tl) {
+                    const int j = jg * TPG + tl;
+                    const int tile = base + j;
+                    const _Float16* xt = xa + (tile * KT - k_base);
+                    f16x8_t av[S];
+#pragma unroll
+                    for (int st = 0; st < S; ++st) av[st] = *reinterpret_cast<const f16x8_t*>(xt + 8 * st);
+#pragma unroll
+                    for (int i = 0; i < NMAT; ++i) {
+                        f16x8_t b[S];
+                        codes_to_f16<BITS>(r.raw[i][j], b);
+                        if (tile + D < tend) r.raw[i][j] = wt[i][(size_t)(tile + D) * 64];
+#pragma unroll
+                        for (int st = 0; st < S; ++st)
+                            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                                av[st], b[st], (tl == 0 && st == 0) ? zero : acc[i], 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < NMAT; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) out[i][j] = fmaf(s[i], acc[i][j], out[i][j]);
+            }
+        }
+    }
+}
+
+// The register ring's type depends on the tiles per group; the format of an
+// expert is only known at run time, so the kernels branch once to the matching
+// instantiation.  tpg in {1, 2, 4} for int4, {2, 4} for int8 (checked on the host).
+#define FATE_FORMAT_SWITCH(bits, tpg, BODY)                \
+    if ((bits) == 4) {                                     \
+        if ((tpg) == 2) { BODY(4, 2) }                     \
+        else if ((tpg) == 1) { BODY(4, 1) }                \
+        else { BODY(4, 4) }                                \
+    } else {                                               \
+        if ((tpg) == 4) { BODY(8, 4) }                     \
+        else { BODY(8, 2) }                                \
+    }
+
+static inline bool decode_group_ok(int bits, int group) {
+    const int tpg = group / (bits == 4 ? 64 : 32);
+    return bits == 4 ? (tpg == 1 || tpg == 2 || tpg == 4) : (tpg == 2 || tpg == 4);
+}
+
+// sigmoid(x . g) for one token row (bf16 inputs), one wave
+__device__ __forceinline__ float wave_sigmoid_dot_bf16(const uint4* xr, const uint4* gv, int nvec) {
+    const int lane = threadIdx.x & 63;
+    float acc = 0.f;
+    for (int c = lane; c < nvec; c += 64) {
+        const uint4 xv = xr[c], g = gv[c];
+        acc = fmaf(bf16_lo(xv.x), bf16_lo(g.x), acc); acc = fmaf(bf16_hi(xv.x), bf16_hi(g.x), acc);
+        acc = fmaf(bf16_lo(xv.y), bf16_lo(g.y), acc); acc = fmaf(bf16_hi(xv.y), bf16_hi(g.y), acc);
+        acc = fmaf(bf16_lo(xv.z), bf16_lo(g.z), acc); acc = fmaf(bf16_hi(xv.z), bf16_hi(g.z), acc);
+        acc = fmaf(bf16_lo(xv.w), bf16_lo(g.w), acc); acc = fmaf(bf16_hi(xv.w), bf16_hi(g.w), acc);
+    }
+    acc = wave_sum(acc);
+    return 1.0f / (1.0f + expf(-acc));
+}
+
+}  // namespace fate

@@ -1,6 +1,7 @@
 // fate_moe_ffn_q: argument checks, workspace carving, dispatch.
 #include "common.h"
 #include "ffn_internal.h"
+#include "layer_decode.h"
 
 namespace fate {
 
@@ -104,4 +105,63 @@ extern "C" fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, cons
     const int mode = d->mode ? d->mode : (d->N <= 16 ? 1 : 2);
     if (mode == 1) return launch_ffn_decode(st, *d, a, y);
     return launch_ffn_mfma(st, *d, a, w.ms, y);
+}
+
+extern "C" fate_status fate_moe_layer_decode_workspace(const fate_ffn_desc* d, size_t* bytes,
+                                                       size_t* status_offset) {
+    fate_status s = check_desc(d);
+    if (s != FATE_OK) return s;
+    if (bytes == nullptr) FATE_FAIL(FATE_EINVAL, "bytes is NULL");
+    const LayerWorkspace w = layer_workspace(d->N, d->H, d->E, d->y_is_fp32 != 0);
+    *bytes = w.bytes;
+    if (status_offset) *status_offset = w.status;
+    return FATE_OK;
+}
+
+extern "C" fate_status fate_moe_layer_decode(void* stream, const fate_ffn_desc* d, const void* x_bf16,
+                                             const void* Wg_bf16, const float* bias, const void* Wg_next_bf16,
+                                             const float* bias_next, int m, int renorm, const fate_route_out* out,
+                                             const fate_qexpert* experts_dev, const fate_qexpert* shared_dev,
+                                             const void* shared_gate_bf16, void* y, void* workspace,
+                                             size_t workspace_bytes) {
+    fate_status s = check_desc(d);
+    if (s != FATE_OK) return s;
+    if (d->mode == 2) FATE_FAIL(FATE_EINVAL, "the fused layer call has no MFMA-GEMM mode");
+    if (d->phases != 0) FATE_FAIL(FATE_EINVAL, "the fused layer call runs all phases");
+    if (d->N < 1) FATE_FAIL(FATE_ESHAPE, "fused layer: N = %d < 1", d->N);
+    if (m < d->k || m > d->E || m > kMaxM) FATE_FAIL(FATE_EINVAL, "need k <= m <= min(E, %d) (m = %d)", kMaxM, m);
+    FATE_CHECK_PTR(x_bf16);
+    FATE_CHECK_PTR(Wg_bf16);
+    FATE_CHECK_PTR_OPT(bias);
+    FATE_CHECK_PTR_OPT(Wg_next_bf16);
+    FATE_CHECK_PTR_OPT(bias_next);
+    FATE_CHECK_PTR(y);
+    FATE_CHECK_PTR_OPT(shared_gate_bf16);
+    if (out == nullptr || !out->topk_ids || !out->topk_w || !out->counts || !out->offsets || !out->perm ||
+        !out->inv_perm || !out->expert_order)
+        FATE_FAIL(FATE_EINVAL, "routing outputs must not be NULL");
+    if (Wg_next_bf16 && (!out->pred_ids || !out->pred_w || !out->pred_pop))
+        FATE_FAIL(FATE_EINVAL, "prediction outputs must not be NULL when the next gate is given");
+    if (!experts_dev) FATE_FAIL(FATE_EINVAL, "experts_dev is NULL");
+    if (d->n_shared && !shared_dev) FATE_FAIL(FATE_EINVAL, "shared_dev is NULL with n_shared = %d", d->n_shared);
+    const LayerWorkspace w = layer_workspace(d->N, d->H, d->E, d->y_is_fp32 != 0);
+    if (workspace == nullptr || workspace_bytes < w.bytes)
+        FATE_FAIL(FATE_EWORKSPACE, "workspace of %zu bytes needed, %zu given", w.bytes, workspace_bytes);
+    FATE_CHECK_PTR(workspace);
+    char* base = static_cast<char*>(workspace);
+
+    LayerArgs a{};
+    a.r = FusedRouteArgs{static_cast<const uint16_t*>(x_bf16), static_cast<const uint16_t*>(Wg_bf16), bias,
+                         static_cast<const uint16_t*>(Wg_next_bf16), bias_next, d->N, d->H, d->E, d->k, m,
+                         renorm != 0, out->topk_ids, out->topk_w, out->pred_ids, out->pred_w, out->pred_pop,
+                         out->counts, out->offsets, out->perm, out->inv_perm, out->expert_order, nullptr};
+    a.zq = reinterpret_cast<unsigned long long*>(base + w.zq);
+    a.experts = experts_dev; a.shared = shared_dev; a.n_shared = d->n_shared;
+    a.shared_gate = static_cast<const uint16_t*>(shared_gate_bf16);
+    a.bits_r = d->bits; a.group_r = d->group;
+    a.bits_s = d->n_shared ? d->shared_bits : d->bits; a.group_s = d->n_shared ? d->shared_group : d->group;
+    a.y = d->y_is_fp32 ? static_cast<float*>(y) : reinterpret_cast<float*>(base + w.ybuf);
+    a.status = reinterpret_cast<int32_t*>(base + w.status);
+    a.sync = reinterpret_cast<int32_t*>(base + w.sync);
+    return launch_layer_decode(static_cast<hipStream_t>(stream), *d, a, y);
 }

@@ -26,6 +26,7 @@ struct DecodeArgs {
     float* y;                 // [N,H] fp32 accumulator
     int32_t* status;
     int nchunk_r, nchunk_s, cg_r, cg_s;   // reduction chunks of the down kernel
+    int lds_rows;        // activation rows staged in LDS per pass, plus one zero row
 };
 
 struct MfmaScratch {

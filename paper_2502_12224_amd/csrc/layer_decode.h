@@ -1,0 +1,50 @@
+// Whole decode-side MoE layer in one launch: arguments and workspace layout
+// shared between the entry point and the kernel's translation unit.
+#pragma once
+#include "common.h"
+#include "route_device.h"
+
+namespace fate {
+
+constexpr int kLayerWaves = 8;                  // waves per workgroup
+constexpr int kLayerThreads = 64 * kLayerWaves;
+constexpr int kLayerNeurons = 64;               // intermediate neurons per work block
+constexpr int kLayerMaxN = 8;                   // tokens per call
+constexpr int kLayerMaxP = 64;                  // (token, expert) pairs per call
+
+struct LayerArgs {
+    FusedRouteArgs r;              // x, gates, sizes, routing outputs (its zbuf is not used)
+    unsigned long long* zq;        // [2][N][E] logits, each tagged with the call's epoch in the high word
+    const fate_qexpert* experts;
+    const fate_qexpert* shared;
+    const uint16_t* shared_gate;
+    int n_shared, bits_r, group_r, bits_s, group_s;
+    int nb_route;                  // routing workgroups (block ids [0, nb_route))
+    int nb_zero;                   // the first nb_zero of them clear y (those whose logits every consumer awaits)
+    int nkb_r, nkb_s;              // 64-neuron blocks per routed / shared expert
+    int nact;                      // routed expert slots: min(E, N*k)
+    float* y;                      // [N,H] fp32, accumulated with atomics
+    int32_t* status;
+    int32_t* sync;                 // [0] epoch of the previous call, [1] workgroups that have left
+};
+
+// byte offsets inside the workspace of fate_moe_layer_decode
+struct LayerWorkspace {
+    size_t sync, zq, status, ybuf, bytes;
+};
+
+inline LayerWorkspace layer_workspace(int N, int H, int E, bool y_is_fp32) {
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    LayerWorkspace w;
+    size_t off = 0;
+    w.sync = off; off += 256;
+    w.zq = off; off += up((size_t)2 * N * E * sizeof(unsigned long long));
+    w.status = off; off += 256;
+    w.ybuf = off; off += y_is_fp32 ? 0 : up((size_t)N * H * sizeof(float));
+    w.bytes = off;
+    return w;
+}
+
+fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArgs a, void* y_out);
+
+}  // namespace fate

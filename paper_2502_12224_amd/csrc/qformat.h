@@ -28,6 +28,7 @@ template <>
 struct QFmt<4> {
     static constexpr int KT = 64;       // columns per tile
     static constexpr int NP = 16;       // 16-bit pairs per lane per tile
+    static constexpr int MSTEPS = 4;    // 8-code matrix-core operands per lane per tile
     static constexpr float OFF_BF16 = 136.f;   // 128 + 8
     static constexpr float OFF_F16 = 1032.f;   // 1024 + 8
 };
@@ -35,6 +36,7 @@ template <>
 struct QFmt<8> {
     static constexpr int KT = 32;
     static constexpr int NP = 8;
+    static constexpr int MSTEPS = 2;
     static constexpr float OFF_BF16 = 128.f;   // value is u itself
     static constexpr float OFF_F16 = 1152.f;   // 1024 + 128
 };
@@ -71,6 +73,44 @@ __device__ __forceinline__ void unpack_pairs(const uint4& raw, uint32_t* p) {
                 p[2 * d + 0] = (f0 >> 16) | (f1 & 0xffff0000u);
                 p[2 * d + 1] = (f2 >> 16) | (f3 & 0xffff0000u);
             }
+        }
+    }
+}
+
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+
+// raw 16 bytes of one lane -> MSTEPS operands of 8 fp16 values holding the
+// signed codes q themselves (exact), in column order.  int4 uses two
+// power-of-two mantissa tricks so that one shift serves four pairs:
+// 0x6400|u = 1024 + u for nibbles at bits 0..3, 0x5400|(u << 4) = 64 + u for
+// nibbles at bits 4..7 of each 16-bit half.
+template <int BITS>
+__device__ __forceinline__ void codes_to_f16(const uint4& raw, f16x8_t* b) {
+    const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
+    if constexpr (BITS == 4) {
+        const f16x2_t offA = {(_Float16)1032.f, (_Float16)1032.f};   // 1024 + 8
+        const f16x2_t offB = {(_Float16)72.f, (_Float16)72.f};       // 64 + 8
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t hi = r[d] >> 8;
+            const f16x2_t w0 = __builtin_bit_cast(f16x2_t, (r[d] & 0x000f000fu) | 0x64006400u) - offA;
+            const f16x2_t w1 = __builtin_bit_cast(f16x2_t, (r[d] & 0x00f000f0u) | 0x54005400u) - offB;
+            const f16x2_t w2 = __builtin_bit_cast(f16x2_t, (hi & 0x000f000fu) | 0x64006400u) - offA;
+            const f16x2_t w3 = __builtin_bit_cast(f16x2_t, (hi & 0x00f000f0u) | 0x54005400u) - offB;
+            b[d] = f16x8_t{w0.x, w0.y, w1.x, w1.y, w2.x, w2.y, w3.x, w3.y};
+        }
+    } else {
+        const f16x2_t off = {(_Float16)1152.f, (_Float16)1152.f};    // 1024 + 128
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            f16x2_t w[4];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const uint32_t v = r[2 * h + j];
+                w[2 * j] = __builtin_bit_cast(f16x2_t, __builtin_amdgcn_perm(0x64646464u, v, 0x04010400u)) - off;
+                w[2 * j + 1] = __builtin_bit_cast(f16x2_t, __builtin_amdgcn_perm(0x64646464u, v, 0x04030402u)) - off;
+            }
+            b[h] = f16x8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
         }
     }
 }

@@ -20,18 +20,6 @@ __global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
     if (i < n) p[i] = v;
 }
 
-__device__ __forceinline__ float dot8_bf16(const uint4& a, const uint4& b, float acc) {
-    acc = fmaf(bf16_lo(a.x), bf16_lo(b.x), acc);
-    acc = fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
-    acc = fmaf(bf16_lo(a.y), bf16_lo(b.y), acc);
-    acc = fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
-    acc = fmaf(bf16_lo(a.z), bf16_lo(b.z), acc);
-    acc = fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
-    acc = fmaf(bf16_lo(a.w), bf16_lo(b.w), acc);
-    acc = fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
-    return acc;
-}
-
 // 4 waves per block, TPW token rows per wave.
 template <int TPW>
 __global__ __launch_bounds__(256) void route_rows_kernel(const uint16_t* __restrict__ x,
@@ -93,114 +81,16 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict
 // ---- fused decode-side routing --------------------------------------------
 // workspace: [0] ticket counter (int32, zero between calls), then at byte 256
 // the logits zbuf[2][N][E] fp32.
-constexpr int kFusedMaxN = 16;
-
-__global__ __launch_bounds__(256) void route_fused_kernel(
-    const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg, const float* __restrict__ bias,
-    const uint16_t* __restrict__ Wg2, const float* __restrict__ bias2, int N, int H, int E, int k, int m,
-    int renorm, int32_t* ids, float* w, int32_t* pids, float* pw, int32_t* pop, int32_t* counts,
-    int32_t* offsets, int32_t* perm, int32_t* inv_perm, int32_t* order, int32_t* ticket, float* zbuf) {
+__global__ __launch_bounds__(256) void route_fused_kernel(FusedRouteArgs a, int32_t* ticket) {
+    __shared__ FusedRouteSmem sm;
     __shared__ int32_t sm_perm[kPermSmemInts];
-    __shared__ float sm_z[4][kMaxE];
-    __shared__ int32_t sm_ids[kFusedMaxN * kMaxM];
-    __shared__ int32_t sm_pop[kMaxE];
     __shared__ int sm_last;
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-#ifdef FATE_PROBE
-    unsigned long long ts[8];
-    ts[0] = wall_clock64();
-#define FATE_TS(i) ts[i] = wall_clock64()
-#else
-#define FATE_TS(i)
-#endif
-    const int nvec = H >> 3;
-    const int nrows = Wg2 ? 2 * E : E;
-    const uint4* xg = reinterpret_cast<const uint4*>(x);
-    const int r = blockIdx.x * 4 + wave;
-    if (r < nrows) {
-        // one gate row against every token; x comes straight from L2
-        const int g = r >= E, e = g ? r - E : r;
-        const uint4* wr = reinterpret_cast<const uint4*>(g ? Wg2 : Wg) + (size_t)e * nvec;
-        const float* bb = g ? bias2 : bias;
-        const float b = bb ? bb[e] : 0.f;
-        for (int t0 = 0; t0 < N; t0 += 4) {
-            float acc[4] = {0.f, 0.f, 0.f, 0.f};
-            for (int c0 = lane; c0 < nvec; c0 += 64 * 8) {
-                // all requests of the batch go out before the first use
-                uint4 wv[8], xv[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int c = c0 + 64 * j;
-                    wv[j] = c < nvec ? wr[c] : make_uint4(0, 0, 0, 0);
-                    xv[j] = c < nvec ? xg[(size_t)t0 * nvec + c] : make_uint4(0, 0, 0, 0);
-                }
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int c = c0 + 64 * j;
-                    acc[0] = dot8_bf16(xv[j], wv[j], acc[0]);
-                    if (c < nvec) {
-#pragma unroll
-                        for (int t = 1; t < 4; ++t)
-                            if (t0 + t < N) acc[t] = dot8_bf16(xg[(size_t)(t0 + t) * nvec + c], wv[j], acc[t]);
-                    }
-                }
-            }
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                float s = wave_sum(acc[t]);
-                if (lane == 0 && t0 + t < N) zbuf[((size_t)g * N + t0 + t) * E + e] = s + b;
-            }
-        }
-    }
-    FATE_TS(1);
-    __threadfence();
-    FATE_TS(2);
-    __syncthreads();
+    fused_gate_rows(a, blockIdx.x, ZbufStore{a.zbuf, a.N, a.E});
+    __syncthreads();        // every wave's logit stores have completed
     if (threadIdx.x == 0) sm_last = (atomicAdd(ticket, 1) == (int)gridDim.x - 1);
     __syncthreads();
-    FATE_TS(3);
     if (!sm_last) return;
-    __threadfence();
-    FATE_TS(4);
-#ifdef FATE_PROBE
-    unsigned long long cyc4 = clock64();
-#endif
-    for (int i = threadIdx.x; i < E; i += 256) sm_pop[i] = 0;
-    __syncthreads();
-    const int njobs = (Wg2 ? 2 : 1) * N;
-    for (int j0 = 0; j0 < njobs; j0 += 4) {
-        int job = j0 + wave;
-        int g = job >= N, t = g ? job - N : job;
-        if (job < njobs) {
-            const volatile float* zr = zbuf + ((size_t)g * N + t) * E;
-            for (int e = lane; e < E; e += 64) sm_z[wave][e] = zr[e];
-            __builtin_amdgcn_wave_barrier();
-            if (!g) {
-                wave_softmax_topm(sm_z[wave], E, k, renorm, sm_ids + t * k, w + (size_t)t * k, nullptr, nullptr);
-            } else {
-                wave_softmax_topm(sm_z[wave], E, m, 0, pids + (size_t)t * m, pw + (size_t)t * m, nullptr, sm_pop);
-            }
-        }
-    }
-    __syncthreads();
-    FATE_TS(5);
-#ifdef FATE_PROBE
-    ts[7] = clock64() - cyc4;
-#endif
-    const int P = N * k;
-    for (int i = threadIdx.x; i < P; i += 256) ids[i] = sm_ids[i];
-    if (Wg2)
-        for (int i = threadIdx.x; i < E; i += 256) pop[i] = sm_pop[i];
-    if (P <= 64) {
-        if (wave == 0) wave_permute_small(sm_ids, P, E, counts, offsets, perm, inv_perm, order);
-    } else {
-        block_permute(sm_ids, P, E, counts, offsets, perm, inv_perm, order, sm_perm);
-    }
-    FATE_TS(6);
-#ifdef FATE_PROBE
-    if (threadIdx.x == 0)
-        for (int i = 0; i < 8; ++i) reinterpret_cast<unsigned long long*>(ticket)[8 + i] = ts[i];
-#endif
+    fused_select(a, sm, sm_perm, ZbufLoad{a.zbuf, a.N, a.E});
     if (threadIdx.x == 0) *ticket = 0;
 }
 
@@ -319,11 +209,11 @@ extern "C" fate_status fate_route_fused(void* stream, const void* x_bf16, const 
     FATE_CHECK_PTR(workspace);
     const int nrows = Wg_next_bf16 ? 2 * E : E;
     const int grid = (nrows + 3) / 4;
-    route_fused_kernel<<<grid, 256, 0, static_cast<hipStream_t>(stream)>>>(
-        static_cast<const uint16_t*>(x_bf16), static_cast<const uint16_t*>(Wg_bf16), bias,
-        static_cast<const uint16_t*>(Wg_next_bf16), bias_next, N, H, E, k, m, renorm != 0, topk_ids, topk_w,
-        pred_ids, pred_w, pred_pop, counts, offsets, perm, inv_perm, expert_order,
-        static_cast<int32_t*>(workspace), reinterpret_cast<float*>(static_cast<char*>(workspace) + 256));
+    FusedRouteArgs a{static_cast<const uint16_t*>(x_bf16), static_cast<const uint16_t*>(Wg_bf16), bias,
+                     static_cast<const uint16_t*>(Wg_next_bf16), bias_next, N, H, E, k, m, renorm != 0,
+                     topk_ids, topk_w, pred_ids, pred_w, pred_pop, counts, offsets, perm, inv_perm, expert_order,
+                     reinterpret_cast<float*>(static_cast<char*>(workspace) + 256)};
+    route_fused_kernel<<<grid, 256, 0, static_cast<hipStream_t>(stream)>>>(a, static_cast<int32_t*>(workspace));
     FATE_HIP(hipGetLastError());
     return FATE_OK;
 }

@@ -269,4 +269,132 @@ __device__ inline void block_permute(const int32_t* ids, int P, int E, int32_t* 
     }
 }
 
+__device__ __forceinline__ float dot8_bf16(const uint4& a, const uint4& b, float acc) {
+    acc = fmaf(bf16_lo(a.x), bf16_lo(b.x), acc);
+    acc = fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
+    acc = fmaf(bf16_lo(a.y), bf16_lo(b.y), acc);
+    acc = fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
+    acc = fmaf(bf16_lo(a.z), bf16_lo(b.z), acc);
+    acc = fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
+    acc = fmaf(bf16_lo(a.w), bf16_lo(b.w), acc);
+    acc = fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
+    return acc;
+}
+
+// ---- decode-side routing spread over workgroups ------------------------------
+constexpr int kFusedMaxN = 16;
+
+struct FusedRouteArgs {
+    const uint16_t* x; const uint16_t* Wg; const float* bias;
+    const uint16_t* Wg2; const float* bias2;      // next layer's gate (NULL: no prediction)
+    int N, H, E, k, m, renorm;
+    int32_t* ids; float* w; int32_t* pids; float* pw; int32_t* pop;
+    int32_t* counts; int32_t* offsets; int32_t* perm; int32_t* inv_perm; int32_t* order;
+    float* zbuf;                                  // [2][N][E] logits
+};
+
+struct FusedRouteSmem {
+    float z[8][kMaxE];                            // one row per wave of the workgroup (at most 8)
+    int32_t ids[kFusedMaxN * kMaxM];
+    int32_t pop[kMaxE];
+};
+
+// Logits go through device-scope stores / loads: the selecting workgroup may
+// sit on another compute die than the one that produced a logit.
+struct ZbufStore {
+    float* zbuf; int N, E;
+    __device__ __forceinline__ void operator()(int g, int t, int e, float v) const {
+        st_dev(zbuf + ((size_t)g * N + t) * E + e, v);
+    }
+};
+struct ZbufLoad {
+    const float* zbuf; int N, E;
+    __device__ __forceinline__ float operator()(int g, int t, int e) const {
+        return ld_dev(zbuf + ((size_t)g * N + t) * E + e);
+    }
+};
+
+// Workgroup `rblock` of ceil(rows / waves-per-workgroup): each of its waves
+// takes one gate row (of this layer's gate, then of the next layer's) against
+// every token and hands each logit to store(g, token, expert, value).
+template <class Store>
+__device__ __forceinline__ void fused_gate_rows(const FusedRouteArgs& a, int rblock, const Store& store) {
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int N = a.N, E = a.E, nvec = a.H >> 3;
+    const int nrows = a.Wg2 ? 2 * E : E;
+    const uint4* xg = reinterpret_cast<const uint4*>(a.x);
+    const int r = rblock * (int)(blockDim.x >> 6) + wave;
+    if (r >= nrows) return;
+    const int g = r >= E, e = g ? r - E : r;
+    const uint4* wr = reinterpret_cast<const uint4*>(g ? a.Wg2 : a.Wg) + (size_t)e * nvec;
+    const float* bb = g ? a.bias2 : a.bias;
+    const float b = bb ? bb[e] : 0.f;
+    for (int t0 = 0; t0 < N; t0 += 4) {
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int c0 = lane; c0 < nvec; c0 += 64 * 8) {
+            // all requests of the batch go out before the first use
+            uint4 wv[8], xv[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int c = c0 + 64 * j;
+                wv[j] = c < nvec ? wr[c] : make_uint4(0, 0, 0, 0);
+                xv[j] = c < nvec ? xg[(size_t)t0 * nvec + c] : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int c = c0 + 64 * j;
+                acc[0] = dot8_bf16(xv[j], wv[j], acc[0]);
+                if (c < nvec) {
+#pragma unroll
+                    for (int t = 1; t < 4; ++t)
+                        if (t0 + t < N) acc[t] = dot8_bf16(xg[(size_t)(t0 + t) * nvec + c], wv[j], acc[t]);
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            float s = wave_sum(acc[t]);
+            if (lane == 0 && t0 + t < N) store(g, t0 + t, e, s + b);
+        }
+    }
+}
+
+// Run by one whole workgroup (4..8 waves) once every logit has been stored:
+// softmax and selection per token, predicted popularity, permutation.
+// load(g, token, expert) returns a logit.  sm_perm: kPermSmemInts ints, only
+// touched when N*k > 64 (may be NULL otherwise).
+template <class Load>
+__device__ __forceinline__ void fused_select(const FusedRouteArgs& a, FusedRouteSmem& sm, int32_t* sm_perm,
+                                             const Load& load) {
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nthreads = blockDim.x, nw = nthreads >> 6;
+    const int N = a.N, E = a.E, k = a.k, m = a.m;
+    for (int i = threadIdx.x; i < E; i += nthreads) sm.pop[i] = 0;
+    __syncthreads();
+    const int njobs = (a.Wg2 ? 2 : 1) * N;
+    for (int j0 = 0; j0 < njobs; j0 += nw) {
+        const int job = j0 + wave;
+        const int g = job >= N, t = g ? job - N : job;
+        if (job < njobs) {
+            for (int e = lane; e < E; e += 64) sm.z[wave][e] = load(g, t, e);
+            __builtin_amdgcn_wave_barrier();
+            if (!g) {
+                wave_softmax_topm(sm.z[wave], E, k, a.renorm, sm.ids + t * k, a.w + (size_t)t * k, nullptr, nullptr);
+            } else {
+                wave_softmax_topm(sm.z[wave], E, m, 0, a.pids + (size_t)t * m, a.pw + (size_t)t * m, nullptr, sm.pop);
+            }
+        }
+    }
+    __syncthreads();
+    const int P = N * k;
+    for (int i = threadIdx.x; i < P; i += nthreads) a.ids[i] = sm.ids[i];
+    if (a.Wg2)
+        for (int i = threadIdx.x; i < E; i += nthreads) a.pop[i] = sm.pop[i];
+    if (P <= 64) {
+        if (wave == 0) wave_permute_small(sm.ids, P, E, a.counts, a.offsets, a.perm, a.inv_perm, a.order);
+    } else {
+        block_permute(sm.ids, P, E, a.counts, a.offsets, a.perm, a.inv_perm, a.order, sm_perm);
+    }
+}
+
 }  // namespace fate

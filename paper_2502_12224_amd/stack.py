@@ -58,10 +58,28 @@ class LayerBuffers:
         self.ffn_ws = torch.zeros(B.fate_moe_ffn_q_workspace(self.desc), dtype=torch.uint8, device=device)
         self.fused_ok = 1 <= N <= 16
         self.route_ws = torch.zeros(B.fate_route_fused_workspace(max(N, 1), E), dtype=torch.uint8, device=device)
+        # whole layer in one launch (small decode batches)
+        self.one_launch_ok = 1 <= N <= 8 and N * k <= 64 and mode != 2
+        if self.one_launch_ok:
+            nbytes, self.status_offset = B.fate_moe_layer_decode_workspace(self.desc)
+            self.layer_ws = torch.zeros(nbytes, dtype=torch.uint8, device=device)
+
+    def status(self):
+        """Status word of the last one-launch layer call (0 = fine)."""
+        return int(self.layer_ws[self.status_offset:self.status_offset + 4].view(torch.int32)[0])
 
 
-def layer_forward(cfg: MoEShape, lw: LayerWeights, lw_next, x, buf: LayerBuffers, fused=None, phases=0):
+def layer_forward(cfg: MoEShape, lw: LayerWeights, lw_next, x, buf: LayerBuffers, fused=None, phases=0,
+                  one_launch=None):
     """One MoE layer: route, predict the next layer's experts, permute, FFN."""
+    one_launch = (buf.one_launch_ok and phases == 0 and fused is None) if one_launch is None else one_launch
+    if one_launch:
+        B.fate_moe_layer_decode(buf.desc, x, lw.Wg, lw.bias, None if lw_next is None else lw_next.Wg,
+                                None if lw_next is None else lw_next.bias, cfg.m, cfg.renorm, buf.ids, buf.w,
+                                buf.pred_ids, buf.pred_w, buf.pred_pop, buf.counts, buf.offsets, buf.perm,
+                                buf.inv_perm, buf.order, lw.table, lw.shared_table, lw.shared_gate, buf.y,
+                                buf.layer_ws)
+        return buf.y
     fused = buf.fused_ok if fused is None else fused
     if fused:
         B.fate_route_fused(x, lw.Wg, lw.bias, None if lw_next is None else lw_next.Wg,

@@ -1,0 +1,85 @@
+"""One-launch decode layer against the separate calls and the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe as O
+import paper_2502_12224_amd.binding as B
+from paper_2502_12224_amd.stack import LayerBuffers, LayerWeights, layer_forward
+from workloads import SHAPES, gen_hidden
+from helpers import DEV, bias_np, f32, ffn_rel_err, oracle_expert
+
+pytestmark = pytest.mark.gpu
+
+ROUTE_FIELDS = ("ids", "w", "counts", "offsets", "perm", "inv_perm", "order")
+PRED_FIELDS = ("pred_ids", "pred_w", "pred_pop")
+
+
+def _snapshot(buf, fields):
+    return {f: getattr(buf, f).clone() for f in fields}
+
+
+@pytest.mark.parametrize("name,N,last", [("tiny", 1, False), ("tiny", 8, False), ("tiny", 5, True),
+                                         ("qwen", 1, False), ("qwen", 1, True), ("qwen", 6, False),
+                                         ("deepseek", 8, False), ("mixtral", 1, False), ("mixtral", 4, False)])
+def test_one_launch_layer_equals_separate_calls_and_oracle(name, N, last):
+    cfg = SHAPES[name]
+    print(f"case {name} N={N} last={last}", flush=True)
+    x = gen_hidden(cfg, N, device=DEV)
+    lw = LayerWeights(cfg, 0, DEV)
+    ln = None
+    if not last:
+        ln = LayerWeights(cfg, 1, DEV, experts=[])
+    sep = LayerBuffers(cfg, N, DEV)
+    one = LayerBuffers(cfg, N, DEV)
+    assert one.one_launch_ok
+    layer_forward(cfg, lw, ln, x, sep, one_launch=False)
+    torch.cuda.synchronize()
+    y_sep = sep.y.clone()
+    fields = ROUTE_FIELDS + (() if last else PRED_FIELDS)
+    want = _snapshot(sep, fields)
+    P = N * cfg.k
+    # three calls in a row on the same workspace: the counters must come back to zero each time
+    for rep in range(3):
+        one.y.fill_(float("nan"))
+        layer_forward(cfg, lw, ln, x, one, one_launch=True)
+        torch.cuda.synchronize()
+        assert one.status() == 0, f"status {one.status()} on call {rep}"
+        for f in fields:
+            a, b = getattr(one, f), want[f]
+            if f in ("perm", "inv_perm"):
+                a, b = a[:P], b[:P]
+            assert torch.equal(a, b), (f, rep)
+        y_one = f32(one.y)
+        assert np.isfinite(y_one).all()
+        # same arithmetic up to the order of the fp32 partial sums (which can move an fp16 rounding of h)
+        assert ffn_rel_err(y_one, f32(y_sep).astype(np.float64)).max() <= 1e-4, rep
+    sync_words = one.layer_ws[:8].view(torch.int32).cpu().numpy()
+    assert sync_words[0] == 3 and sync_words[1] == 0       # epoch = number of calls, exit counter back at zero
+    # against the oracle
+    rid, rw, _, rz = O.gate_route(f32(x), f32(lw.Wg), bias_np(lw.bias), cfg.k, cfg.renorm)
+    if len(O.near_tie_rows(rz, cfg.k)) == 0:
+        assert np.array_equal(one.ids.cpu().numpy(), rid)
+    ids_h = one.ids.cpu().numpy()
+    from workloads import gen_expert
+    experts = {int(e): oracle_expert(gen_expert(cfg, 0, int(e), device=DEV)) for e in set(ids_h.ravel().tolist())}
+    shared = [oracle_expert(gen_expert(cfg, 0, s, shared=True, device=DEV)) for s in range(cfg.n_shared)]
+    sg = None if lw.shared_gate is None else f32(lw.shared_gate)
+    y_ref = O.moe_ffn(f32(x), ids_h, one.w.cpu().numpy().astype(np.float64), experts, shared, sg)
+    err = ffn_rel_err(f32(one.y), y_ref).max()
+    print(f"  max row error vs oracle {err:.2e}")
+    assert err <= 2e-3
+
+
+def test_one_launch_layer_rejects_large_batches():
+    cfg = SHAPES["tiny"]
+    d = B.make_ffn_desc(9, cfg.H, cfg.E, cfg.k, cfg.I, cfg.bits, cfg.group, 0, 0, cfg.bits, cfg.group, True, 0)
+    nbytes, _ = B.fate_moe_layer_decode_workspace(d)
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device=DEV)
+    buf = LayerBuffers(cfg, 9, DEV)
+    lw = LayerWeights(cfg, 0, DEV)
+    x = gen_hidden(cfg, 9, device=DEV)
+    with pytest.raises(B.FateError):
+        B.fate_moe_layer_decode(d, x, lw.Wg, lw.bias, None, None, cfg.m, cfg.renorm, buf.ids, buf.w, None, None, None,
+                                buf.counts, buf.offsets, buf.perm, buf.inv_perm, buf.order, lw.table, None, None,
+                                buf.y, ws)
