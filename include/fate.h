@@ -124,20 +124,24 @@ fate_status fate_route_fused(void* stream, const void* x_bf16, const void* Wg_bf
  * wavefront, so that a wave-wide load is one contiguous KiB and each lane's
  * piece feeds its MFMA operand or its dot products directly.
  * fate_pack_weight converts canonical -> device-native (dev to dev, same
- * byte size, out of place).  rows % 32 == 0, K % 64 == 0.  Scales are used
- * in canonical layout.
+ * byte size, out of place).  rows % 32 == 0, K % 64 == 0.
+ * Device-native scales are group-major, fp16 [K/group, rows]: the 32 rows of
+ * a tile find their scales of one group in 64 contiguous bytes.
+ * fate_pack_scales transposes canonical [rows, groups] into that form (dev
+ * to dev, out of place).
  * ---------------------------------------------------------------------- */
 fate_status fate_pack_weight(void* stream, const void* canonical_dev, int rows, int K, int bits,
                              void* packed_dev);
+fate_status fate_pack_scales(void* stream, const void* canonical_dev, int rows, int groups, void* packed_dev);
 
 /* One SwiGLU expert on the device (an element of a device-resident table). */
 typedef struct {
     const void* w1; /* gate proj  [I,H] device-native codes; NULL = not resident */
     const void* w3; /* up proj    [I,H] */
     const void* w2; /* down proj  [H,I] */
-    const void* s1; /* fp16 scales [I,H/group] */
+    const void* s1; /* fp16 scales, group-major [H/group, I] */
     const void* s3;
-    const void* s2; /* fp16 scales [H,I/group] */
+    const void* s2; /* fp16 scales, group-major [I/group, H] */
     int32_t bits;   /* 4 or 8 */
     int32_t group;  /* multiple of 64 */
     int32_t I;      /* intermediate size, multiple of 64 */

@@ -19,7 +19,7 @@ STATUS_NAMES = {0: "FATE_OK", 1: "FATE_EINVAL", 2: "FATE_ESHAPE", 3: "FATE_EALIG
 
 EXPORTS = [
     "fate_last_error", "fate_version", "fate_gate_route", "fate_cross_layer_predict", "fate_permute",
-    "fate_route_fused_workspace", "fate_route_fused", "fate_pack_weight", "fate_moe_ffn_q_workspace",
+    "fate_route_fused_workspace", "fate_route_fused", "fate_pack_weight", "fate_pack_scales", "fate_moe_ffn_q_workspace",
     "fate_moe_ffn_q", "fate_moe_layer_decode_workspace", "fate_moe_layer_decode", "fate_cache_total_from_budget", "fate_n_max_from_times", "fate_cache_layer_capacities",
     "fate_cache_create", "fate_cache_destroy", "fate_cache_total_slots", "fate_cache_set_n_max", "fate_cache_slot_of",
     "fate_cache_resident", "fate_expert_cache_step", "fate_expert_cache_step_dense",
@@ -215,6 +215,10 @@ def fate_moe_ffn_q(desc, x, experts_dev, counts, offsets, perm, inv_perm, expert
 # ---------------------------------------------------------------------------
 
 
+def fate_pack_scales(canonical, rows, groups, packed, stream=None):
+    _check(lib().fate_pack_scales(_stream(stream), _p(canonical), rows, groups, _p(packed)))
+
+
 class PackedExpert:
     """Device-native copy of one expert: packed codes + scales, kept alive."""
 
@@ -226,8 +230,11 @@ class PackedExpert:
             dst = torch.empty_like(src)
             fate_pack_weight(src, rows, K, ex.bits, dst)
             self.t[name] = dst
-        for name in ("s1", "s3", "s2"):
-            self.t[name] = getattr(ex, name).to(device).contiguous()
+        for name, rows, K in (("s1", ex.I, ex.H), ("s3", ex.I, ex.H), ("s2", ex.H, ex.I)):
+            src = getattr(ex, name).to(device).contiguous()
+            dst = torch.empty_like(src).view(K // ex.group, rows)
+            fate_pack_scales(src, rows, K // ex.group, dst)
+            self.t[name] = dst
         torch.cuda.current_stream().synchronize()
 
     def struct(self):

@@ -39,6 +39,13 @@ __device__ __forceinline__ float half_bits_to_float(uint32_t b) {
 
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits
+// for every outstanding global load of the wave, which would drain the ring
+// of weight tiles that is meant to stay in flight across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ f32x16_t f32x16_zero() {
     return f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 }
@@ -62,10 +69,11 @@ struct TileRing {
     uint32_t sc[NMAT][D / TPG];   // fp16 bits of the group scale, one full register each
 };
 
-// request the first D tiles of the groups [g_beg, g_end) (TPG tiles per group)
+// request the first D tiles of the groups [g_beg, g_end) (TPG tiles per group).
+// sc[i]: this lane's row in the group-major scale array, srows = its row count.
 template <int NMAT, int D, int TPG>
 __device__ __forceinline__ void ring_start(TileRing<NMAT, D, TPG>& r, const gu4_t* wt, const gu16_t* sc,
-                                           int g_beg, int g_end) {
+                                           int srows, int g_beg, int g_end) {
     const int tbeg = g_beg * TPG, tend = g_end * TPG;
 #pragma unroll
     for (int j = 0; j < D; ++j) {
@@ -73,7 +81,7 @@ __device__ __forceinline__ void ring_start(TileRing<NMAT, D, TPG>& r, const gu4_
 #pragma unroll
             for (int i = 0; i < NMAT; ++i) {
                 r.raw[i][j] = wt[i][(size_t)(tbeg + j) * 64];
-                if (j % TPG == 0) r.sc[i][j / TPG] = sc[i][g_beg + j / TPG];
+                if (j % TPG == 0) r.sc[i][j / TPG] = sc[i][(size_t)(g_beg + j / TPG) * srows];
             }
         }
     }
@@ -87,7 +95,7 @@ __device__ __forceinline__ void ring_start(TileRing<NMAT, D, TPG>& r, const gu4_
 // 4*half + j.
 template <int BITS, int TPG, int NMAT, int D>
 __device__ __forceinline__ void ring_run(TileRing<NMAT, D, TPG>& r, const gu4_t* wt, const gu16_t* sc,
-                                         int g_beg, int g_end, const _Float16* xa, int k_base,
+                                         int srows, int g_beg, int g_end, const _Float16* xa, int k_base,
                                          float (&out)[NMAT][4]) {
     constexpr int KT = QFmt<BITS>::KT, S = QFmt<BITS>::MSTEPS;
     static_assert(D % TPG == 0, "ring depth must hold whole groups");
@@ -104,7 +112,7 @@ __device__ __forceinline__ void ring_run(TileRing<NMAT, D, TPG>& r, const gu4_t*
                 const int gnext = base / TPG + jg + D / TPG;
                 if (gnext < g_end) {
 #pragma unroll
-                    for (int i = 0; i < NMAT; ++i) r.sc[i][jg] = sc[i][gnext];
+                    for (int i = 0; i < NMAT; ++i) r.sc[i][jg] = sc[i][(size_t)gnext * srows];
                 }
 #pragma unroll
                 for (int tl = 0; tl < TPG; ++tl) {

@@ -112,7 +112,7 @@ extern "C" fate_status fate_moe_layer_decode_workspace(const fate_ffn_desc* d, s
     fate_status s = check_desc(d);
     if (s != FATE_OK) return s;
     if (bytes == nullptr) FATE_FAIL(FATE_EINVAL, "bytes is NULL");
-    const LayerWorkspace w = layer_workspace(d->N, d->H, d->E, d->y_is_fp32 != 0);
+    const LayerWorkspace w = layer_workspace(*d);
     *bytes = w.bytes;
     if (status_offset) *status_offset = w.status;
     return FATE_OK;
@@ -144,7 +144,7 @@ extern "C" fate_status fate_moe_layer_decode(void* stream, const fate_ffn_desc* 
         FATE_FAIL(FATE_EINVAL, "prediction outputs must not be NULL when the next gate is given");
     if (!experts_dev) FATE_FAIL(FATE_EINVAL, "experts_dev is NULL");
     if (d->n_shared && !shared_dev) FATE_FAIL(FATE_EINVAL, "shared_dev is NULL with n_shared = %d", d->n_shared);
-    const LayerWorkspace w = layer_workspace(d->N, d->H, d->E, d->y_is_fp32 != 0);
+    const LayerWorkspace w = layer_workspace(*d);
     if (workspace == nullptr || workspace_bytes < w.bytes)
         FATE_FAIL(FATE_EWORKSPACE, "workspace of %zu bytes needed, %zu given", w.bytes, workspace_bytes);
     FATE_CHECK_PTR(workspace);
@@ -160,8 +160,11 @@ extern "C" fate_status fate_moe_layer_decode(void* stream, const fate_ffn_desc* 
     a.shared_gate = static_cast<const uint16_t*>(shared_gate_bf16);
     a.bits_r = d->bits; a.group_r = d->group;
     a.bits_s = d->n_shared ? d->shared_bits : d->bits; a.group_s = d->n_shared ? d->shared_group : d->group;
-    a.y = d->y_is_fp32 ? static_cast<float*>(y) : reinterpret_cast<float*>(base + w.ybuf);
+    a.part_r = reinterpret_cast<float*>(base + w.part_r);
+    a.part_s = reinterpret_cast<float*>(base + w.part_s);
+    a.y = y;
+    a.y_is_fp32 = d->y_is_fp32;
     a.status = reinterpret_cast<int32_t*>(base + w.status);
     a.sync = reinterpret_cast<int32_t*>(base + w.sync);
-    return launch_layer_decode(static_cast<hipStream_t>(stream), *d, a, y);
+    return launch_layer_decode(static_cast<hipStream_t>(stream), *d, a);
 }

@@ -76,8 +76,8 @@ __global__ __launch_bounds__(256, 2) void ffn_up_decode_kernel(DecodeArgs a) {
     const int n = lane & 31, half = lane >> 5;
     const int g_beg = G * wave / 4, g_end = G * (wave + 1) / 4;
     gu4_t wt[2] = {w1 + (size_t)rb * tiles_k * 64 + lane, w3 + (size_t)rb * tiles_k * 64 + lane};
-    gu16_t sc[2] = {as_global<uint16_t>(ex->s1) + (size_t)(rb * 32 + n) * G,
-                    as_global<uint16_t>(ex->s3) + (size_t)(rb * 32 + n) * G};
+    gu16_t sc[2] = {as_global<uint16_t>(ex->s1) + rb * 32 + n, as_global<uint16_t>(ex->s3) + rb * 32 + n};
+    const int srows = ex->I;
     const int ldx = H + kLdsPad;                       // halves per LDS row; the last row is all zero
     const int zrow = a.lds_rows - 1;
     _Float16* xs = reinterpret_cast<_Float16*>(smem);
@@ -114,18 +114,18 @@ __global__ __launch_bounds__(256, 2) void ffn_up_decode_kernel(DecodeArgs a) {
 #define FATE_UP_BODY(BITS, TPG)                                                                          \
     {                                                                                                     \
         TileRing<2, kRing, TPG> ring;                                                                     \
-        ring_start<2, kRing, TPG>(ring, wt, sc, g_beg, g_end);                                            \
+        ring_start<2, kRing, TPG>(ring, wt, sc, srows, g_beg, g_end);                                            \
         for (int t0 = 0; t0 < T; t0 += kTokPass) {                                                        \
             const int nt = min(kTokPass, T - t0);                                                         \
             if (t0 > 0) {                                                                                 \
                 __syncthreads();                                                                          \
-                ring_start<2, kRing, TPG>(ring, wt, sc, g_beg, g_end);                                    \
+                ring_start<2, kRing, TPG>(ring, wt, sc, srows, g_beg, g_end);                                    \
             }                                                                                             \
             stage_x(nt, t0);                                                                              \
             __syncthreads();                                                                              \
             float out[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};                               \
             const int arow = n < nt ? n : zrow;                                                           \
-            ring_run<BITS, TPG, 2, kRing>(ring, wt, sc, g_beg, g_end,                                     \
+            ring_run<BITS, TPG, 2, kRing>(ring, wt, sc, srows, g_beg, g_end,                                    \
                                           xs + arow * ldx + half * (QFmt<BITS>::KT / 2), 0, out);         \
             finish(nt, t0, out);                                                                          \
         }                                                                                                 \
@@ -176,7 +176,8 @@ __global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
     const int tiles_k = I / KT, tpg = group / KT;
     const int n = lane & 31, half = lane >> 5;
     gu4_t wt[1] = {w2 + (size_t)rb * tiles_k * 64 + lane};
-    gu16_t sc[1] = {as_global<uint16_t>(ex->s2) + (size_t)(rb * 32 + n) * G};
+    gu16_t sc[1] = {as_global<uint16_t>(ex->s2) + rb * 32 + n};
+    const int srows = a.H;
     const int ng = ge - gb;
     const int g_beg = gb + ng * wave / 4, g_end = gb + ng * (wave + 1) / 4;
     const int Kc = ng * group, kvec = Kc >> 3, k_base = gb * group;
@@ -226,18 +227,18 @@ __global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
 #define FATE_DOWN_BODY(BITS, TPG)                                                                         \
     {                                                                                                     \
         TileRing<1, kRing, TPG> ring;                                                                     \
-        ring_start<1, kRing, TPG>(ring, wt, sc, g_beg, g_end);                                            \
+        ring_start<1, kRing, TPG>(ring, wt, sc, srows, g_beg, g_end);                                            \
         for (int t0 = 0; t0 < T; t0 += kTokPass) {                                                        \
             const int nt = min(kTokPass, T - t0);                                                         \
             if (t0 > 0) {                                                                                 \
                 __syncthreads();                                                                          \
-                ring_start<1, kRing, TPG>(ring, wt, sc, g_beg, g_end);                                    \
+                ring_start<1, kRing, TPG>(ring, wt, sc, srows, g_beg, g_end);                                    \
             }                                                                                             \
             stage_h(nt, t0);                                                                              \
             __syncthreads();                                                                              \
             float out[1][4] = {{0.f, 0.f, 0.f, 0.f}};                                                     \
             const int arow = n < nt ? n : zrow;                                                           \
-            ring_run<BITS, TPG, 1, kRing>(ring, wt, sc, g_beg, g_end,                                     \
+            ring_run<BITS, TPG, 1, kRing>(ring, wt, sc, srows, g_beg, g_end,                                    \
                                           xs + arow * ldx + half * (QFmt<BITS>::KT / 2), k_base, out);    \
             finish(nt, t0, out);                                                                          \
         }                                                                                                 \

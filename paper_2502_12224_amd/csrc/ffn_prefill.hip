@@ -174,7 +174,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
 #pragma unroll
         for (int i = 0; i < NMAT; ++i) {
             wt[i] = (gu4p_t)(uintptr_t)wp[i] + (size_t)(wrow0 >> 5) * tiles_k * 64 + lane;
-            sc[i] = (gu16p_t)(uintptr_t)sp[i] + (size_t)(wrow0 + n) * G;
+            sc[i] = (gu16p_t)(uintptr_t)sp[i] + wrow0 + n;          // group-major scales: [G][Nout]
         }
     }
     f32x16_t acc[NMAT][kBM / 32];
@@ -204,7 +204,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
                 for (int tl = 0; tl < TPC; ++tl) {
                     const int tile = kc * TPC + tl;
                     raw[i][tl] = wt[i][(size_t)tile * 64];
-                    sbits[i][tl] = sc[i][(tile * KT) / group];
+                    sbits[i][tl] = sc[i][(size_t)((tile * KT) / group) * Nout];
                 }
         }
     };

@@ -6,9 +6,9 @@
 
 namespace fate {
 
-constexpr int kLayerWaves = 8;                  // waves per workgroup
+constexpr int kLayerWaves = 4;                  // waves per workgroup
 constexpr int kLayerThreads = 64 * kLayerWaves;
-constexpr int kLayerNeurons = 64;               // intermediate neurons per work block
+constexpr int kLayerNeurons = 32;               // intermediate neurons per work block
 constexpr int kLayerMaxN = 8;                   // tokens per call
 constexpr int kLayerMaxP = 64;                  // (token, expert) pairs per call
 
@@ -20,31 +20,36 @@ struct LayerArgs {
     const uint16_t* shared_gate;
     int n_shared, bits_r, group_r, bits_s, group_s;
     int nb_route;                  // routing workgroups (block ids [0, nb_route))
-    int nb_zero;                   // the first nb_zero of them clear y (those whose logits every consumer awaits)
-    int nkb_r, nkb_s;              // 64-neuron blocks per routed / shared expert
+    int nkb_r, nkb_s;              // 32-neuron blocks per routed / shared expert
     int nact;                      // routed expert slots: min(E, N*k)
-    float* y;                      // [N,H] fp32, accumulated with atomics
+    float* part_r;                 // [N*k pairs][nkb_r][H] weighted partial outputs of the routed blocks
+    float* part_s;                 // [n_shared][nkb_s][N][H] same for the shared experts
+    void* y;                       // [N,H] fp32 or bf16, written by the reduction kernel
+    int y_is_fp32;
     int32_t* status;
     int32_t* sync;                 // [0] epoch of the previous call, [1] workgroups that have left
 };
 
 // byte offsets inside the workspace of fate_moe_layer_decode
 struct LayerWorkspace {
-    size_t sync, zq, status, ybuf, bytes;
+    size_t sync, zq, status, part_r, part_s, bytes;
 };
 
-inline LayerWorkspace layer_workspace(int N, int H, int E, bool y_is_fp32) {
+inline LayerWorkspace layer_workspace(const fate_ffn_desc& d) {
+    const int N = d.N, H = d.H, E = d.E;
     auto up = [](size_t v) { return (v + 255) / 256 * 256; };
     LayerWorkspace w;
     size_t off = 0;
     w.sync = off; off += 256;
     w.zq = off; off += up((size_t)2 * N * E * sizeof(unsigned long long));
     w.status = off; off += 256;
-    w.ybuf = off; off += y_is_fp32 ? 0 : up((size_t)N * H * sizeof(float));
+    w.part_r = off; off += up((size_t)N * d.k * (d.I_max / kLayerNeurons) * H * sizeof(float));
+    w.part_s = off;
+    off += up((size_t)d.n_shared * (d.n_shared ? d.I_shared_max / kLayerNeurons : 0) * N * H * sizeof(float));
     w.bytes = off;
     return w;
 }
 
-fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArgs a, void* y_out);
+fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArgs a);
 
 }  // namespace fate

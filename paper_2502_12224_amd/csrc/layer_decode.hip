@@ -1,23 +1,24 @@
-// fate_moe_layer_decode: one launch for a whole decode-side MoE layer (1..8
+// fate_moe_layer_decode: a whole decode-side MoE layer in two launches (1..8
 // tokens): gate logits, softmax / top-k, cross-layer prediction, permutation
 // and the quantised expert FFN.
 //
 // Block ids, in order:
 //  routing workgroups: each wave evaluates one gate row (this layer's gate,
 //    then the next layer's) for every token and publishes the logit tagged
-//    with the call's epoch.  The first of them also clear y.  The last one
-//    waits for all logits and writes the routing outputs of the API.
-//  work blocks: 64 intermediate neurons of one shared expert or of one routed
+//    with the call's epoch.  The last one waits for all logits and writes the
+//    routing outputs of the API.
+//  work blocks: 32 intermediate neurons of one shared expert or of one routed
 //    slot.  A routed block polls the tagged logits (the only cross-workgroup
 //    dependency on its path), redoes softmax / top-k / permutation for itself
 //    in LDS - same code on the same bits as the routing workgroup - and so
 //    learns its expert without waiting for another workgroup's bookkeeping.
-//    Then: all requests for its W1/W3 row blocks and W2 column block go out,
-//    eight waves split the reduction dimension of the up projection, the 64
+//    Then: all requests for its W1/W3 row block and W2 column block go out,
+//    the waves split the reduction dimension of the up projection, the 32
 //    values of h stay in LDS, and each wave multiplies them into its share of
-//    the 32-row blocks of W2 and adds weight * partial into y with fp32
-//    atomics (blocks walk the row blocks from different starting points so
-//    that they do not hit the same addresses at the same time).
+//    the 32-row blocks of W2 and stores weight * partial as a row of its own
+//    (device-scope fp32 atomics on y serialise at the memory side and were
+//    several times slower than writing the rows out and adding them up).
+//  A second, small kernel adds the partial rows into y.
 // A workgroup only ever waits for workgroups with lower ids, which the
 // dispatcher of its compute die has started before it; every wait is bounded
 // and turns into a status bit when it runs out.
@@ -30,9 +31,12 @@
 
 namespace fate {
 
+#ifndef FATE_EXP
+#define FATE_EXP 0
+#endif
 constexpr int kSpinMax = 1 << 18;
-constexpr int kUpRing = 4;        // tiles in flight per (row block, matrix) per wave: 16 KiB
-constexpr int kDownRing = 8;      // W2 tiles in flight per wave
+constexpr int kUpRing = 8;        // tiles in flight per matrix per wave
+constexpr int kDownRing = 8;      // W2 pieces in flight per wave
 constexpr int kHsLd = kLayerNeurons + kLdsPad;   // halves per row of h in LDS
 
 #ifdef FATE_PROBE
@@ -85,7 +89,7 @@ __host__ __device__ inline WorkLds work_lds(int N, int H, int E, int k) {
     int off = 0;
     L.xs = off; off += up((N + 1) * (H + kLdsPad) * 2);
     L.hs = off; off += up((kTokPass + 1) * kHsLd * 2);
-    L.red = off; off += up(kLayerWaves * 4 * ntp * 32 * 4);
+    L.red = off; off += up(kLayerWaves * 2 * ntp * 32 * 4);
     L.tab = off; off += up(E * (int)sizeof(fate_qexpert));
     L.zl = off; off += up(2 * N * E * 4);
     L.ids = off; off += up(P * 4);
@@ -104,14 +108,6 @@ __host__ __device__ inline WorkLds work_lds(int N, int H, int E, int k) {
 __device__ __forceinline__ void route_role(const LayerArgs& a, int b, uint32_t tag, char* dyn, FusedRouteSmem& rsm) {
     const int tid = threadIdx.x;
     const FusedRouteArgs& r = a.r;
-    if (b < a.nb_zero) {
-        const int total = r.N * r.H;
-        const int per = (total + a.nb_zero - 1) / a.nb_zero;
-        const int b1 = min(total, (b + 1) * per);
-        for (int i = b * per + tid; i < b1; i += kLayerThreads) st_dev(a.y + i, 0.f);
-        // the cleared slice is in place before any logit of this workgroup can be seen
-        __syncthreads();
-    }
     fused_gate_rows(r, b, TaggedStore{a.zq, r.N, r.E, tag});
     FATE_TS(1);
     if (b != a.nb_route - 1) return;
@@ -173,32 +169,24 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
 
     fate_qexpert ex;
     int kb, T, bits, group;
+    int32_t* pairq = reinterpret_cast<int32_t*>(dyn + L.perm);   // routed: original pair index of each of the T rows
+    float* part;                  // where this block's weighted partial output rows go
+    size_t part_stride;           // floats between the rows of consecutive tokens of this block
     if (is_shared) {
         const int s = wb / a.nkb_s;
         kb = wb - s * a.nkb_s;
         ex = a.shared[s];
         T = N;
         bits = a.bits_s; group = a.group_s;
-        if (a.shared_gate != nullptr) {
-            for (int t = wave; t < N; t += kLayerWaves) {
-                const float g = wave_sigmoid_dot_bf16(reinterpret_cast<const uint4*>(a.r.x) + (size_t)t * nvec,
-                                                      reinterpret_cast<const uint4*>(a.shared_gate), nvec);
-                if (lane == 0) wtok[t] = g;
-            }
-        } else if (tid < N) {
-            wtok[tid] = 1.0f;
-        }
+        part = a.part_s + ((size_t)s * a.nkb_s + kb) * N * H;
+        part_stride = H;
         if (tid < N) tokid[tid] = tid;
+        FATE_TS(1);
     } else {
         uint4* tab = reinterpret_cast<uint4*>(dyn + L.tab);
         float* zl = reinterpret_cast<float*>(dyn + L.zl);
         int32_t* ids = reinterpret_cast<int32_t*>(dyn + L.ids);
         float* wv = reinterpret_cast<float*>(dyn + L.w);
-        int32_t* counts = reinterpret_cast<int32_t*>(dyn + L.counts);
-        int32_t* offsets = reinterpret_cast<int32_t*>(dyn + L.offsets);
-        int32_t* perm = reinterpret_cast<int32_t*>(dyn + L.perm);
-        int32_t* inv = reinterpret_cast<int32_t*>(dyn + L.inv);
-        int32_t* order = reinterpret_cast<int32_t*>(dyn + L.order);
         // the expert table travels while the logits are awaited
         {
             const uint4* src = reinterpret_cast<const uint4*>(a.experts);
@@ -209,30 +197,36 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
             return;
         }
         FATE_TS(1);
-        if (wave < N)
-            wave_softmax_topm(zl + wave * E, E, k, a.r.renorm, ids + wave * k, wv + wave * k, nullptr, nullptr);
-        __syncthreads();
-        if (wave == 0) wave_permute_small(ids, N * k, E, counts, offsets, perm, inv, order);
+        for (int t = wave; t < N; t += kLayerWaves)
+            wave_softmax_topk_rounds(zl + t * E, E, k, a.r.renorm, ids + t * k, wv + t * k);
         __syncthreads();
         const int rwb = wb - nsh;
         const int slot = rwb / a.nkb_r;
         kb = rwb - slot * a.nkb_r;
-        const int e = order[slot];
-        T = counts[e];
-        if (T == 0) return;
-        const int sbeg = offsets[e];
+        int pos;
+        const int e = wave_slot_expert(ids, N * k, E, slot, &T, &pos);     // same in every wave
+        if (e < 0) return;                    // fewer activated experts than slots: no pair, nothing to write
         ex = reinterpret_cast<const fate_qexpert*>(tab)[e];
         bits = a.bits_r; group = a.group_r;
-        if (tid < T) {
-            const int p = perm[sbeg + tid];
-            tokid[tid] = p / k;
-            wtok[tid] = wv[p];
+        if (wave == 0 && pos >= 0) {
+            tokid[pos] = lane / k;
+            wtok[pos] = wv[lane];
+            pairq[pos] = lane;
         }
+        part = a.part_r + (size_t)kb * H;
+        part_stride = (size_t)a.nkb_r * H;    // row of pair q: part + q * part_stride
     }
     const int I = ex.I;
-    if (kb * kLayerNeurons >= I) return;
-    if (ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr) {
-        if (tid == 0) atomicOr(a.status, 1);
+    const bool absent = ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr;
+    if (kb * kLayerNeurons >= I || absent) {
+        // nothing to compute, but the reduction reads this block's rows: they must be zero
+        if (absent && tid == 0) atomicOr(a.status, 1);
+        __syncthreads();
+        for (int idx = tid; idx < T * (H >> 2); idx += kLayerThreads) {
+            const int t = idx / (H >> 2), c = idx - t * (H >> 2);
+            float* row = part + (size_t)(is_shared ? t : pairq[t]) * part_stride;
+            *reinterpret_cast<float4*>(row + 4 * c) = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
         return;
     }
     const int KT = bits == 4 ? 64 : 32;
@@ -240,120 +234,130 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
     const int G = H / group;                 // groups along the reduction dimension of W1 / W3
     const int tiles_k = H / KT;
     const int g_beg = G * wave / kLayerWaves, g_end = G * (wave + 1) / kLayerWaves;
-    gu4_t wt[4];
-    gu16_t sc[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int rb = 2 * kb + (i >> 1);
-        wt[i] = as_global<uint4>((i & 1) ? ex.w3 : ex.w1) + (size_t)rb * tiles_k * 64 + lane;
-        sc[i] = as_global<uint16_t>((i & 1) ? ex.s3 : ex.s1) + (size_t)(rb * 32 + n) * G;
-    }
-    // W2: the column block [kb*64, kb*64+64) of every 32-row block; this wave takes row blocks
-    // wave, wave+8, ... starting from a block-dependent one
-    const int tpn = kLayerNeurons / KT;      // tiles per row block: 1 (int4) or 2 (int8)
+    gu4_t wt[2] = {as_global<uint4>(ex.w1) + (size_t)kb * tiles_k * 64 + lane,
+                   as_global<uint4>(ex.w3) + (size_t)kb * tiles_k * 64 + lane};
+    gu16_t sc[2] = {as_global<uint16_t>(ex.s1) + kb * 32 + n, as_global<uint16_t>(ex.s3) + kb * 32 + n};
+    // W2: the 32 columns [kb*32, kb*32+32) of every 32-row block.  int8: one whole tile per row
+    // block; int4: the half of a 64-column tile that the lanes of one half-wave own (the other
+    // lanes load nothing and their activation operand is zero).  This wave takes every
+    // kLayerWaves-th row block, starting from a block-dependent one.
     const int tiles_k2 = I / KT;
-    const int G2 = I / group, g2 = kb * kLayerNeurons / group;
+    const int g2 = kb * kLayerNeurons / group;
     const int nrb = H >> 5;
     const int nq = (nrb - wave + kLayerWaves - 1) / kLayerWaves;     // row blocks of this wave
     const int qrot = nq > 0 ? wb % nq : 0;
-    gu4_t w2 = as_global<uint4>(ex.w2) + (size_t)kb * tpn * 64 + lane;
-    gu16_t s2 = as_global<uint16_t>(ex.s2) + (size_t)n * G2 + g2;
+    const int kt2 = bits == 4 ? (kb >> 1) : kb;
+    const bool mine = bits == 4 ? (half == (kb & 1)) : true;
+    gu4_t w2 = as_global<uint4>(ex.w2) + (size_t)kt2 * 64 + lane;
+    gu16_t s2 = as_global<uint16_t>(ex.s2) + (size_t)g2 * H + n;
     auto rb_of = [&](int q) { int qq = q + qrot; if (qq >= nq) qq -= nq; return wave + kLayerWaves * qq; };
+    // sigmoid gate of a shared expert (after the weight requests have gone out)
+    auto shared_gate = [&]() {
+        if (a.shared_gate != nullptr) {
+            for (int t = wave; t < N; t += kLayerWaves) {
+                const float g = wave_sigmoid_dot_bf16(reinterpret_cast<const uint4*>(a.r.x) + (size_t)t * nvec,
+                                                      reinterpret_cast<const uint4*>(a.shared_gate), nvec);
+                if (lane == 0) wtok[t] = g;
+            }
+        } else if (tid < N) {
+            wtok[tid] = 1.0f;
+        }
+    };
 
 #define FATE_LAYER_BODY(BITS, TPG)                                                                        \
     {                                                                                                     \
-        constexpr int S = QFmt<BITS>::MSTEPS, TPN = kLayerNeurons / QFmt<BITS>::KT;                       \
+        constexpr int S = QFmt<BITS>::MSTEPS;                                                             \
         if (defer_x) load_x();                                                                            \
-        TileRing<4, kUpRing, TPG> ring;                                                                   \
-        ring_start<4, kUpRing, TPG>(ring, wt, sc, g_beg, g_end);                                          \
-        /* W2 tiles behind them */                                                                        \
-        uint4 draw[kDownRing];                                                                            \
-        uint32_t dsc[kDownRing / TPN];                                                                    \
-        const int nu = nq * TPN;                                                                          \
-        _Pragma("unroll")                                                                                 \
-        for (int u = 0; u < kDownRing; ++u) {                                                             \
-            if (u < nu) {                                                                                 \
-                const int rb = rb_of(u / TPN);                                                            \
-                draw[u] = w2[((size_t)rb * tiles_k2 + (u % TPN)) * 64];                                   \
-                if (u % TPN == 0) dsc[u / TPN] = s2[(size_t)rb * 32 * G2];                                \
-            }                                                                                             \
-        }                                                                                                 \
-        if (defer_x) store_x(true);                                                                       \
-        /* y must have been cleared before this block adds to it: every logit of this layer's gate  */   \
-        /* carries that guarantee (a routed block has waited for them already)                      */   \
-        if (is_shared && !wait_logits(a.zq, N * E, tag, reinterpret_cast<float*>(dyn + L.zl))) {          \
-            if (tid == 0) atomicOr(a.status, 2);                                                          \
-            return;                                                                                       \
-        }                                                                                                 \
-        __syncthreads();          /* x, token ids and weights are in LDS */                               \
-        FATE_TS(2);                                                                                       \
-        float out[4][4];                                                                                  \
-        _Pragma("unroll")                                                                                 \
-        for (int i = 0; i < 4; ++i)                                                                       \
+        TileRing<2, kUpRing, TPG> ring;                                                                   \
+        ring_start<2, kUpRing, TPG>(ring, wt, sc, I, g_beg, g_end);                                          \
+        /* W2 pieces behind them: two register sets of kDownRing pieces, filled in turn */             \
+        uint4 dA[kDownRing], dB[kDownRing];                                                               \
+        uint32_t sA[kDownRing], sB[kDownRing];                                                            \
+        auto issue = [&](uint4 (&d)[kDownRing], uint32_t (&sd)[kDownRing], int chunk) {                   \
             _Pragma("unroll")                                                                             \
-            for (int j = 0; j < 4; ++j) out[i][j] = 0.f;                                                  \
+            for (int u = 0; u < kDownRing; ++u) {                                                         \
+                const int q = chunk * kDownRing + u;                                                      \
+                d[u] = make_uint4(0, 0, 0, 0);                                                            \
+                if (q < nq) {                                                                             \
+                    const int rb = rb_of(q);                                                              \
+                    if (mine) d[u] = w2[(size_t)rb * tiles_k2 * 64];                                      \
+                    sd[u] = s2[rb * 32];                                                                  \
+                }                                                                                         \
+            }                                                                                             \
+        };                                                                                                \
+        issue(dA, sA, 0);                                                                                 \
+        FATE_TS(5);                                                                                       \
+        if (defer_x) store_x(true);                                                                       \
+        if (is_shared) shared_gate();                                                                     \
+        lds_barrier();            /* x, token ids and weights are in LDS */                               \
+        FATE_TS(2);                                                                                       \
+        float out[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};                                   \
         const int arow = n < T ? tokid[n] : N;                                                            \
-        ring_run<BITS, TPG, 4, kUpRing>(ring, wt, sc, g_beg, g_end,                                       \
+        ring_run<BITS, TPG, 2, kUpRing>(ring, wt, sc, I, g_beg, g_end,                                      \
                                         xs + arow * ldx + half * (QFmt<BITS>::KT / 2), 0, out);           \
+        issue(dB, sB, 1);         /* the ring's registers are free now */                                 \
         FATE_TS(3);                                                                                       \
         _Pragma("unroll")                                                                                 \
-        for (int i = 0; i < 4; ++i)                                                                       \
+        for (int i = 0; i < 2; ++i)                                                                       \
             _Pragma("unroll")                                                                             \
             for (int j = 0; j < 4; ++j)                                                                   \
-                if (4 * half + j < ntp) red[((wave * 4 + i) * ntp + 4 * half + j) * 32 + n] = out[i][j];  \
-        __syncthreads();                                                                                  \
+                if (4 * half + j < ntp) red[((wave * 2 + i) * ntp + 4 * half + j) * 32 + n] = out[i][j];  \
+        lds_barrier();                                                                                    \
         for (int idx = tid; idx < T * kLayerNeurons; idx += kLayerThreads) {                              \
-            const int t = idx >> 6, nn = idx & 63, sel = nn >> 5, n32 = nn & 31;                          \
+            const int t = idx >> 5, n32 = idx & 31;                                                       \
             float a1 = 0.f, a3 = 0.f;                                                                     \
             _Pragma("unroll")                                                                             \
             for (int w = 0; w < kLayerWaves; ++w) {                                                       \
-                a1 += red[((w * 4 + 2 * sel) * ntp + t) * 32 + n32];                                      \
-                a3 += red[((w * 4 + 2 * sel + 1) * ntp + t) * 32 + n32];                                  \
+                a1 += red[((w * 2) * ntp + t) * 32 + n32];                                                \
+                a3 += red[((w * 2 + 1) * ntp + t) * 32 + n32];                                            \
             }                                                                                             \
-            hs[t * kHsLd + nn] = (_Float16)(a1 / (1.0f + expf(-a1)) * a3);                                \
+            hs[t * kHsLd + n32] = (_Float16)(a1 / (1.0f + expf(-a1)) * a3);                               \
         }                                                                                                 \
-        __syncthreads();                                                                                  \
+        lds_barrier();                                                                                    \
         FATE_TS(4);                                                                                       \
-        /* down projection of the 64 values of h */                                                       \
-        const _Float16* ha = hs + (n < T ? n : kTokPass) * kHsLd + half * (QFmt<BITS>::KT / 2);           \
+        /* down projection of the 32 values of h: int8 spreads them over both half-waves (16 each),  */  \
+        /* int4 keeps them in the half-wave that owns the columns                                    */  \
+        const bool arow_ok = n < T && mine;                                                               \
+        const _Float16* ha = hs + (arow_ok ? n : kTokPass) * kHsLd + (BITS == 8 ? half * 16 : 0);         \
         float wj[4];                                                                                      \
-        int tj[4];                                                                                        \
+        float* rowj[4];                                                                                   \
         _Pragma("unroll")                                                                                 \
         for (int j = 0; j < 4; ++j) {                                                                     \
             const int t = 4 * half + j;                                                                   \
             wj[j] = t < T ? wtok[t] : 0.f;                                                                \
-            tj[j] = t < T ? tokid[t] : 0;                                                                 \
+            rowj[j] = part + (size_t)(t < T ? (is_shared ? t : pairq[t]) : 0) * part_stride + n;          \
         }                                                                                                 \
+        f16x8_t av[S];                                                                                    \
+        _Pragma("unroll")                                                                                 \
+        for (int st = 0; st < S; ++st) av[st] = *reinterpret_cast<const f16x8_t*>(ha + 8 * st);           \
         const f32x16_t zero = f32x16_zero();                                                              \
-        for (int base = 0; base < nu; base += kDownRing) {                                                \
+        auto process = [&](uint4 (&d)[kDownRing], uint32_t (&sd)[kDownRing], int chunk) {                 \
             _Pragma("unroll")                                                                             \
-            for (int uq = 0; uq < kDownRing / TPN; ++uq) {                                                \
-                if (base + uq * TPN < nu) {                                                               \
-                    const int q = (base + uq * TPN) / TPN;                                                \
+            for (int u = 0; u < kDownRing; ++u) {                                                         \
+                const int q = chunk * kDownRing + u;                                                      \
+                if (q < nq) {                                                                             \
                     const int rb = rb_of(q);                                                              \
-                    const float s = half_bits_to_float(dsc[uq]);                                          \
-                    const int qn = q + kDownRing / TPN;                                                   \
-                    if (qn < nq) dsc[uq] = s2[(size_t)rb_of(qn) * 32 * G2];                               \
+                    const float s = half_bits_to_float(sd[u]);                                            \
+                    f16x8_t bq[S];                                                                        \
+                    codes_to_f16<BITS>(d[u], bq);                                                         \
                     f32x16_t acc;                                                                         \
                     _Pragma("unroll")                                                                     \
-                    for (int sub = 0; sub < TPN; ++sub) {                                                 \
-                        const int u = uq * TPN + sub;                                                     \
-                        f16x8_t bq[S];                                                                    \
-                        codes_to_f16<BITS>(draw[u], bq);                                                  \
-                        if (qn < nq) draw[u] = w2[((size_t)rb_of(qn) * tiles_k2 + sub) * 64];             \
-                        _Pragma("unroll")                                                                 \
-                        for (int st = 0; st < S; ++st) {                                                  \
-                            const f16x8_t av = *reinterpret_cast<const f16x8_t*>(                         \
-                                ha + sub * QFmt<BITS>::KT + 8 * st);                                      \
-                            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(                                 \
-                                av, bq[st], (sub == 0 && st == 0) ? zero : acc, 0, 0, 0);                 \
-                        }                                                                                 \
-                    }                                                                                     \
+                    for (int st = 0; st < S; ++st)                                                        \
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[st], bq[st], st == 0 ? zero : acc, \
+                                                                     0, 0, 0);                            \
                     _Pragma("unroll")                                                                     \
                     for (int j = 0; j < 4; ++j)                                                           \
-                        if (4 * half + j < T)                                                             \
-                            atomicAdd(a.y + (size_t)tj[j] * H + rb * 32 + n, wj[j] * (s * acc[j]));       \
+                        if (4 * half + j < T) rowj[j][rb * 32] = wj[j] * (s * acc[j]);                    \
                 }                                                                                         \
+            }                                                                                             \
+        };                                                                                                \
+        const int nchunk = (nq + kDownRing - 1) / kDownRing;                                              \
+        for (int c = 0; c < nchunk; c += 2) {                                                             \
+            process(dA, sA, c);                                                                           \
+            if (c + 2 < nchunk) issue(dA, sA, c + 2);                                                     \
+            if (c + 1 < nchunk) {                                                                         \
+                process(dB, sB, c + 1);                                                                   \
+                if (c + 3 < nchunk) issue(dB, sB, c + 3);                                                 \
             }                                                                                             \
         }                                                                                                 \
     }
@@ -361,7 +365,7 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
 #undef FATE_LAYER_BODY
 }
 
-__global__ __launch_bounds__(kLayerThreads) void moe_layer_decode_kernel(LayerArgs a) {
+__global__ __launch_bounds__(kLayerThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void moe_layer_decode_kernel(LayerArgs a) {
     extern __shared__ uint4 smem[];
     __shared__ FusedRouteSmem rsm;
     char* dyn = reinterpret_cast<char*>(smem);
@@ -373,16 +377,51 @@ __global__ __launch_bounds__(kLayerThreads) void moe_layer_decode_kernel(LayerAr
     else work_role(a, b - a.nb_route, tag, dyn);
     // the workgroup that leaves last opens the next epoch
     __syncthreads();
-    FATE_TS(7);
+    FATE_TS(6);
     if (threadIdx.x == 0 && atomicAdd(a.sync + 1, 1) == (int)gridDim.x - 1) {
         st_dev(a.sync + 1, 0);
         st_dev(a.sync, (int32_t)tag);
     }
 }
 
-__global__ void layer_f32_to_bf16_kernel(const float* __restrict__ src, uint16_t* __restrict__ dst, long long n) {
-    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) dst[i] = (uint16_t)f32_to_bf16_bits(src[i]);
+// y[t] = sum over the k pairs of token t and the 32-neuron blocks of their experts, plus the
+// shared experts' blocks.  A workgroup owns 32 consecutive outputs of one token; one wave load
+// covers two partial rows (a half-wave each), the 16 waves take rows in turn with all their
+// loads in flight at once, and the partial sums meet in LDS.  Deterministic.
+constexpr int kReduceWaves = 16;
+constexpr int kReduceMaxLoads = 16;      // rows per half-wave: covers 2 * 16 * 16 = 512 partial rows
+__global__ __launch_bounds__(64 * kReduceWaves) void layer_reduce_kernel(LayerArgs a) {
+    __shared__ float red[kReduceWaves][32];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 31, half = lane >> 5;
+    const int H = a.r.H, N = a.r.N, k = a.r.k;
+    const int chunks = H >> 5;
+    const int t = blockIdx.x / chunks, c0 = (blockIdx.x - t * chunks) * 32 + n;
+    const int nr = k * a.nkb_r, ns = a.n_shared * a.nkb_s, nrows = nr + ns;
+    const float* base_r = a.part_r + (size_t)(t * k) * a.nkb_r * H + c0;     // pairs t*k .. t*k+k-1, their blocks
+    const float* base_s = a.part_s + (size_t)t * H + c0;
+    float acc = 0.f;
+    for (int i0 = 2 * wave + half; i0 < nrows; i0 += 2 * kReduceWaves * kReduceMaxLoads) {
+        float v[kReduceMaxLoads];
+#pragma unroll
+        for (int j = 0; j < kReduceMaxLoads; ++j) {
+            const int i = i0 + 2 * kReduceWaves * j;
+            v[j] = 0.f;
+            if (i < nrows) v[j] = i < nr ? base_r[(size_t)i * H] : base_s[(size_t)(i - nr) * N * H];
+        }
+#pragma unroll
+        for (int j = 0; j < kReduceMaxLoads; ++j) acc += v[j];
+    }
+    acc += __shfl_xor(acc, 32, 64);
+    if (half == 0) red[wave][n] = acc;
+    __syncthreads();
+    if (wave == 0 && half == 0) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < kReduceWaves; ++w) s += red[w][n];
+        if (a.y_is_fp32) static_cast<float*>(a.y)[(size_t)t * H + c0] = s;
+        else static_cast<uint16_t*>(a.y)[(size_t)t * H + c0] = (uint16_t)f32_to_bf16_bits(s);
+    }
 }
 
 #ifdef FATE_PROBE
@@ -391,7 +430,7 @@ extern "C" int fate_debug_probe(unsigned long long* host_out, int nblocks) {
 }
 #endif
 
-fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArgs a, void* y_out) {
+fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArgs a) {
     if (d.N < 1 || d.N > kLayerMaxN || d.N * d.k > kLayerMaxP)
         FATE_FAIL(FATE_ESHAPE, "fused layer: need 1 <= N <= %d and N*k <= %d (N = %d, k = %d)", kLayerMaxN,
                   kLayerMaxP, d.N, d.k);
@@ -408,18 +447,13 @@ fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArg
     }
     const int rows = (a.r.Wg2 ? 2 : 1) * d.E;
     a.nb_route = (rows + kLayerWaves - 1) / kLayerWaves;
-    a.nb_zero = (d.E + kLayerWaves - 1) / kLayerWaves;        // the workgroups that hold this layer's gate rows
     a.nkb_r = d.I_max / kLayerNeurons;
     a.nkb_s = d.n_shared ? d.I_shared_max / kLayerNeurons : 0;
     a.nact = min(d.E, d.N * d.k);
     const int grid = a.nb_route + d.n_shared * a.nkb_s + a.nact * a.nkb_r;
     moe_layer_decode_kernel<<<grid, kLayerThreads, L.bytes, st>>>(a);
+    layer_reduce_kernel<<<d.N * (d.H / 32), 64 * kReduceWaves, 0, st>>>(a);
     FATE_HIP(hipGetLastError());
-    if (!d.y_is_fp32) {
-        const long long n = (long long)d.N * d.H;
-        layer_f32_to_bf16_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(a.y, static_cast<uint16_t*>(y_out), n);
-        FATE_HIP(hipGetLastError());
-    }
     return FATE_OK;
 }
 

@@ -36,9 +36,33 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const uint32_t* __rest
     }
 }
 
+// [rows, groups] -> [groups, rows], one thread per element
+__global__ __launch_bounds__(256) void pack_scales_kernel(const uint16_t* __restrict__ src,
+                                                          uint16_t* __restrict__ dst, int rows, int groups) {
+    const long long o = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (o >= (long long)rows * groups) return;
+    const int g = (int)(o / rows), r = (int)(o - (long long)g * rows);
+    dst[o] = src[(long long)r * groups + g];
+}
+
 }  // namespace fate
 
 using namespace fate;
+
+extern "C" fate_status fate_pack_scales(void* stream, const void* canonical_dev, int rows, int groups,
+                                        void* packed_dev) {
+    if (rows < 1 || groups < 1) FATE_FAIL(FATE_ESHAPE, "rows = %d, groups = %d must be positive", rows, groups);
+    FATE_CHECK_PTR(canonical_dev);
+    FATE_CHECK_PTR(packed_dev);
+    if (canonical_dev == packed_dev) FATE_FAIL(FATE_EINVAL, "packing is out of place");
+    const long long n = (long long)rows * groups;
+    const long long grid = (n + 255) / 256;
+    if (grid > 0x7fffffffLL) FATE_FAIL(FATE_ESHAPE, "matrix too large");
+    pack_scales_kernel<<<(unsigned)grid, 256, 0, static_cast<hipStream_t>(stream)>>>(
+        static_cast<const uint16_t*>(canonical_dev), static_cast<uint16_t*>(packed_dev), rows, groups);
+    FATE_HIP(hipGetLastError());
+    return FATE_OK;
+}
 
 extern "C" fate_status fate_pack_weight(void* stream, const void* canonical_dev, int rows, int K, int bits,
                                         void* packed_dev) {

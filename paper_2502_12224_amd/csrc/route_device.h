@@ -163,6 +163,109 @@ __device__ __forceinline__ void wave_permute_small(const int32_t* ids, int P, in
     else wave_permute_small_ns<4>(ids, P, E, counts, offsets, perm, inv_perm, order);
 }
 
+// The m largest of E logits by m rounds of arg-max: same ids, order and
+// weights as wave_softmax_topm, cheaper when m is a handful (no loop over E).
+template <int NS>
+__device__ __forceinline__ void wave_softmax_topk_rounds_ns(const float* z, int E, int m, int renorm,
+                                                            int32_t* ids_out, float* w_out) {
+    const int lane = threadIdx.x & 63;
+    float v[NS];
+    float lmax = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        const int e = lane + 64 * i;
+        float t = (e < E) ? z[e] : -INFINITY;
+        if (t != t) t = -INFINITY;
+        v[i] = t;
+        lmax = fmaxf(lmax, t);
+    }
+    const float zmax = wave_max(lmax);
+    float p[NS];
+    float lsum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        p[i] = (lane + 64 * i < E) ? __expf(v[i] - zmax) : 0.f;
+        lsum += p[i];
+    }
+    const float inv = 1.0f / wave_sum(lsum);
+    int myrank[NS];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        p[i] *= inv;
+        myrank[i] = -1;
+    }
+    for (int r = 0; r < m; ++r) {
+        float lbest = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+            if (lane + 64 * i < E && myrank[i] < 0) lbest = fmaxf(lbest, v[i]);
+        const float vbest = wave_max(lbest);
+        int found = -1;
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            const unsigned long long ball = __ballot(lane + 64 * i < E && myrank[i] < 0 && v[i] == vbest);
+            if (found < 0 && ball) found = 64 * i + __ffsll((long long)ball) - 1;
+        }
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+            if (found == lane + 64 * i) myrank[i] = r;
+    }
+    float wsel = 0.f;
+#pragma unroll
+    for (int i = 0; i < NS; ++i)
+        if (myrank[i] >= 0) wsel += p[i];
+    const float scale = renorm ? 1.0f / wave_sum(wsel) : 1.0f;
+#pragma unroll
+    for (int i = 0; i < NS; ++i)
+        if (myrank[i] >= 0) {
+            ids_out[myrank[i]] = lane + 64 * i;
+            w_out[myrank[i]] = p[i] * scale;
+        }
+}
+
+__device__ __forceinline__ void wave_softmax_topk_rounds(const float* z, int E, int m, int renorm,
+                                                         int32_t* ids_out, float* w_out) {
+    if (E <= 64) wave_softmax_topk_rounds_ns<1>(z, E, m, renorm, ids_out, w_out);
+    else if (E <= 128) wave_softmax_topk_rounds_ns<2>(z, E, m, renorm, ids_out, w_out);
+    else wave_softmax_topk_rounds_ns<4>(z, E, m, renorm, ids_out, w_out);
+}
+
+// One wavefront, P <= 64 (token, expert) pairs in ids[]: the expert at position
+// `slot` of the order (pair count descending, id ascending) - what
+// expert_order[slot] of the permutation holds for an activated expert - or -1
+// when fewer experts are activated.  *T_out = its pair count; a lane whose pair
+// belongs to it gets *pos_out = the pair's position among them (pair order),
+// other lanes -1.  The result is the same in every lane.
+__device__ __forceinline__ int wave_slot_expert(const int32_t* ids, int P, int E, int slot, int* T_out,
+                                                int* pos_out) {
+    const int lane = threadIdx.x & 63;
+    const int ei = (lane < P) ? ids[lane] : -1;
+    const bool valid = lane < P && ei >= 0 && ei < E;
+    const int key = valid ? ei : -1;
+    int cnt = 0, before = 0;
+    for (int src = 0; src < P; ++src) {
+        const int ej = lane_bcast(key, src);
+        const bool same = valid && ej == key;
+        cnt += same;
+        before += same && src < lane;
+    }
+    const int first = valid && before == 0;
+    int rank = 0;
+    for (int src = 0; src < P; ++src) {
+        const int cj = lane_bcast(cnt, src), ej = lane_bcast(key, src), fj = lane_bcast(first, src);
+        rank += fj && ((cj > cnt) || (cj == cnt && ej < key));
+    }
+    const unsigned long long ball = __ballot(first && rank == slot);
+    *T_out = 0;
+    *pos_out = -1;
+    if (!ball) return -1;
+    const int L = __ffsll((long long)ball) - 1;
+    const int e = lane_bcast(key, L);
+    *T_out = lane_bcast(cnt, L);
+    if (valid && key == e) *pos_out = before;
+    return e;
+}
+
 // Per-lane mask of the lanes in this wave that hold the same key (valid lanes only).
 __device__ __forceinline__ unsigned long long wave_match(int key, bool valid, int nbits) {
     unsigned long long mask = __ballot(valid);
