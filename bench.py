@@ -180,8 +180,8 @@ def bench_decode(args):
     x_in.copy_(xs[3]); graph.replay(); torch.cuda.synchronize()
     assert np.array_equal(bufs[5].ids.cpu().numpy(), t_ids[3, 5]), "graph replay diverged from the chain"
 
-    # roofline of the dominant kernel: the one-launch layer kernel streams every byte the layer needs
-    # (activated routed experts, the shared expert, both gate matrices, x, y)
+    # roofline of the dominant kernel pair (the layer kernel and its small reduction): they stream every
+    # byte the layer needs (activated routed experts, the shared expert, both gate matrices, x, y)
     layer_bytes = cfg.k * expert_bytes(H, cfg.I, cfg.bits, cfg.group) + \
         cfg.n_shared * expert_bytes(H, cfg.I_shared, cfg.shared_bits, cfg.group) + 2 * E * H * 2 + N * H * (2 + 4)
     reps = 20
@@ -224,7 +224,7 @@ def bench_decode(args):
                    "layer_hbm_frac": layer_bytes / (ms_per_step * 1e-3 / L) / 1e9 / HBM_PEAK_GBS,
                    "prediction_accuracy_topk": acc_k, "prediction_recall_topm": rec_m, "m": cfg.m,
                    "cache_hit_rate": tot["hits"] / max(1, tot["hits"] + tot["misses"])},
-        "roofline": {"bound": "hbm", "kernel": "moe_layer_decode_kernel", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "moe_layer_decode_kernel + layer_reduce_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "bytes_per_launch": layer_bytes, "us_per_launch": kern_us},
         "cpu_baseline": cpu,

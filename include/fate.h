@@ -189,13 +189,15 @@ fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, const void* x_b
                            void* y, void* workspace, size_t workspace_bytes);
 
 /* ------------------------------------------------------------------------
- * Whole decode-side MoE layer in one launch (1 <= N <= 8, N*k <= 64):
- * fate_gate_route + fate_cross_layer_predict + fate_permute +
- * fate_moe_ffn_q (section 4.1 steps 1-2, 5-6 of one layer), with the same
- * results as those calls: routing outputs bit for bit, y up to the order of
- * its fp32 additions.  The weight stream of the shared experts starts while
- * the gate is still being evaluated, and that of the down projections
- * before the up projections have finished.
+ * Whole decode-side MoE layer in one call (1 <= N <= 8, N*k <= 64; two
+ * launches: the layer kernel and a small reduction): fate_gate_route +
+ * fate_cross_layer_predict + fate_permute + fate_moe_ffn_q (section 4.1
+ * steps 1-2, 5-6 of one layer), with the same results as those calls:
+ * routing outputs bit for bit, y up to the order of its fp32 additions.  The
+ * weight stream of the shared experts starts while the gate is still being
+ * evaluated; a work group owns 32 intermediate neurons of one expert, does
+ * their up projection and multiplies the result into its columns of the down
+ * projection, and leaves a partial output row that the reduction adds up.
  *   out: device pointers for every routing output, sized as in the separate
  *        calls; pred_* may be NULL when Wg_next is NULL (last layer).
  *   d->mode must be 0 or 1, d->phases 0.

@@ -9,7 +9,7 @@ LIB = os.path.join(HERE, "libfate.so")
 SOURCES = ["api.cpp", "route.hip", "pack.hip", "ffn.hip", "ffn_decode.hip", "layer_decode.hip", "ffn_prefill.hip", "cache.cpp",
            "cache_hip.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = (["-DFATE_PROBE"] if os.environ.get("FATE_PROBE") else []) + ([f"-DFATE_EXP={os.environ['FATE_EXP']}"] if os.environ.get("FATE_EXP") else []) + ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+FLAGS = (["-DFATE_PROBE"] if os.environ.get("FATE_PROBE") else []) + ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-result", "-Wno-unknown-warning-option"]
 
 

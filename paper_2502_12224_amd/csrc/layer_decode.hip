@@ -31,9 +31,6 @@
 
 namespace fate {
 
-#ifndef FATE_EXP
-#define FATE_EXP 0
-#endif
 constexpr int kSpinMax = 1 << 18;
 constexpr int kUpRing = 8;        // tiles in flight per matrix per wave
 constexpr int kDownRing = 8;      // W2 pieces in flight per wave
@@ -79,7 +76,7 @@ __device__ __forceinline__ bool wait_logits(const unsigned long long* zq, int n,
 
 // LDS carve of a work block (bytes from the start of dynamic shared memory)
 struct WorkLds {
-    int xs, hs, red, tab, zl, ids, w, counts, offsets, perm, inv, order, tokid, wtok, bytes;
+    int xs, hs, red, tab, zl, ids, w, pairq, tokid, wtok, bytes;
 };
 __host__ __device__ inline WorkLds work_lds(int N, int H, int E, int k) {
     auto up = [](int v) { return (v + 15) & ~15; };
@@ -94,11 +91,7 @@ __host__ __device__ inline WorkLds work_lds(int N, int H, int E, int k) {
     L.zl = off; off += up(2 * N * E * 4);
     L.ids = off; off += up(P * 4);
     L.w = off; off += up(P * 4);
-    L.counts = off; off += up(E * 4);
-    L.offsets = off; off += up((E + 1) * 4);
-    L.perm = off; off += up(P * 4);
-    L.inv = off; off += up(P * 4);
-    L.order = off; off += up(E * 4);
+    L.pairq = off; off += up(kTokPass * 4);
     L.tokid = off; off += up(kTokPass * 4);
     L.wtok = off; off += up(kTokPass * 4);
     L.bytes = off;
@@ -169,7 +162,7 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
 
     fate_qexpert ex;
     int kb, T, bits, group;
-    int32_t* pairq = reinterpret_cast<int32_t*>(dyn + L.perm);   // routed: original pair index of each of the T rows
+    int32_t* pairq = reinterpret_cast<int32_t*>(dyn + L.pairq);  // routed: original pair index of each of the T rows
     float* part;                  // where this block's weighted partial output rows go
     size_t part_stride;           // floats between the rows of consecutive tokens of this block
     if (is_shared) {
