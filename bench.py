@@ -34,6 +34,18 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def measured_traffic(name):
+    """HBM bytes per launch from the counter runs summarised under profiles/ (None if not measured)."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def expert_bytes(H, I, bits, group):
     """Algorithmic bytes of one expert: codes + fp16 scales of W1, W3, W2."""
     return 3 * (H * I * bits // 8 + H * I // group * 2)
@@ -200,6 +212,16 @@ def bench_decode(args):
     log(f"[bench] layer kernel {kern_us:.2f} us/launch ({achieved:.0f} GB/s), layer algorithmic bytes "
         f"{layer_bytes / 1e6:.1f} MB")
 
+    if args.calibrate_copy:
+        # a plain device copy of known size, so that a counter run of this command can be scaled:
+        # 5 copies of 1 GiB (reads 1 GiB, writes 1 GiB each)
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     cpu = None
     if not args.no_cpu_baseline:
         ncores = len(os.sched_getaffinity(0))
@@ -225,7 +247,8 @@ def bench_decode(args):
                    "prediction_accuracy_topk": acc_k, "prediction_recall_topm": rec_m, "m": cfg.m,
                    "cache_hit_rate": tot["hits"] / max(1, tot["hits"] + tot["misses"])},
         "roofline": {"bound": "hbm", "kernel": "moe_layer_decode_kernel + layer_reduce_kernel", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic("decode_qwen_b1_traffic.txt"),
                      "bytes_per_launch": layer_bytes, "us_per_launch": kern_us},
         "cpu_baseline": cpu,
     }
@@ -486,6 +509,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=None, help="default 32 (decode) / 2 (prefill)")
     ap.add_argument("--workload", default="qwen_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="decode: also run five 1 GiB device copies (reference for hardware-counter runs)")
     ap.add_argument("--n-max", type=int, default=None,
                     help="offload workloads: cap on prefetched experts per layer (default: batch * m, at most E)")
     args = ap.parse_args()
