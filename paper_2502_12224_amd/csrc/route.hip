@@ -67,6 +67,74 @@ __global__ __launch_bounds__(256) void route_rows_kernel(const uint16_t* __restr
     }
 }
 
+// Many tokens (prefill): the gate is a small GEMM, z[N,E] = x[N,H] . Wg[E,H]^T, done on the matrix
+// cores.  A workgroup owns 32 tokens; wave w takes expert tile (w & 1) of a pair of 32-expert
+// tiles and half (w >> 1) of the reduction dimension.  Both operands are row-major with the
+// reduction dimension contiguous, which is the register layout of v_mfma_f32_32x32x16_bf16 as it
+// stands: lane (half, r) holds 8 consecutive elements of row r - 16 bytes straight from memory.
+// bf16 products are exact in fp32; accumulation is fp32.  The logits meet in LDS, then one wave
+// per token does softmax and selection as in the other kernels.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float rf32x16_t;
+constexpr int kGemmTok = 32;
+
+__global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restrict__ x,
+                                                         const uint16_t* __restrict__ Wg,
+                                                         const float* __restrict__ bias, int N, int H, int E,
+                                                         int m, int renorm, int32_t* __restrict__ ids,
+                                                         float* __restrict__ w, float* __restrict__ probs,
+                                                         int32_t* __restrict__ pop) {
+    extern __shared__ float zs[];                 // [2 halves][32 tokens][Epad]
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 31, half = lane >> 5;
+    const int etile = wave & 1, khalf = wave >> 1;
+    const int Epad = (E + 63) & ~63;
+    const int t0 = blockIdx.x * kGemmTok;
+    const int tok = t0 + n;
+    const int kbeg = khalf * (H >> 1), kend = kbeg + (H >> 1);
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)(tok < N ? tok : 0) * H) + half;
+    for (int e0 = 0; e0 < E; e0 += 64) {
+        const int e = e0 + etile * 32 + n;
+        const uint4* wr = reinterpret_cast<const uint4*>(Wg + (size_t)(e < E ? e : 0) * H) + half;
+        rf32x16_t acc;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+        for (int k = kbeg; k < kend; k += 16 * 8) {
+            uint4 av[8], bv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int kk = k + 16 * u;
+                const bool in = kk < kend;
+                av[u] = (in && tok < N) ? xr[kk >> 3] : zero4;
+                bv[u] = (in && e < E) ? wr[kk >> 3] : zero4;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av[u]),
+                                                              __builtin_bit_cast(bf16x8_t, bv[u]), acc, 0, 0, 0);
+        }
+        // lane (half, n) holds expert column n, token rows 8*(j/4) + 4*half + j%4
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int t = 8 * (j >> 2) + 4 * half + (j & 3);
+            zs[((size_t)khalf * kGemmTok + t) * Epad + e0 + etile * 32 + n] = acc[j];
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kGemmTok * E; i += 256) {
+        const int t = i / E, e = i - t * E;
+        zs[(size_t)t * Epad + e] += zs[((size_t)kGemmTok + t) * Epad + e] + (bias ? bias[e] : 0.f);
+    }
+    __syncthreads();
+    for (int t = wave; t < kGemmTok; t += 4) {
+        const int tk = t0 + t;
+        if (tk < N)
+            wave_softmax_topm(zs + (size_t)t * Epad, E, m, renorm, ids + (size_t)tk * m, w + (size_t)tk * m,
+                              probs ? probs + (size_t)tk * E : nullptr, pop);
+    }
+}
+
 __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict__ ids, int P, int E,
                                                        int32_t* counts, int32_t* offsets, int32_t* perm,
                                                        int32_t* inv_perm, int32_t* order) {
@@ -120,12 +188,20 @@ static int pick_tpw(int N, int H, int E) {
 static fate_status launch_route_rows(hipStream_t st, const void* x, const void* Wg, const float* bias, int N,
                                      int H, int E, int m, int renorm, int32_t* ids, float* w, float* probs,
                                      int32_t* pop) {
+    auto xs = static_cast<const uint16_t*>(x);
+    auto ws = static_cast<const uint16_t*>(Wg);
+    if (N >= 64 && H % 256 == 0) {
+        // prefill-sized batches: gate GEMM on the matrix cores
+        const size_t lds_g = (size_t)2 * kGemmTok * ((E + 63) & ~63) * sizeof(float);
+        route_mfma_kernel<<<(N + kGemmTok - 1) / kGemmTok, 256, lds_g, st>>>(xs, ws, bias, N, H, E, m, renorm, ids, w,
+                                                                          probs, pop);
+        FATE_HIP(hipGetLastError());
+        return FATE_OK;
+    }
     const int tpw = pick_tpw(N, H, E);
     const size_t lds = (size_t)4 * tpw * (2 * (size_t)H + 4 * (size_t)E);
     if (lds > 65536) FATE_FAIL(FATE_ESHAPE, "H = %d, E = %d need %zu bytes of LDS (> 64 KiB)", H, E, lds);
     const int grid = (N + 4 * tpw - 1) / (4 * tpw);
-    auto xs = static_cast<const uint16_t*>(x);
-    auto ws = static_cast<const uint16_t*>(Wg);
     switch (tpw) {
         case 4: route_rows_kernel<4><<<grid, 256, lds, st>>>(xs, ws, bias, N, H, E, m, renorm, ids, w, probs, pop); break;
         case 2: route_rows_kernel<2><<<grid, 256, lds, st>>>(xs, ws, bias, N, H, E, m, renorm, ids, w, probs, pop); break;
