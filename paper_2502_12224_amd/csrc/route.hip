@@ -68,8 +68,8 @@ __global__ __launch_bounds__(256) void route_rows_kernel(const uint16_t* __restr
 }
 
 // Many tokens (prefill): the gate is a small GEMM, z[N,E] = x[N,H] . Wg[E,H]^T, done on the matrix
-// cores.  A workgroup owns 32 tokens; wave w takes expert tile (w & 1) of a pair of 32-expert
-// tiles and half (w >> 1) of the reduction dimension.  Both operands are row-major with the
+// cores.  A workgroup (8 waves) owns 32 tokens; wave w takes expert tile (w & 1) of a pair of
+// 32-expert tiles and quarter (w >> 1) of the reduction dimension; the quarters add up in LDS.  Both operands are row-major with the
 // reduction dimension contiguous, which is the register layout of v_mfma_f32_32x32x16_bf16 as it
 // stands: lane (half, r) holds 8 consecutive elements of row r - 16 bytes straight from memory.
 // bf16 products are exact in fp32; accumulation is fp32.  The logits meet in LDS, then one wave
@@ -78,20 +78,21 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float rf32x16_t;
 constexpr int kGemmTok = 32;
 
-__global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restrict__ x,
+__global__ __launch_bounds__(512) void route_mfma_kernel(const uint16_t* __restrict__ x,
                                                          const uint16_t* __restrict__ Wg,
                                                          const float* __restrict__ bias, int N, int H, int E,
                                                          int m, int renorm, int32_t* __restrict__ ids,
                                                          float* __restrict__ w, float* __restrict__ probs,
                                                          int32_t* __restrict__ pop) {
-    extern __shared__ float zs[];                 // [2 halves][32 tokens][Epad]
+    extern __shared__ float zs[];                 // [4 quarters][32 tokens][Epad]
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, half = lane >> 5;
-    const int etile = wave & 1, khalf = wave >> 1;
+    const int etile = wave & 1, kq = wave >> 1;
     const int Epad = (E + 63) & ~63;
     const int t0 = blockIdx.x * kGemmTok;
     const int tok = t0 + n;
-    const int kbeg = khalf * (H >> 1), kend = kbeg + (H >> 1);
+    const int kbeg = kq * (H >> 2), kend = kbeg + (H >> 2);
+
     const uint4 zero4 = make_uint4(0, 0, 0, 0);
     const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)(tok < N ? tok : 0) * H) + half;
     for (int e0 = 0; e0 < E; e0 += 64) {
@@ -118,16 +119,17 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restr
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int t = 8 * (j >> 2) + 4 * half + (j & 3);
-            zs[((size_t)khalf * kGemmTok + t) * Epad + e0 + etile * 32 + n] = acc[j];
+            zs[((size_t)kq * kGemmTok + t) * Epad + e0 + etile * 32 + n] = acc[j];
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < kGemmTok * E; i += 256) {
+    for (int i = threadIdx.x; i < kGemmTok * E; i += 512) {
         const int t = i / E, e = i - t * E;
-        zs[(size_t)t * Epad + e] += zs[((size_t)kGemmTok + t) * Epad + e] + (bias ? bias[e] : 0.f);
+        const size_t o = (size_t)t * Epad + e, q = (size_t)kGemmTok * Epad;
+        zs[o] = ((zs[o] + zs[o + q]) + (zs[o + 2 * q] + zs[o + 3 * q])) + (bias ? bias[e] : 0.f);
     }
     __syncthreads();
-    for (int t = wave; t < kGemmTok; t += 4) {
+    for (int t = wave; t < kGemmTok; t += 8) {
         const int tk = t0 + t;
         if (tk < N)
             wave_softmax_topm(zs + (size_t)t * Epad, E, m, renorm, ids + (size_t)tk * m, w + (size_t)tk * m,
@@ -190,10 +192,16 @@ static fate_status launch_route_rows(hipStream_t st, const void* x, const void* 
                                      int32_t* pop) {
     auto xs = static_cast<const uint16_t*>(x);
     auto ws = static_cast<const uint16_t*>(Wg);
-    if (N >= 64 && H % 256 == 0) {
+    if (N >= 64 && H % 512 == 0) {
         // prefill-sized batches: gate GEMM on the matrix cores
-        const size_t lds_g = (size_t)2 * kGemmTok * ((E + 63) & ~63) * sizeof(float);
-        route_mfma_kernel<<<(N + kGemmTok - 1) / kGemmTok, 256, lds_g, st>>>(xs, ws, bias, N, H, E, m, renorm, ids, w,
+        const size_t lds_g = (size_t)4 * kGemmTok * ((E + 63) & ~63) * sizeof(float);
+        static bool attr_done = false;
+        if (!attr_done) {
+            FATE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(route_mfma_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kGemmTok * kMaxE * 4));
+            attr_done = true;
+        }
+        route_mfma_kernel<<<(N + kGemmTok - 1) / kGemmTok, 512, lds_g, st>>>(xs, ws, bias, N, H, E, m, renorm, ids, w,
                                                                           probs, pop);
         FATE_HIP(hipGetLastError());
         return FATE_OK;
