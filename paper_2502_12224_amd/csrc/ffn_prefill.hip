@@ -31,6 +31,13 @@ constexpr int kBM = 128;            // rows per workgroup tile
 constexpr int kBN = 128;            // weight rows per workgroup tile (4 waves x 32)
 constexpr int kKC = 128;            // columns per LDS chunk
 constexpr int kLdsRow = kKC + 8;    // halves per LDS row (16-byte pad against bank conflicts)
+constexpr int kWRing = 3;           // chunks of weights in flight per wave
+
+// Workgroup barrier that orders LDS traffic only: __syncthreads() would also wait for the
+// weight tiles that are meant to stay in flight across it.
+__device__ __forceinline__ void lds_only_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 
 #if defined(__HIP_DEVICE_COMPILE__)
 #define FATE_GLOBAL __attribute__((address_space(1)))
@@ -188,55 +195,79 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
     // staging assignment: thread -> (row r0 + 16*i, 16-byte column piece cp)
     const int cp = tid & 15, r0 = tid >> 4;
     uint4 xr[kBM / 16];
-    uint4 raw[NMAT][TPC];
-    uint32_t sbits[NMAT][TPC];
-    auto load_chunk = [&](int kc) {
+    uint4 raw[kWRing][NMAT][TPC];
+    uint32_t sbits[kWRing][NMAT][TPC];
+    auto load_x = [&](int kc) {
 #pragma unroll
         for (int i = 0; i < kBM / 16; ++i) {
             const int ar = arow[r0 + 16 * i];
             xr[i] = ar >= 0 ? *reinterpret_cast<const uint4*>(A + (size_t)ar * lda + kc * kKC + cp * 8)
                             : make_uint4(0, 0, 0, 0);
         }
-        if (wlive) {
+    };
+    // weights: kWRing chunks ahead, so that the requests cover the memory latency
+#pragma unroll
+    for (int u = 0; u < kWRing; ++u) {
+        if (wlive && u < nchunk) {
 #pragma unroll
             for (int i = 0; i < NMAT; ++i)
 #pragma unroll
                 for (int tl = 0; tl < TPC; ++tl) {
-                    const int tile = kc * TPC + tl;
-                    raw[i][tl] = wt[i][(size_t)tile * 64];
-                    sbits[i][tl] = sc[i][(size_t)((tile * KT) / group) * Nout];
+                    const int tile = u * TPC + tl;
+                    raw[u][i][tl] = wt[i][(size_t)tile * 64];
+                    sbits[u][i][tl] = sc[i][(size_t)((tile * KT) / group) * Nout];
                 }
         }
-    };
-    load_chunk(0);
-    for (int kc = 0; kc < nchunk; ++kc) {
-        __syncthreads();   // everyone is done reading the previous chunk
+    }
+    load_x(0);
+    for (int kc0 = 0; kc0 < nchunk; kc0 += kWRing) {
 #pragma unroll
-        for (int i = 0; i < kBM / 16; ++i)
-            *reinterpret_cast<uint4*>(xt + (r0 + 16 * i) * kLdsRow + cp * 8) = xr[i];
-        f16x8_t b[NMAT][kKC / 16];
-        if (wlive) {
+        for (int u = 0; u < kWRing; ++u) {
+            const int kc = kc0 + u;
+            if (kc < nchunk) {
+                lds_only_barrier();   // everyone is done reading the previous chunk
 #pragma unroll
-            for (int i = 0; i < NMAT; ++i)
+                for (int i = 0; i < kBM / 16; ++i)
+                    *reinterpret_cast<uint4*>(xt + (r0 + 16 * i) * kLdsRow + cp * 8) = xr[i];
+                // the next activations are requested before the weight refill below: loads return
+                // in order, and the next iteration must not have to wait for that refill
+                if (kc + 1 < nchunk) load_x(kc + 1);
+                f16x8_t b[NMAT][kKC / 16];
+                if (wlive) {
 #pragma unroll
-                for (int tl = 0; tl < TPC; ++tl) dequant_tile<BITS>(raw[i][tl], sbits[i][tl], &b[i][tl * SPT]);
-        }
-        __syncthreads();
-        if (kc + 1 < nchunk) load_chunk(kc + 1);
-        if (wlive) {
+                    for (int i = 0; i < NMAT; ++i)
 #pragma unroll
-            for (int mt = 0; mt < kBM / 32; ++mt) {
-                if (mt < nmt) {
-#pragma unroll
-                for (int tl = 0; tl < TPC; ++tl)
-#pragma unroll
-                    for (int d = 0; d < SPT; ++d) {
-                        const int kl = tl * KT + half * (KT / 2) + 8 * d;
-                        const f16x8_t av = *reinterpret_cast<const f16x8_t*>(xt + (mt * 32 + n) * kLdsRow + kl);
+                        for (int tl = 0; tl < TPC; ++tl)
+                            dequant_tile<BITS>(raw[u][i][tl], sbits[u][i][tl], &b[i][tl * SPT]);
+                    if (kc + kWRing < nchunk) {
 #pragma unroll
                         for (int i = 0; i < NMAT; ++i)
-                            acc[i][mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, b[i][tl * SPT + d], acc[i][mt],
-                                                                                0, 0, 0);
+#pragma unroll
+                            for (int tl = 0; tl < TPC; ++tl) {
+                                const int tile = (kc + kWRing) * TPC + tl;
+                                raw[u][i][tl] = wt[i][(size_t)tile * 64];
+                                sbits[u][i][tl] = sc[i][(size_t)((tile * KT) / group) * Nout];
+                            }
+                    }
+                }
+                lds_only_barrier();
+                if (wlive) {
+#pragma unroll
+                    for (int mt = 0; mt < kBM / 32; ++mt) {
+                        if (mt < nmt) {
+#pragma unroll
+                            for (int tl = 0; tl < TPC; ++tl)
+#pragma unroll
+                                for (int d = 0; d < SPT; ++d) {
+                                    const int kl = tl * KT + half * (KT / 2) + 8 * d;
+                                    const f16x8_t av =
+                                        *reinterpret_cast<const f16x8_t*>(xt + (mt * 32 + n) * kLdsRow + kl);
+#pragma unroll
+                                    for (int i = 0; i < NMAT; ++i)
+                                        acc[i][mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                                            av, b[i][tl * SPT + d], acc[i][mt], 0, 0, 0);
+                                }
+                        }
                     }
                 }
             }
