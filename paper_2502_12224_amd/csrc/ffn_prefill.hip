@@ -9,9 +9,11 @@
 // Rows are (token, expert) pairs in the sorted order of the permutation, so
 // an expert's rows are contiguous; shared experts are extra segments of N rows.
 //
-// GEMM tile: a workgroup of four waves owns 128 rows x 128 weight rows; each
-// wave owns 32 weight rows (one device-native tile row-block) and all 128
-// rows.  Activations go through LDS in chunks of 128 columns; weights go
+// GEMM tile: a workgroup of four waves owns 64 rows x 128 weight rows; each
+// wave owns 32 weight rows (one device-native tile row-block) and all 64
+// rows; two workgroups share a compute unit (two waves per SIMD), so that one
+// wave's dequantisation and LDS reads run under the other's matrix products
+// (128-row tiles at one wave per SIMD left the matrix pipe idle 78 % of the time).  Activations go through LDS in chunks of 128 columns; weights go
 // straight from global memory into registers in their tile layout (one
 // contiguous KiB per wave load) and are dequantised there to fp16
 // (exact code, one rounding in code*scale), which is the B operand of
@@ -27,11 +29,12 @@ typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2v_t __attribute__((ext_vector_type(2)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
-constexpr int kBM = 128;            // rows per workgroup tile
+constexpr int kBMUp = 64;           // rows per workgroup tile of the up GEMM (two matrices)
+constexpr int kBMDown = 64;         // rows per workgroup tile of the down GEMM
 constexpr int kBN = 128;            // weight rows per workgroup tile (4 waves x 32)
 constexpr int kKC = 128;            // columns per LDS chunk
 constexpr int kLdsRow = kKC + 8;    // halves per LDS row (16-byte pad against bank conflicts)
-constexpr int kWRing = 3;           // chunks of weights in flight per wave
+constexpr int kWRing = 2;           // chunks of weights in flight per wave
 
 // Workgroup barrier that orders LDS traffic only: __syncthreads() would also wait for the
 // weight tiles that are meant to stay in flight across it.
@@ -107,11 +110,10 @@ __global__ __launch_bounds__(256) void prefill_prep_kernel(const uint16_t* __res
         int ru = 0, rd = 0;
         for (int s = 0; s < E + n_shared; ++s) {
             const int T = s < E ? offsets[s + 1] - offsets[s] : N;
-            const int mb = (T + kBM - 1) / kBM;
             tab_up[s] = ru;
             tab_down[s] = rd;
-            ru += mb * (s < E ? nb_r_up : nb_s_up);
-            rd += mb * (s < E ? nb_r_down : nb_s_down);
+            ru += ((T + kBMUp - 1) / kBMUp) * (s < E ? nb_r_up : nb_s_up);
+            rd += ((T + kBMDown - 1) / kBMDown) * (s < E ? nb_r_down : nb_s_down);
         }
         tab_up[E + n_shared] = ru;
         tab_down[E + n_shared] = rd;
@@ -160,7 +162,7 @@ __device__ __forceinline__ void dequant_tile(const uint4& raw, uint32_t scale_bi
     }
 }
 
-template <int BITS, int NMAT>
+template <int BITS, int NMAT, int kBM>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert* ex, int group, int row0, int T,
                                           int nblk, const int* arow, __half* xt, __half* out, int ldo,
                                           int out_row0, int Nout, int K, const __half* A, int lda) {
@@ -294,7 +296,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
 }
 
 template <int NMAT>
-__global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void grouped_gemm_kernel(GemmArgs a) {
+    constexpr int kBM = NMAT == 2 ? kBMUp : kBMDown;
     __shared__ __align__(16) __half xt[kBM * kLdsRow];
     __shared__ int arow[kBM];
     const int nseg = a.E + a.n_shared;
@@ -336,9 +339,9 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
     const int out_row0 = (is_shared ? (seg - a.E) * a.N : sbeg) + row0;
     const int bits = is_shared ? a.bits_s : a.bits_r, group = is_shared ? a.group_s : a.group_r;
     if (bits == 4)
-        gemm_tile<4, NMAT>(a, ex, group, row0, T, nblk, arow, xt, out, ldo, out_row0, Nout, K, A, lda);
+        gemm_tile<4, NMAT, kBM>(a, ex, group, row0, T, nblk, arow, xt, out, ldo, out_row0, Nout, K, A, lda);
     else
-        gemm_tile<8, NMAT>(a, ex, group, row0, T, nblk, arow, xt, out, ldo, out_row0, Nout, K, A, lda);
+        gemm_tile<8, NMAT, kBM>(a, ex, group, row0, T, nblk, arow, xt, out, ldo, out_row0, Nout, K, A, lda);
 }
 
 // y[t,:] = sum_j w[t,j] * Yp_r[inv_perm[t*k+j], :] + sum_s g_s(t) * Yp_s[s*N+t, :]
@@ -402,8 +405,9 @@ fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs d
                                                   nb_down, nb_down);
         FATE_HIP(hipGetLastError());
     }
-    const int mb_r = P / kBM + (d.E < P ? d.E : P);            // upper bound of routed row blocks
-    const int mb_s = (d.N + kBM - 1) / kBM;
+    // upper bounds of the routed row blocks, and the shared experts' row blocks, per GEMM
+    const int mb_r_up = P / kBMUp + (d.E < P ? d.E : P), mb_s_up = (d.N + kBMUp - 1) / kBMUp;
+    const int mb_r_down = P / kBMDown + (d.E < P ? d.E : P), mb_s_down = (d.N + kBMDown - 1) / kBMDown;
     GemmArgs g{};
     g.experts = da.experts; g.shared = da.shared; g.E = d.E; g.n_shared = d.n_shared; g.N = d.N; g.k = d.k;
     g.offsets = da.offsets; g.perm = da.perm;
@@ -414,7 +418,7 @@ fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs d
         g.A_r = ms.xh; g.lda_r = d.H; g.A_s = ms.xh; g.lda_s = d.H; g.mode = 0; g.tile_start = ms.tab_up;
         g.out_r = da.h_r; g.ldo_r = da.ldh_r; g.out_s = da.h_s; g.ldo_s = da.ldh_s;
         g.nb_r = nb_r_up; g.nb_s = nb_s_up;
-        const long long grid = (long long)mb_r * nb_r_up + (long long)d.n_shared * mb_s * nb_s_up;
+        const long long grid = (long long)mb_r_up * nb_r_up + (long long)d.n_shared * mb_s_up * nb_s_up;
         if (grid > 0x7fffffffLL) FATE_FAIL(FATE_ESHAPE, "too many tiles");
         grouped_gemm_kernel<2><<<(unsigned)grid, 256, 0, st>>>(g);
         FATE_HIP(hipGetLastError());
@@ -423,7 +427,7 @@ fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs d
         g.A_r = da.h_r; g.lda_r = da.ldh_r; g.A_s = da.h_s; g.lda_s = da.ldh_s; g.mode = 1;
         g.tile_start = ms.tab_down; g.nb_r = nb_down; g.nb_s = nb_down;
         g.out_r = ms.yp_r; g.ldo_r = d.H; g.out_s = ms.yp_s; g.ldo_s = d.H;
-        const long long grid = ((long long)mb_r + (long long)d.n_shared * mb_s) * nb_down;
+        const long long grid = ((long long)mb_r_down + (long long)d.n_shared * mb_s_down) * nb_down;
         if (grid > 0x7fffffffLL) FATE_FAIL(FATE_ESHAPE, "too many tiles");
         grouped_gemm_kernel<1><<<(unsigned)grid, 256, 0, st>>>(g);
         FATE_HIP(hipGetLastError());
