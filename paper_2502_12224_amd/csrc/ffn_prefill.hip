@@ -133,10 +133,10 @@ __device__ __forceinline__ void dequant_tile(const uint4& raw, uint32_t scale_bi
         for (int d = 0; d < 4; ++d) {
             const uint32_t hi = r[d] >> 8;
             uint32_t u[4];
-            u[0] = (r[d] & 0x000f000fu) | 0x64006400u;   // columns 0,1: 1024 + u
-            u[1] = (r[d] & 0x00f000f0u) | 0x54005400u;   // columns 2,3: 64 + u
-            u[2] = (hi & 0x000f000fu) | 0x64006400u;     // columns 4,5
-            u[3] = (hi & 0x00f000f0u) | 0x54005400u;     // columns 6,7
+            u[0] = and_or_b32(r[d], 0x000f000fu, 0x64006400u);   // columns 0,1: 1024 + u
+            u[1] = and_or_b32(r[d], 0x00f000f0u, 0x54005400u);   // columns 2,3: 64 + u
+            u[2] = and_or_b32(hi, 0x000f000fu, 0x64006400u);     // columns 4,5
+            u[3] = and_or_b32(hi, 0x00f000f0u, 0x54005400u);     // columns 6,7
             f16x2v_t w[4];
             w[0] = (__builtin_bit_cast(f16x2v_t, u[0]) - offA) * s2;
             w[1] = (__builtin_bit_cast(f16x2v_t, u[1]) - offB) * s2;

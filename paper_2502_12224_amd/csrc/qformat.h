@@ -79,6 +79,18 @@ __device__ __forceinline__ void unpack_pairs(const uint4& raw, uint32_t* p) {
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 
+// A constant the compiler must keep in a vector register.  (x & mask) | bits with two literal
+// operands cannot be one VOP3 instruction on gfx9 (one scalar or literal operand per
+// instruction), and the compiler then emits v_and + v_or and re-materialises the literals;
+// with both constants in registers it selects v_and_or_b32.
+__device__ __forceinline__ uint32_t vgpr_const(uint32_t c) {
+    asm("" : "+v"(c));
+    return c;
+}
+__device__ __forceinline__ uint32_t and_or_b32(uint32_t x, uint32_t mask, uint32_t bits) {
+    return (x & vgpr_const(mask)) | vgpr_const(bits);
+}
+
 // raw 16 bytes of one lane -> MSTEPS operands of 8 fp16 values holding the
 // signed codes q themselves (exact), in column order.  int4 uses two
 // power-of-two mantissa tricks so that one shift serves four pairs:
@@ -93,10 +105,10 @@ __device__ __forceinline__ void codes_to_f16(const uint4& raw, f16x8_t* b) {
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             const uint32_t hi = r[d] >> 8;
-            const f16x2_t w0 = __builtin_bit_cast(f16x2_t, (r[d] & 0x000f000fu) | 0x64006400u) - offA;
-            const f16x2_t w1 = __builtin_bit_cast(f16x2_t, (r[d] & 0x00f000f0u) | 0x54005400u) - offB;
-            const f16x2_t w2 = __builtin_bit_cast(f16x2_t, (hi & 0x000f000fu) | 0x64006400u) - offA;
-            const f16x2_t w3 = __builtin_bit_cast(f16x2_t, (hi & 0x00f000f0u) | 0x54005400u) - offB;
+            const f16x2_t w0 = __builtin_bit_cast(f16x2_t, and_or_b32(r[d], 0x000f000fu, 0x64006400u)) - offA;
+            const f16x2_t w1 = __builtin_bit_cast(f16x2_t, and_or_b32(r[d], 0x00f000f0u, 0x54005400u)) - offB;
+            const f16x2_t w2 = __builtin_bit_cast(f16x2_t, and_or_b32(hi, 0x000f000fu, 0x64006400u)) - offA;
+            const f16x2_t w3 = __builtin_bit_cast(f16x2_t, and_or_b32(hi, 0x00f000f0u, 0x54005400u)) - offB;
             b[d] = f16x8_t{w0.x, w0.y, w1.x, w1.y, w2.x, w2.y, w3.x, w3.y};
         }
     } else {
