@@ -61,7 +61,7 @@ def cpu_baseline_decode(cfg, xs, layers_sample, tokens_sample):
     dev = "cuda"
     # stage the stored weights of the sampled layers on the host first (not timed)
     staged = {}
-    for l in layers_sample:
+    for l in sorted(set(layers_sample) | {l + 1 for l in layers_sample if l + 1 < cfg.layers}):
         Wg, b = gen_gate(cfg, l, dev)
         staged[l] = dict(Wg=Wg.float().cpu().numpy(), b=None if b is None else b.cpu().numpy(),
                          sg=gen_shared_gate(cfg, l, dev), experts={}, shared=[])
@@ -91,6 +91,37 @@ def cpu_baseline_decode(cfg, xs, layers_sample, tokens_sample):
             n_units += 1
     per_layer_token = t_total / n_units
     return per_layer_token, n_units, t_total
+
+
+def cpu_baseline_prefill(cfg, x, layer, rows):
+    """Oracle time for one layer: routing / prediction / permutation of all tokens, FFN of `rows`."""
+    import torch
+    from oracle import moe as O
+    from workloads import gen_expert, gen_gate, gen_shared_gate
+    dev = "cuda"
+    Wg, b = gen_gate(cfg, layer, dev)
+    Wg2, b2 = gen_gate(cfg, layer + 1, dev)
+    sg = gen_shared_gate(cfg, layer, dev)
+    xn = x.float().cpu().numpy()
+    Wg, Wg2 = Wg.float().cpu().numpy(), Wg2.float().cpu().numpy()
+    b = None if b is None else b.cpu().numpy()
+    b2 = None if b2 is None else b2.cpu().numpy()
+    sg = None if sg is None else sg.float().cpu().numpy()
+    ids, w, _, _ = O.gate_route(xn, Wg, b, cfg.k, cfg.renorm)
+    need = sorted(set(ids[rows].ravel().tolist()))
+    host = {e: gen_expert(cfg, layer, e, device=dev).cpu() for e in need}
+    sh = [gen_expert(cfg, layer, i, shared=True, device=dev).cpu() for i in range(cfg.n_shared)]
+    mk = lambda h: O.OracleExpert(h.w1.numpy(), h.s1.numpy(), h.w3.numpy(), h.s3.numpy(), h.w2.numpy(),
+                                  h.s2.numpy(), h.bits, h.group)
+    t0 = time.perf_counter()
+    ids, w, _, _ = O.gate_route(xn, Wg, b, cfg.k, cfg.renorm)
+    O.cross_layer_predict(xn, Wg2, b2, cfg.m)
+    O.permute(ids, cfg.E)
+    t_route = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    O.moe_ffn_rows(xn, ids, w, {e: mk(h) for e, h in host.items()}, [mk(h) for h in sh], sg, rows=rows)
+    t_ffn = time.perf_counter() - t0
+    return t_route, t_ffn
 
 
 def bench_decode(args):
@@ -225,10 +256,11 @@ def bench_decode(args):
     cpu = None
     if not args.no_cpu_baseline:
         ncores = len(os.sched_getaffinity(0))
-        per, n_units, t_cpu = cpu_baseline_decode(cfg, xs, layers_sample=[0, 1, 12], tokens_sample=[0, 1])
+        per, n_units, t_cpu = cpu_baseline_decode(cfg, xs, layers_sample=[0, 1, 6, 12, 18, 22],
+                                                  tokens_sample=list(range(12)))
         cpu = {"value": 1.0 / (per * L), "unit": "tokens/s", "cores": min(ncores, torch.get_num_threads()),
                "kind": "oracle",
-               "sample": f"{n_units} (token, layer) units of the same stack (layers 0, 1, 12; decode steps 0, 1), "
+               "sample": f"{n_units} (token, layer) units of the same stack (layers 0, 1, 6, 12, 18, 22; decode steps 0-11), "
                          f"{t_cpu:.1f} s of oracle time, scaled to {L} layers per token"}
         log(f"[bench] oracle: {per:.2f} s per (token, layer) on the host")
 
@@ -366,6 +398,18 @@ def bench_prefill(args):
     log(f"[bench] prep+up GEMM {up_us:.1f} us/layer ({achieved:.0f} TFLOP/s), whole FFN {ffn_us:.1f} us/layer "
         f"({layer_flops / (ffn_us * 1e-6) / 1e12:.0f} TFLOP/s)")
 
+    cpu = None
+    if not args.no_cpu_baseline and L > 1:
+        rows = list(range(0, N, max(1, N // 128)))[:128]
+        t_route, t_ffn = cpu_baseline_prefill(cfg, x_in[0], 0, rows)
+        per_token = t_route / N + t_ffn / len(rows)
+        cpu = {"value": 1.0 / (per_token * L), "unit": "tokens/s",
+               "cores": min(len(os.sched_getaffinity(0)), torch.get_num_threads()), "kind": "oracle",
+               "sample": f"layer 0: routing, prediction and permutation of all {N} tokens ({t_route:.2f} s) and the "
+                         f"FFN of {len(rows)} token rows ({t_ffn:.1f} s, includes dequantising their experts), "
+                         f"scaled per token to {L} layers"}
+        log(f"[bench] oracle: {per_token:.3f} s per (token, layer) on the host")
+
     out = {
         "metric": "MoE-layer tokens/s (decode b=1, prefill 512) + % HBM / MFMA roofline",
         "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -381,7 +425,7 @@ def bench_prefill(args):
         "roofline": {"bound": "mfma", "kernel": "prefill_prep_kernel + grouped_gemm_kernel<2>", "achieved": achieved,
                      "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_PEAK_TFLOPS,
                      "traffic": None, "flops_per_launch": up_flops, "us_per_launch": up_us},
-        "cpu_baseline": None,
+        "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
 
