@@ -116,6 +116,11 @@ __device__ __forceinline__ void route_role(const LayerArgs& a, int b, uint32_t t
     FATE_TS(3);
 }
 
+// BR/TR: bits and tiles per group of the routed experts, BS/TS: of the shared experts (equal to
+// the routed ones when the layer has none).  One kernel per combination keeps the code a
+// workgroup runs through small: instruction fetch at the cold start of a launch is on the
+// critical path of the first weight requests.
+template <int BR, int TR, int BS, int TS>
 __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t tag, char* dyn) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, half = lane >> 5;
@@ -354,10 +359,16 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
             }                                                                                             \
         }                                                                                                 \
     }
-    FATE_FORMAT_SWITCH(bits, tpg, FATE_LAYER_BODY)
+    if constexpr (BR == BS && TR == TS) {
+        FATE_LAYER_BODY(BR, TR)
+    } else {
+        if (is_shared) { FATE_LAYER_BODY(BS, TS) }
+        else { FATE_LAYER_BODY(BR, TR) }
+    }
 #undef FATE_LAYER_BODY
 }
 
+template <int BR, int TR, int BS, int TS>
 __global__ __launch_bounds__(kLayerThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void moe_layer_decode_kernel(LayerArgs a) {
     extern __shared__ uint4 smem[];
     __shared__ FusedRouteSmem rsm;
@@ -367,7 +378,7 @@ __global__ __launch_bounds__(kLayerThreads) __attribute__((amdgpu_waves_per_eu(2
     FATE_TS(0);
     const int b = blockIdx.x;
     if (b < a.nb_route) route_role(a, b, tag, dyn, rsm);
-    else work_role(a, b - a.nb_route, tag, dyn);
+    else work_role<BR, TR, BS, TS>(a, b - a.nb_route, tag, dyn);
     // the workgroup that leaves last opens the next epoch
     __syncthreads();
     FATE_TS(6);
@@ -423,6 +434,28 @@ extern "C" int fate_debug_probe(unsigned long long* host_out, int nblocks) {
 }
 #endif
 
+template <int BR, int TR, int BS, int TS>
+static fate_status launch_layer_kernel(hipStream_t st, int grid, int lds_bytes, int lds_max, const LayerArgs& a) {
+    static bool attr_done = false;
+    if (!attr_done) {
+        FATE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(moe_layer_decode_kernel<BR, TR, BS, TS>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds_max));
+        attr_done = true;
+    }
+    moe_layer_decode_kernel<BR, TR, BS, TS><<<grid, kLayerThreads, lds_bytes, st>>>(a);
+    return FATE_OK;
+}
+
+template <int BR, int TR>
+static fate_status launch_layer_routed(hipStream_t st, int bits_s, int tpg_s, int grid, int lds_bytes, int lds_max,
+                                       const LayerArgs& a) {
+    fate_status rc = FATE_OK;
+#define FATE_SHARED_BODY(BS, TS) rc = launch_layer_kernel<BR, TR, BS, TS>(st, grid, lds_bytes, lds_max, a);
+    FATE_FORMAT_SWITCH(bits_s, tpg_s, FATE_SHARED_BODY)
+#undef FATE_SHARED_BODY
+    return rc;
+}
+
 fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArgs a) {
     if (d.N < 1 || d.N > kLayerMaxN || d.N * d.k > kLayerMaxP)
         FATE_FAIL(FATE_ESHAPE, "fused layer: need 1 <= N <= %d and N*k <= %d (N = %d, k = %d)", kLayerMaxN,
@@ -432,19 +465,19 @@ fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArg
     const WorkLds L = work_lds(d.N, d.H, d.E, d.k);
     constexpr int kLdsMax = 128 * 1024;
     if (L.bytes > kLdsMax) FATE_FAIL(FATE_ESHAPE, "fused layer: N = %d, H = %d need %d bytes of LDS", d.N, d.H, L.bytes);
-    static bool attr_done = false;
-    if (!attr_done) {
-        FATE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(moe_layer_decode_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsMax));
-        attr_done = true;
-    }
     const int rows = (a.r.Wg2 ? 2 : 1) * d.E;
     a.nb_route = (rows + kLayerWaves - 1) / kLayerWaves;
     a.nkb_r = d.I_max / kLayerNeurons;
     a.nkb_s = d.n_shared ? d.I_shared_max / kLayerNeurons : 0;
     a.nact = min(d.E, d.N * d.k);
     const int grid = a.nb_route + d.n_shared * a.nkb_s + a.nact * a.nkb_r;
-    moe_layer_decode_kernel<<<grid, kLayerThreads, L.bytes, st>>>(a);
+    const int bits_s = d.n_shared ? d.shared_bits : d.bits, group_s = d.n_shared ? d.shared_group : d.group;
+    const int tpg_r = d.group / (d.bits == 4 ? 64 : 32), tpg_s = group_s / (bits_s == 4 ? 64 : 32);
+    fate_status rc = FATE_OK;
+#define FATE_ROUTED_BODY(BR, TR) rc = launch_layer_routed<BR, TR>(st, bits_s, tpg_s, grid, L.bytes, kLdsMax, a);
+    FATE_FORMAT_SWITCH(d.bits, tpg_r, FATE_ROUTED_BODY)
+#undef FATE_ROUTED_BODY
+    if (rc != FATE_OK) return rc;
     layer_reduce_kernel<<<d.N * (d.H / 32), 64 * kReduceWaves, 0, st>>>(a);
     FATE_HIP(hipGetLastError());
     return FATE_OK;
