@@ -76,7 +76,7 @@ __device__ __forceinline__ bool wait_logits(const unsigned long long* zq, int n,
 
 // LDS carve of a work block (bytes from the start of dynamic shared memory)
 struct WorkLds {
-    int xs, hs, red, tab, zl, ids, w, pairq, tokid, wtok, bytes;
+    int xs, hs, red, tab, zl, ids, w, pairq, tokid, wtok, cx, ch, bytes;
 };
 __host__ __device__ inline WorkLds work_lds(int N, int H, int E, int k) {
     auto up = [](int v) { return (v + 15) & ~15; };
@@ -94,6 +94,8 @@ __host__ __device__ inline WorkLds work_lds(int N, int H, int E, int k) {
     L.pairq = off; off += up(kTokPass * 4);
     L.tokid = off; off += up(kTokPass * 4);
     L.wtok = off; off += up(kTokPass * 4);
+    L.cx = off; off += up((H / 64) * (kTokPass + 1) * 4);     // [group][token] bias sums of x (groups of >= 64 columns)
+    L.ch = off; off += up(kTokPass * 4);                      // [row] bias sum of h
     L.bytes = off;
     return L;
 }
@@ -115,6 +117,280 @@ __device__ __forceinline__ void route_role(const LayerArgs& a, int b, uint32_t t
     fused_select(r, rsm, nullptr, LdsLoad{zl, r.N, r.E});
     FATE_TS(3);
 }
+
+// ---- Fast body: shapes whose per-wave share is a whole number of register rings ----
+//
+// The codes enter the matrix cores as u + C (C = 1024 or 64 for int4 depending on the nibble's
+// position, 1024 for int8: one v_and_or_b32 / v_perm_b32 per pair of codes and nothing else),
+// and the constant part leaves afterwards:  sum_k x_k q_k = sum_k x_k (u_k + C_k) - sum_k x_k (C_k + zero).
+// The second sum does not depend on the weight row, so it is taken once per token and group
+// from the fp16 activations in LDS.  u + C and x are exact in fp16, their products exact in
+// fp32; the fp32 accumulation carries terms about (C + zero) / |q| times larger than the
+// result, which costs that factor times 2^-24 in relative accuracy per addition.
+struct BiasConst {
+    uint32_t m0, b0, m1, b1;    // int4: masks / exponent bits of the two nibble positions
+};
+__device__ __forceinline__ BiasConst bias_const() {
+    return BiasConst{vgpr_const(0x000f000fu), vgpr_const(0x64006400u), vgpr_const(0x00f000f0u), vgpr_const(0x54005400u)};
+}
+// one dword of eight int4 codes -> 8 fp16 values u + C in column order (C = 1024, 1024, 64, 64, 1024, 1024, 64, 64)
+__device__ __forceinline__ f16x8_t biased_int4(uint32_t r, const BiasConst& c) {
+    const uint32_t hi = r >> 8;
+    const uint32_t w0 = (r & c.m0) | c.b0, w1 = (r & c.m1) | c.b1, w2 = (hi & c.m0) | c.b0, w3 = (hi & c.m1) | c.b1;
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+    return __builtin_bit_cast(f16x8_t, u32x4_t{w0, w1, w2, w3});
+}
+// two dwords of four int8 codes each -> 8 fp16 values 1024 + u
+__device__ __forceinline__ f16x8_t biased_int8(uint32_t r0, uint32_t r1) {
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+    return __builtin_bit_cast(f16x8_t, u32x4_t{__builtin_amdgcn_perm(0x64646464u, r0, 0x04010400u),
+                                               __builtin_amdgcn_perm(0x64646464u, r0, 0x04030402u),
+                                               __builtin_amdgcn_perm(0x64646464u, r1, 0x04010400u),
+                                               __builtin_amdgcn_perm(0x64646464u, r1, 0x04030402u)});
+}
+template <int BITS>
+__device__ __forceinline__ void biased_tile(const uint4& raw, const BiasConst& c, f16x8_t* b) {
+    if constexpr (BITS == 4) {
+        b[0] = biased_int4(raw.x, c); b[1] = biased_int4(raw.y, c);
+        b[2] = biased_int4(raw.z, c); b[3] = biased_int4(raw.w, c);
+    } else {
+        b[0] = biased_int8(raw.x, raw.y); b[1] = biased_int8(raw.z, raw.w);
+    }
+}
+// sum_k v_k (C_k + zero) over 8 fp16 values in column order
+template <int BITS>
+__device__ __forceinline__ float bias_dot8(const uint4& v, float acc) {
+    const f16x2_t cA = BITS == 4 ? f16x2_t{(_Float16)1032.f, (_Float16)1032.f} : f16x2_t{(_Float16)1152.f, (_Float16)1152.f};
+    const f16x2_t cB = BITS == 4 ? f16x2_t{(_Float16)72.f, (_Float16)72.f} : cA;
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, v.x), cA, acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, v.y), cB, acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, v.z), cA, acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, v.w), cB, acc, false);
+    return acc;
+}
+__device__ __forceinline__ float bias_of_column(int bits, int col) {
+    return bits == 4 ? ((col & 2) ? 72.f : 1032.f) : 1152.f;
+}
+
+struct WorkCtx {
+    int N, H, I, T, kb, wb, ntp, ldx;
+    bool is_shared, defer_x;
+    fate_qexpert ex;
+    _Float16 *xs, *hs;
+    float *red, *wtok, *cx, *ch;
+    const int32_t *tokid, *pairq;
+    float* part;
+    size_t part_stride;
+};
+
+constexpr int kCxLd = kTokPass + 1;      // bias sums per group: tokens 0..7 and a zero for absent rows
+
+// one ring of the up projection: D tiles of both matrices, straight-line so that the compiler
+// can wait for exactly the tile it needs
+// (mid: called once half of the ring's registers are free again)
+template <int BITS, int TPG, bool REFILL, class Mid>
+__device__ __forceinline__ void up_round(uint4 (&raw)[2][kUpRing], uint32_t (&scr)[2][kUpRing / TPG], const gu4_t* wt,
+                                         const gu16_t* sc, int srows, int round, const _Float16* xa, const float* cxg,
+                                         const int (&ctok)[4], const BiasConst& bc, float (&out)[2][4], Mid&& mid) {
+    constexpr int KT = QFmt<BITS>::KT, S = QFmt<BITS>::MSTEPS, D = kUpRing, GR = D / TPG;
+    const f32x16_t zero = f32x16_zero();
+#pragma unroll
+    for (int jg = 0; jg < GR; ++jg) {
+        float s[2], cj[4];
+        f32x16_t acc[2];
+        if (jg == (GR + 1) / 2) mid();
+#pragma unroll
+        for (int i = 0; i < 2; ++i) s[i] = half_bits_to_float(scr[i][jg]);
+        if constexpr (REFILL) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) scr[i][jg] = sc[i][(size_t)((round + 1) * GR + jg) * srows];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) cj[j] = cxg[(round * GR + jg) * kCxLd + ctok[j]];
+#pragma unroll
+        for (int tl = 0; tl < TPG; ++tl) {
+            const int j = jg * TPG + tl;
+            const _Float16* xt = xa + (round * D + j) * KT;
+            f16x8_t av[S];
+#pragma unroll
+            for (int st = 0; st < S; ++st) av[st] = *reinterpret_cast<const f16x8_t*>(xt + 8 * st);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                f16x8_t b[S];
+                biased_tile<BITS>(raw[i][j], bc, b);
+                if constexpr (REFILL) raw[i][j] = wt[i][(size_t)((round + 1) * D + j) * 64];
+#pragma unroll
+                for (int st = 0; st < S; ++st)
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[st], b[st], (tl == 0 && st == 0) ? zero : acc[i],
+                                                                    0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) out[i][j] = fmaf(s[i], acc[i][j] - cj[j], out[i][j]);
+    }
+}
+
+template <int BITS>
+struct DownPiece;
+template <>
+struct DownPiece<4> { typedef uint2 type; static constexpr int NQ = 16; };
+template <>
+struct DownPiece<8> { typedef uint4 type; static constexpr int NQ = 8; };
+
+template <int BITS, int TPG, class LoadX, class StoreX, class Gate>
+__device__ __forceinline__ void body_fast(const WorkCtx& c, LoadX&& load_x, StoreX&& store_x, Gate&& shared_gate) {
+    constexpr int KT = QFmt<BITS>::KT, D = kUpRing, GR = D / TPG, NQ = DownPiece<BITS>::NQ;
+    typedef typename DownPiece<BITS>::type piece_t;
+    typedef const FATE_GLOBAL piece_t* gpiece_t;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 31, half = lane >> 5;
+    const int H = c.H, I = c.I, T = c.T, N = c.N, kb = c.kb;
+    const int tiles_k = H / KT;
+    const int tw = tiles_k / kLayerWaves;            // tiles per wave and matrix, a multiple of D
+    const int rounds = tw / D;
+    const int g_beg = wave * (tw / TPG);
+    const gu4_t wt[2] = {as_global<uint4>(c.ex.w1) + ((size_t)kb * tiles_k + wave * tw) * 64 + lane,
+                         as_global<uint4>(c.ex.w3) + ((size_t)kb * tiles_k + wave * tw) * 64 + lane};
+    const gu16_t sc[2] = {as_global<uint16_t>(c.ex.s1) + (size_t)g_beg * I + kb * 32 + n,
+                          as_global<uint16_t>(c.ex.s3) + (size_t)g_beg * I + kb * 32 + n};
+    // W2: the 32 columns of this block in every 32-row block; a wave takes every kLayerWaves-th
+    // row block, starting from a block-dependent one.  int4: the 32 codes of a row are the 16
+    // bytes of one lane of the tile; the two half-waves fetch 8 of them each (columns 0..15 and
+    // 16..31 of the block), so every lane feeds the matrix core.  int8: one whole tile.
+    const int tiles_k2 = I / KT;
+    const int nq = (H >> 5) / kLayerWaves;           // row blocks per wave, a multiple of NQ
+    const int qrot = c.wb % nq;
+    const char FATE_GLOBAL* w2b = as_global<char>(c.ex.w2) +
+        (BITS == 4 ? ((size_t)(kb >> 1) * 1024 + ((kb & 1) * 32 + n) * 16 + 8 * half) : ((size_t)kb * 1024 + lane * 16));
+    const gu16_t s2 = as_global<uint16_t>(c.ex.s2) + (size_t)(kb * kLayerNeurons / (KT * TPG)) * H + n;
+    auto rb_of = [&](int q) { int qq = q + qrot; if (qq >= nq) qq -= nq; return wave + kLayerWaves * qq; };
+
+    if (c.defer_x) load_x();
+    uint4 raw[2][D];
+    uint32_t scr[2][GR];
+#pragma unroll
+    for (int j = 0; j < D; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) raw[i][j] = wt[i][(size_t)j * 64];
+#pragma unroll
+    for (int jg = 0; jg < GR; ++jg)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) scr[i][jg] = sc[i][(size_t)jg * I];
+    piece_t dA[NQ], dB[NQ];
+    uint32_t sA[NQ], sB[NQ];
+    auto issue_w = [&](piece_t (&d)[NQ], int chunk) {
+#pragma unroll
+        for (int u = 0; u < NQ; ++u)
+            d[u] = *reinterpret_cast<gpiece_t>(w2b + (size_t)rb_of(chunk * NQ + u) * tiles_k2 * 1024);
+    };
+    auto issue_s = [&](uint32_t (&sd)[NQ], int chunk) {
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) sd[u] = s2[rb_of(chunk * NQ + u) * 32];
+    };
+    auto issue = [&](piece_t (&d)[NQ], uint32_t (&sd)[NQ], int chunk) { issue_w(d, chunk); issue_s(sd, chunk); };
+    issue_w(dA, 0);           // its scales follow once half of the ring has been consumed
+    FATE_TS(5);
+    if (c.defer_x) store_x(true);
+    if (c.is_shared) shared_gate();
+    lds_barrier();            // x, token ids and weights are in LDS
+    FATE_TS(2);
+    // bias sums of x for this wave's groups: 8 lanes per token, each a slice of the group
+    {
+        constexpr int per = KT * TPG / 8;            // columns per lane
+        const int t = lane >> 3, sub = lane & 7;
+        const _Float16* xp = c.xs + (t < N ? t : N) * c.ldx + (size_t)g_beg * (KT * TPG) + sub * per;
+        for (int g = 0; g < tw / TPG; ++g) {
+            float sum = 0.f;
+#pragma unroll
+            for (int v = 0; v < per / 8; ++v)
+                sum = bias_dot8<BITS>(*reinterpret_cast<const uint4*>(xp + (size_t)g * (KT * TPG) + 8 * v), sum);
+            sum += __shfl_xor(sum, 1, 64);
+            sum += __shfl_xor(sum, 2, 64);
+            sum += __shfl_xor(sum, 4, 64);
+            if (sub == 0) c.cx[(g_beg + g) * kCxLd + t] = sum;
+            if (lane == 1) c.cx[(g_beg + g) * kCxLd + kTokPass] = 0.f;
+        }
+    }
+    const BiasConst bc = bias_const();
+    float out[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    const int arow = n < T ? c.tokid[n] : N;
+    int ctok[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) ctok[j] = 4 * half + j < T ? c.tokid[4 * half + j] : kTokPass;
+    const _Float16* xa = c.xs + arow * c.ldx + half * (KT / 2) + (size_t)wave * tw * KT;
+    const float* cxg = c.cx + g_beg * kCxLd;
+    for (int r = 0; r + 1 < rounds; ++r)
+        up_round<BITS, TPG, true>(raw, scr, wt, sc, I, r, xa, cxg, ctok, bc, out, [] {});
+    up_round<BITS, TPG, false>(raw, scr, wt, sc, I, rounds - 1, xa, cxg, ctok, bc, out, [&] { issue_s(sA, 0); });
+    const int nchunk = nq / NQ;
+    if (nchunk > 1) issue(dB, sB, 1);     // the ring's registers are free now
+    FATE_TS(3);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (4 * half + j < c.ntp) c.red[((wave * 2 + i) * c.ntp + 4 * half + j) * 32 + n] = out[i][j];
+    lds_barrier();
+    if (tid < T * kLayerNeurons) {        // T <= 8 rows of 32: one value per thread, one row per half-wave
+        const int t = tid >> 5;
+        float a1 = 0.f, a3 = 0.f;
+#pragma unroll
+        for (int w = 0; w < kLayerWaves; ++w) {
+            a1 += c.red[((w * 2) * c.ntp + t) * 32 + n];
+            a3 += c.red[((w * 2 + 1) * c.ntp + t) * 32 + n];
+        }
+        const _Float16 hv = (_Float16)(a1 / (1.0f + expf(-a1)) * a3);
+        c.hs[t * kHsLd + n] = hv;
+        float bsum = (float)hv * bias_of_column(BITS, n);
+        bsum += __shfl_xor(bsum, 1, 64);
+        bsum += __shfl_xor(bsum, 2, 64);
+        bsum += __shfl_xor(bsum, 4, 64);
+        bsum += __shfl_xor(bsum, 8, 64);
+        bsum += __shfl_xor(bsum, 16, 64);
+        if (n == 0) c.ch[t] = bsum;
+    }
+    lds_barrier();
+    FATE_TS(4);
+    // down projection: two matrix-core steps per piece (16 columns of h per half-wave)
+    const _Float16* ha = c.hs + (n < T ? n : kTokPass) * kHsLd + 16 * half;
+    float wj[4], chj[4];
+    float* rowj[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int t = 4 * half + j;
+        wj[j] = t < T ? c.wtok[t] : 0.f;
+        chj[j] = t < T ? c.ch[t] : 0.f;
+        rowj[j] = c.part + (size_t)(t < T ? (c.is_shared ? t : c.pairq[t]) : 0) * c.part_stride + n;
+    }
+    const f16x8_t av0 = *reinterpret_cast<const f16x8_t*>(ha), av1 = *reinterpret_cast<const f16x8_t*>(ha + 8);
+    const f32x16_t zero = f32x16_zero();
+    auto process = [&](piece_t (&d)[NQ], uint32_t (&sd)[NQ], int chunk) {
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) {
+            const int rb = rb_of(chunk * NQ + u);
+            const float s = half_bits_to_float(sd[u]);
+            f16x8_t b0, b1;
+            if constexpr (BITS == 4) { b0 = biased_int4(d[u].x, bc); b1 = biased_int4(d[u].y, bc); }
+            else { b0 = biased_int8(d[u].x, d[u].y); b1 = biased_int8(d[u].z, d[u].w); }
+            f32x16_t acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av0, b0, zero, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av1, b1, acc, 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (4 * half + j < T) rowj[j][rb * 32] = (wj[j] * s) * (acc[j] - chj[j]);
+        }
+    };
+    for (int ch = 0; ch < nchunk; ch += 2) {
+        process(dA, sA, ch);
+        if (ch + 2 < nchunk) issue(dA, sA, ch + 2);
+        if (ch + 1 < nchunk) {
+            process(dB, sB, ch + 1);
+            if (ch + 3 < nchunk) issue(dB, sB, ch + 3);
+        }
+    }
+}
+
 
 // BR/TR: bits and tiles per group of the routed experts, BS/TS: of the shared experts (equal to
 // the routed ones when the layer has none).  One kernel per combination keeps the code a
@@ -359,12 +635,27 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
             }                                                                                             \
         }                                                                                                 \
     }
+    // a whole number of rings per wave: the straight-line body
+    const bool fast = H % (kLayerWaves * kUpRing * KT) == 0 && I % KT == 0;
+    WorkCtx cx;
+    cx.N = N; cx.H = H; cx.I = I; cx.T = T; cx.kb = kb; cx.wb = wb; cx.ntp = ntp; cx.ldx = ldx;
+    cx.is_shared = is_shared; cx.defer_x = defer_x; cx.ex = ex; cx.xs = xs; cx.hs = hs; cx.red = red; cx.wtok = wtok;
+    cx.cx = reinterpret_cast<float*>(dyn + L.cx); cx.ch = reinterpret_cast<float*>(dyn + L.ch);
+    cx.tokid = tokid; cx.pairq = pairq; cx.part = part; cx.part_stride = part_stride;
+#define FATE_LAYER_FAST(BITS, TPG) body_fast<BITS, TPG>(cx, load_x, store_x, shared_gate);
     if constexpr (BR == BS && TR == TS) {
-        FATE_LAYER_BODY(BR, TR)
-    } else {
-        if (is_shared) { FATE_LAYER_BODY(BS, TS) }
+        if (fast) { FATE_LAYER_FAST(BR, TR) }
         else { FATE_LAYER_BODY(BR, TR) }
+    } else {
+        if (is_shared) {
+            if (fast) { FATE_LAYER_FAST(BS, TS) }
+            else { FATE_LAYER_BODY(BS, TS) }
+        } else {
+            if (fast) { FATE_LAYER_FAST(BR, TR) }
+            else { FATE_LAYER_BODY(BR, TR) }
+        }
     }
+#undef FATE_LAYER_FAST
 #undef FATE_LAYER_BODY
 }
 

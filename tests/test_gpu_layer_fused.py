@@ -52,8 +52,10 @@ def test_one_launch_layer_equals_separate_calls_and_oracle(name, N, last):
             assert torch.equal(a, b), (f, rep)
         y_one = f32(one.y)
         assert np.isfinite(y_one).all()
-        # same arithmetic up to the order of the fp32 partial sums (which can move an fp16 rounding of h)
-        assert ffn_rel_err(y_one, f32(y_sep).astype(np.float64)).max() <= 1e-4, rep
+        # same weights and activations; the two paths differ in the order of the fp32 sums and in how
+        # the codes' offset is removed (per code, or per group after the matrix cores), which can
+        # move an fp16 rounding of h
+        assert ffn_rel_err(y_one, f32(y_sep).astype(np.float64)).max() <= 5e-4, rep
     sync_words = one.layer_ws[:8].view(torch.int32).cpu().numpy()
     assert sync_words[0] == 3 and sync_words[1] == 0       # epoch = number of calls, exit counter back at zero
     # against the oracle
