@@ -39,8 +39,11 @@ constexpr int kHsLd = kLayerNeurons + kLdsPad;   // halves per row of h in LDS
 #ifdef FATE_PROBE
 // Timing probes (builds with -DFATE_PROBE only): per workgroup eight 100 MHz
 // timestamps, read back with fate_debug_probe().
+// The stamps stay in LDS until the workgroup leaves: a store to memory in the middle of
+// the work would sit in front of the next wait for outstanding memory operations.
 __device__ unsigned long long g_probe[4096 * 8];
-#define FATE_TS(i) do { if (threadIdx.x == 0 && blockIdx.x < 4096) g_probe[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+__shared__ unsigned long long g_pts[8];
+#define FATE_TS(i) do { if (threadIdx.x == 0) g_pts[i] = wall_clock64(); } while (0)
 #else
 #define FATE_TS(i) do { } while (0)
 #endif
@@ -366,19 +369,34 @@ __device__ __forceinline__ void body_fast(const WorkCtx& c, LoadX&& load_x, Stor
     }
     const f16x8_t av0 = *reinterpret_cast<const f16x8_t*>(ha), av1 = *reinterpret_cast<const f16x8_t*>(ha + 8);
     const f32x16_t zero = f32x16_zero();
+    // four pieces at a time, each with its own accumulator: the two dependent matrix-core
+    // steps of one piece overlap with those of the others
     auto process = [&](piece_t (&d)[NQ], uint32_t (&sd)[NQ], int chunk) {
 #pragma unroll
-        for (int u = 0; u < NQ; ++u) {
-            const int rb = rb_of(chunk * NQ + u);
-            const float s = half_bits_to_float(sd[u]);
-            f16x8_t b0, b1;
-            if constexpr (BITS == 4) { b0 = biased_int4(d[u].x, bc); b1 = biased_int4(d[u].y, bc); }
-            else { b0 = biased_int8(d[u].x, d[u].y); b1 = biased_int8(d[u].z, d[u].w); }
-            f32x16_t acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av0, b0, zero, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av1, b1, acc, 0, 0, 0);
+        for (int u0 = 0; u0 < NQ; u0 += 4) {
+            f32x16_t acc[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (4 * half + j < T) rowj[j][rb * 32] = (wj[j] * s) * (acc[j] - chj[j]);
+            for (int v = 0; v < 4; ++v) {
+                f16x8_t b0;
+                if constexpr (BITS == 4) b0 = biased_int4(d[u0 + v].x, bc);
+                else b0 = biased_int8(d[u0 + v].x, d[u0 + v].y);
+                acc[v] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av0, b0, zero, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                f16x8_t b1;
+                if constexpr (BITS == 4) b1 = biased_int4(d[u0 + v].y, bc);
+                else b1 = biased_int8(d[u0 + v].z, d[u0 + v].w);
+                acc[v] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av1, b1, acc[v], 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int rb = rb_of(chunk * NQ + u0 + v);
+                const float s = half_bits_to_float(sd[u0 + v]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (4 * half + j < T) rowj[j][rb * 32] = (wj[j] * s) * (acc[v][j] - chj[j]);
+            }
         }
     };
     for (int ch = 0; ch < nchunk; ch += 2) {
@@ -666,13 +684,20 @@ __global__ __launch_bounds__(kLayerThreads) __attribute__((amdgpu_waves_per_eu(2
     char* dyn = reinterpret_cast<char*>(smem);
     uint32_t tag = (uint32_t)ld_dev(a.sync) + 1u;
     if (tag == 0u) tag = 1u;         // a zero-filled workspace must never look current
-    FATE_TS(0);
+#ifdef FATE_PROBE
+    const unsigned long long t_start = wall_clock64();
+    if (threadIdx.x < 8) g_pts[threadIdx.x] = 0;
+    __syncthreads();
+#endif
     const int b = blockIdx.x;
     if (b < a.nb_route) route_role(a, b, tag, dyn, rsm);
     else work_role<BR, TR, BS, TS>(a, b - a.nb_route, tag, dyn);
     // the workgroup that leaves last opens the next epoch
     __syncthreads();
     FATE_TS(6);
+#ifdef FATE_PROBE
+    if (threadIdx.x < 8 && blockIdx.x < 4096) g_probe[blockIdx.x * 8 + threadIdx.x] = threadIdx.x == 0 ? t_start : g_pts[threadIdx.x];
+#endif
     if (threadIdx.x == 0 && atomicAdd(a.sync + 1, 1) == (int)gridDim.x - 1) {
         st_dev(a.sync + 1, 0);
         st_dev(a.sync, (int32_t)tag);
