@@ -83,14 +83,16 @@ __global__ __launch_bounds__(512) void route_mfma_kernel(const uint16_t* __restr
                                                          const float* __restrict__ bias, int N, int H, int E,
                                                          int m, int renorm, int32_t* __restrict__ ids,
                                                          float* __restrict__ w, float* __restrict__ probs,
-                                                         int32_t* __restrict__ pop) {
+                                                         int32_t* __restrict__ pop, int ntok) {
+    // ntok <= 32 tokens per workgroup: with few tokens in the call, fewer rows of the 32-row
+    // product are live but more workgroups share the work (each still reads all of Wg)
     extern __shared__ float zs[];                 // [4 quarters][32 tokens][Epad]
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, half = lane >> 5;
     const int etile = wave & 1, kq = wave >> 1;
     const int Epad = (E + 63) & ~63;
-    const int t0 = blockIdx.x * kGemmTok;
-    const int tok = t0 + n;
+    const int t0 = blockIdx.x * ntok;
+    const int tok = n < ntok ? t0 + n : N;        // rows past ntok: no token
     const int kbeg = kq * (H >> 2), kend = kbeg + (H >> 2);
 
     const uint4 zero4 = make_uint4(0, 0, 0, 0);
@@ -123,13 +125,13 @@ __global__ __launch_bounds__(512) void route_mfma_kernel(const uint16_t* __restr
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < kGemmTok * E; i += 512) {
+    for (int i = threadIdx.x; i < ntok * E; i += 512) {
         const int t = i / E, e = i - t * E;
         const size_t o = (size_t)t * Epad + e, q = (size_t)kGemmTok * Epad;
         zs[o] = ((zs[o] + zs[o + q]) + (zs[o + 2 * q] + zs[o + 3 * q])) + (bias ? bias[e] : 0.f);
     }
     __syncthreads();
-    for (int t = wave; t < kGemmTok; t += 8) {
+    for (int t = wave; t < ntok; t += 8) {
         const int tk = t0 + t;
         if (tk < N)
             wave_softmax_topm(zs + (size_t)t * Epad, E, m, renorm, ids + (size_t)tk * m, w + (size_t)tk * m,
@@ -201,8 +203,10 @@ static fate_status launch_route_rows(hipStream_t st, const void* x, const void* 
                                          hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kGemmTok * kMaxE * 4));
             attr_done = true;
         }
-        route_mfma_kernel<<<(N + kGemmTok - 1) / kGemmTok, 512, lds_g, st>>>(xs, ws, bias, N, H, E, m, renorm, ids, w,
-                                                                          probs, pop);
+        // enough workgroups for the device before the tile is filled with tokens
+        const int ntok = N >= 8192 ? 32 : (N >= 4096 ? 16 : 8);
+        route_mfma_kernel<<<(N + ntok - 1) / ntok, 512, lds_g, st>>>(xs, ws, bias, N, H, E, m, renorm, ids, w, probs, pop,
+                                                                  ntok);
         FATE_HIP(hipGetLastError());
         return FATE_OK;
     }
