@@ -199,40 +199,101 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
     uint4 xr[kBM / 16];
     uint4 raw[kWRing][NMAT][TPC];
     uint32_t sbits[kWRing][NMAT][TPC];
+    // (the load is unconditional and the row is clamped: a branch around a load makes the
+    // compiler wait for every outstanding load at the next use, which empties the weight ring)
+    // the rows this thread stages do not change from chunk to chunk; a missing row reads row 0
+    // and is masked to zero (an AND, not a select: a select lets the compiler put the load
+    // back under a branch)
+    uint32_t xoff[kBM / 16];       // element offsets (rows * lda < 2^31: checked by the entry point)
+    uint32_t xmask[kBM / 16];
+#pragma unroll
+    for (int i = 0; i < kBM / 16; ++i) {
+        const int ar = arow[r0 + 16 * i];
+        xoff[i] = (uint32_t)(ar >= 0 ? ar : 0) * (uint32_t)lda + cp * 8;
+        xmask[i] = ar >= 0 ? 0xffffffffu : 0u;
+    }
     auto load_x = [&](int kc) {
 #pragma unroll
         for (int i = 0; i < kBM / 16; ++i) {
-            const int ar = arow[r0 + 16 * i];
-            xr[i] = ar >= 0 ? *reinterpret_cast<const uint4*>(A + (size_t)ar * lda + kc * kKC + cp * 8)
-                            : make_uint4(0, 0, 0, 0);
+            const uint4 v = *reinterpret_cast<const uint4*>(A + xoff[i] + kc * kKC);
+            xr[i] = make_uint4(v.x & xmask[i], v.y & xmask[i], v.z & xmask[i], v.w & xmask[i]);
         }
     };
-    // weights: kWRing chunks ahead, so that the requests cover the memory latency
+    auto request_w = [&](int u, int kc) {
 #pragma unroll
-    for (int u = 0; u < kWRing; ++u) {
-        if (wlive && u < nchunk) {
+        for (int i = 0; i < NMAT; ++i)
 #pragma unroll
-            for (int i = 0; i < NMAT; ++i)
+            for (int tl = 0; tl < TPC; ++tl) {
+                const int tile = kc * TPC + tl;
+                raw[u][i][tl] = wt[i][(size_t)tile * 64];
+                sbits[u][i][tl] = sc[i][(size_t)((tile * KT) / group) * Nout];
+            }
+    };
+    auto stage_x = [&]() {
 #pragma unroll
-                for (int tl = 0; tl < TPC; ++tl) {
-                    const int tile = u * TPC + tl;
-                    raw[u][i][tl] = wt[i][(size_t)tile * 64];
-                    sbits[u][i][tl] = sc[i][(size_t)((tile * KT) / group) * Nout];
-                }
+        for (int i = 0; i < kBM / 16; ++i)
+            *reinterpret_cast<uint4*>(xt + (r0 + 16 * i) * kLdsRow + cp * 8) = xr[i];
+    };
+    auto multiply = [&](f16x8_t (&b)[NMAT][kKC / 16]) {
+#pragma unroll
+        for (int mt = 0; mt < kBM / 32; ++mt) {
+            if (mt < nmt) {
+#pragma unroll
+                for (int tl = 0; tl < TPC; ++tl)
+#pragma unroll
+                    for (int d = 0; d < SPT; ++d) {
+                        const int kl = tl * KT + half * (KT / 2) + 8 * d;
+                        const f16x8_t av = *reinterpret_cast<const f16x8_t*>(xt + (mt * 32 + n) * kLdsRow + kl);
+#pragma unroll
+                        for (int i = 0; i < NMAT; ++i)
+                            acc[i][mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, b[i][tl * SPT + d], acc[i][mt], 0, 0, 0);
+                    }
+            }
         }
+    };
+    int kc_done = 0;
+    // (int4 only: the int8 instantiation holds twice the tiles per chunk and has no registers
+    // left for a second copy of the loop)
+    if (BITS == 4 && wlive && nchunk >= kWRing) {
+        // Steady state without a branch around any load: weights kWRing chunks ahead, the next
+        // activations requested before the refill (loads return in order, and the next
+        // iteration must not wait for that refill).
+#pragma unroll
+        for (int u = 0; u < kWRing; ++u) request_w(u, u);
+        load_x(0);
+        const int nfull = (nchunk - kWRing) / kWRing * kWRing;     // chunks whose refill and next x exist
+        for (int kc0 = 0; kc0 < nfull; kc0 += kWRing) {
+#pragma unroll
+            for (int u = 0; u < kWRing; ++u) {
+                const int kc = kc0 + u;
+                lds_only_barrier();   // everyone is done reading the previous chunk
+                stage_x();
+                load_x(kc + 1);
+                f16x8_t b[NMAT][kKC / 16];
+#pragma unroll
+                for (int i = 0; i < NMAT; ++i)
+#pragma unroll
+                    for (int tl = 0; tl < TPC; ++tl) dequant_tile<BITS>(raw[u][i][tl], sbits[u][i][tl], &b[i][tl * SPT]);
+                request_w(u, kc + kWRing);
+                lds_only_barrier();
+                multiply(b);
+            }
+        }
+        kc_done = nfull;
+    } else {
+#pragma unroll
+        for (int u = 0; u < kWRing; ++u)
+            if (wlive && u < nchunk) request_w(u, u);
+        load_x(0);
     }
-    load_x(0);
-    for (int kc0 = 0; kc0 < nchunk; kc0 += kWRing) {
+    // the last chunks (and shapes with a short K, or a wave without weight rows)
+    for (int kc0 = kc_done; kc0 < nchunk; kc0 += kWRing) {
 #pragma unroll
         for (int u = 0; u < kWRing; ++u) {
             const int kc = kc0 + u;
             if (kc < nchunk) {
-                lds_only_barrier();   // everyone is done reading the previous chunk
-#pragma unroll
-                for (int i = 0; i < kBM / 16; ++i)
-                    *reinterpret_cast<uint4*>(xt + (r0 + 16 * i) * kLdsRow + cp * 8) = xr[i];
-                // the next activations are requested before the weight refill below: loads return
-                // in order, and the next iteration must not have to wait for that refill
+                lds_only_barrier();
+                stage_x();
                 if (kc + 1 < nchunk) load_x(kc + 1);
                 f16x8_t b[NMAT][kKC / 16];
                 if (wlive) {
@@ -241,37 +302,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
 #pragma unroll
                         for (int tl = 0; tl < TPC; ++tl)
                             dequant_tile<BITS>(raw[u][i][tl], sbits[u][i][tl], &b[i][tl * SPT]);
-                    if (kc + kWRing < nchunk) {
-#pragma unroll
-                        for (int i = 0; i < NMAT; ++i)
-#pragma unroll
-                            for (int tl = 0; tl < TPC; ++tl) {
-                                const int tile = (kc + kWRing) * TPC + tl;
-                                raw[u][i][tl] = wt[i][(size_t)tile * 64];
-                                sbits[u][i][tl] = sc[i][(size_t)((tile * KT) / group) * Nout];
-                            }
-                    }
+                    if (kc + kWRing < nchunk) request_w(u, kc + kWRing);
                 }
                 lds_only_barrier();
-                if (wlive) {
-#pragma unroll
-                    for (int mt = 0; mt < kBM / 32; ++mt) {
-                        if (mt < nmt) {
-#pragma unroll
-                            for (int tl = 0; tl < TPC; ++tl)
-#pragma unroll
-                                for (int d = 0; d < SPT; ++d) {
-                                    const int kl = tl * KT + half * (KT / 2) + 8 * d;
-                                    const f16x8_t av =
-                                        *reinterpret_cast<const f16x8_t*>(xt + (mt * 32 + n) * kLdsRow + kl);
-#pragma unroll
-                                    for (int i = 0; i < NMAT; ++i)
-                                        acc[i][mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                                            av, b[i][tl * SPT + d], acc[i][mt], 0, 0, 0);
-                                }
-                        }
-                    }
-                }
+                if (wlive) multiply(b);
             }
         }
     }
