@@ -95,7 +95,9 @@ __global__ __launch_bounds__(512) void route_mfma_kernel(const uint16_t* __restr
     const int tok = n < ntok ? t0 + n : N;        // rows past ntok: no token
     const int kbeg = kq * (H >> 2), kend = kbeg + (H >> 2);
 
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    // Rows without a token and columns without an expert read row 0 instead (their products are
+    // never looked at): every load is unconditional, so the compiler's waits count the loads
+    // still in flight and the next chunk's operands travel under this chunk's products.
     const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)(tok < N ? tok : 0) * H) + half;
     for (int e0 = 0; e0 < E; e0 += 64) {
         const int e = e0 + etile * 32 + n;
@@ -103,19 +105,30 @@ __global__ __launch_bounds__(512) void route_mfma_kernel(const uint16_t* __restr
         rf32x16_t acc;
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[j] = 0.f;
-        for (int k = kbeg; k < kend; k += 16 * 8) {
-            uint4 av[8], bv[8];
+        // chunks of eight matrix-core steps (H % 1024 == 0: a quarter of K is a whole number of
+        // pairs of chunks)
+        constexpr int kStep = 8;
+        uint4 av[2][kStep], bv[2][kStep];
+        auto request = [&](uint4 (&a)[kStep], uint4 (&b)[kStep], int k) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int kk = k + 16 * u;
-                const bool in = kk < kend;
-                av[u] = (in && tok < N) ? xr[kk >> 3] : zero4;
-                bv[u] = (in && e < E) ? wr[kk >> 3] : zero4;
+            for (int u = 0; u < kStep; ++u) {
+                a[u] = xr[(k + 16 * u) >> 3];
+                b[u] = wr[(k + 16 * u) >> 3];
             }
+        };
+        auto multiply = [&](const uint4 (&a)[kStep], const uint4 (&b)[kStep]) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av[u]),
-                                                              __builtin_bit_cast(bf16x8_t, bv[u]), acc, 0, 0, 0);
+            for (int u = 0; u < kStep; ++u)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a[u]),
+                                                              __builtin_bit_cast(bf16x8_t, b[u]), acc, 0, 0, 0);
+        };
+        request(av[0], bv[0], kbeg);
+        for (int k = kbeg; k < kend; k += 2 * 16 * kStep) {
+            request(av[1], bv[1], k + 16 * kStep);
+            multiply(av[0], bv[0]);
+            // the last request of the row runs past this wave's quarter by one chunk: clamped to stay inside the row
+            request(av[0], bv[0], k + 2 * 16 * kStep < kend ? k + 2 * 16 * kStep : kbeg);
+            multiply(av[1], bv[1]);
         }
         // lane (half, n) holds expert column n, token rows 8*(j/4) + 4*half + j%4
 #pragma unroll
@@ -194,7 +207,7 @@ static fate_status launch_route_rows(hipStream_t st, const void* x, const void* 
                                      int32_t* pop) {
     auto xs = static_cast<const uint16_t*>(x);
     auto ws = static_cast<const uint16_t*>(Wg);
-    if (N >= 64 && H % 512 == 0) {
+    if (N >= 64 && H % 1024 == 0) {
         // prefill-sized batches: gate GEMM on the matrix cores
         const size_t lds_g = (size_t)4 * kGemmTok * ((E + 63) & ~63) * sizeof(float);
         static bool attr_done = false;
