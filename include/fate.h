@@ -93,10 +93,13 @@ fate_status fate_permute(void* stream, const int32_t* topk_ids, int N, int k, in
                          int32_t* expert_order);
 
 /* ------------------------------------------------------------------------
- * Fused decode-side routing: fate_gate_route + fate_cross_layer_predict +
- * fate_permute in one launch for small N (N <= 16), spreading the two gate
- * matrices over many compute units.  Same outputs, bit for bit, as the three
- * calls.  Wg_next may be NULL (last layer): pred_* are then left untouched.
+ * Fused routing: fate_gate_route + fate_cross_layer_predict + fate_permute
+ * in one call.  N <= 16 (decode): one launch, the two gate matrices spread
+ * over many compute units.  N >= 64 with H a multiple of 1024 (prefill): both
+ * gate products in one launch on the matrix cores, then the permutation.
+ * Other N are rejected (FATE_ESHAPE).  Same outputs, bit for bit, as the
+ * three calls.  Wg_next may be NULL (last layer): pred_* are then left
+ * untouched.
  * workspace: fate_route_fused_workspace bytes, zero-filled once by the
  * caller before the first use (the call leaves it zero-filled).
  * ---------------------------------------------------------------------- */

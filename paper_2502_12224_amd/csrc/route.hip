@@ -74,6 +74,9 @@ __global__ __launch_bounds__(256) void route_rows_kernel(const uint16_t* __restr
 // stands: lane (half, r) holds 8 consecutive elements of row r - 16 bytes straight from memory.
 // bf16 products are exact in fp32; accumulation is fp32.  The logits meet in LDS, then one wave
 // per token does softmax and selection as in the other kernels.
+struct RouteSecond {             // arguments of the second gate (grid.y = 2); unused when grid.y = 1
+    const uint16_t* Wg; const float* bias; int m; int32_t* ids; float* w; int32_t* pop;
+};
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float rf32x16_t;
 constexpr int kGemmTok = 32;
@@ -83,10 +86,13 @@ __global__ __launch_bounds__(512) void route_mfma_kernel(const uint16_t* __restr
                                                          const float* __restrict__ bias, int N, int H, int E,
                                                          int m, int renorm, int32_t* __restrict__ ids,
                                                          float* __restrict__ w, float* __restrict__ probs,
-                                                         int32_t* __restrict__ pop, int ntok) {
+                                                         int32_t* __restrict__ pop, int ntok, RouteSecond g2) {
     // ntok <= 32 tokens per workgroup: with few tokens in the call, fewer rows of the 32-row
     // product are live but more workgroups share the work (each still reads all of Wg)
     extern __shared__ float zs[];                 // [4 quarters][32 tokens][Epad]
+    if (blockIdx.y == 1) {                        // the second gate of the same launch (next layer's)
+        Wg = g2.Wg; bias = g2.bias; m = g2.m; renorm = 0; ids = g2.ids; w = g2.w; probs = nullptr; pop = g2.pop;
+    }
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, half = lane >> 5;
     const int etile = wave & 1, kq = wave >> 1;
@@ -202,27 +208,32 @@ static int pick_tpw(int N, int H, int E) {
     return 1;
 }
 
+static fate_status launch_route_mfma(hipStream_t st, const void* x, const void* Wg, const float* bias, int N, int H,
+                                     int E, int m, bool renorm, int32_t* ids, float* w, float* probs, int32_t* pop,
+                                     RouteSecond second, int ngates) {
+    const size_t lds_g = (size_t)4 * kGemmTok * ((E + 63) & ~63) * sizeof(float);
+    static bool attr_done = false;
+    if (!attr_done) {
+        FATE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(route_mfma_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kGemmTok * kMaxE * 4));
+        attr_done = true;
+    }
+    // enough workgroups for the device before the tile is filled with tokens
+    const int ntok = N >= 8192 ? 32 : (N >= 4096 ? 16 : 8);
+    route_mfma_kernel<<<dim3((N + ntok - 1) / ntok, ngates), 512, lds_g, st>>>(
+        static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(Wg), bias, N, H, E, m, renorm, ids, w, probs, pop,
+        ntok, second);
+    FATE_HIP(hipGetLastError());
+    return FATE_OK;
+}
+
 static fate_status launch_route_rows(hipStream_t st, const void* x, const void* Wg, const float* bias, int N,
                                      int H, int E, int m, int renorm, int32_t* ids, float* w, float* probs,
                                      int32_t* pop) {
     auto xs = static_cast<const uint16_t*>(x);
     auto ws = static_cast<const uint16_t*>(Wg);
-    if (N >= 64 && H % 1024 == 0) {
-        // prefill-sized batches: gate GEMM on the matrix cores
-        const size_t lds_g = (size_t)4 * kGemmTok * ((E + 63) & ~63) * sizeof(float);
-        static bool attr_done = false;
-        if (!attr_done) {
-            FATE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(route_mfma_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kGemmTok * kMaxE * 4));
-            attr_done = true;
-        }
-        // enough workgroups for the device before the tile is filled with tokens
-        const int ntok = N >= 8192 ? 32 : (N >= 4096 ? 16 : 8);
-        route_mfma_kernel<<<(N + ntok - 1) / ntok, 512, lds_g, st>>>(xs, ws, bias, N, H, E, m, renorm, ids, w, probs, pop,
-                                                                  ntok);
-        FATE_HIP(hipGetLastError());
-        return FATE_OK;
-    }
+    if (N >= 64 && H % 1024 == 0)     // prefill-sized batches: gate GEMM on the matrix cores
+        return launch_route_mfma(st, x, Wg, bias, N, H, E, m, renorm, ids, w, probs, pop, RouteSecond{}, 1);
     const int tpw = pick_tpw(N, H, E);
     const size_t lds = (size_t)4 * tpw * (2 * (size_t)H + 4 * (size_t)E);
     if (lds > 65536) FATE_FAIL(FATE_ESHAPE, "H = %d, E = %d need %zu bytes of LDS (> 64 KiB)", H, E, lds);
@@ -295,7 +306,10 @@ extern "C" fate_status fate_route_fused(void* stream, const void* x_bf16, const 
                                         int32_t* expert_order, void* workspace, size_t workspace_bytes) {
     fate_status s = check_route_args(x_bf16, Wg_bf16, bias, N, H, E, k, m, topk_ids, topk_w);
     if (s != FATE_OK) return s;
-    if (N < 1 || N > kFusedMaxN) FATE_FAIL(FATE_ESHAPE, "fused routing needs 1 <= N <= %d (N = %d)", kFusedMaxN, N);
+    const bool big = N >= 64 && H % 1024 == 0;     // both gate products in one launch on the matrix cores
+    if (N < 1 || (N > kFusedMaxN && !big))
+        FATE_FAIL(FATE_ESHAPE, "fused routing needs 1 <= N <= %d, or N >= 64 with H a multiple of 1024 (N = %d, H = %d)",
+                  kFusedMaxN, N, H);
     if (Wg_next_bf16) {
         FATE_CHECK_PTR(Wg_next_bf16);
         FATE_CHECK_PTR_OPT(bias_next);
@@ -308,6 +322,21 @@ extern "C" fate_status fate_route_fused(void* stream, const void* x_bf16, const 
     if (workspace == nullptr || workspace_bytes < need)
         FATE_FAIL(FATE_EWORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
     FATE_CHECK_PTR(workspace);
+    if (big) {
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        if (Wg_next_bf16) {
+            fill_i32_kernel<<<(E + 255) / 256, 256, 0, st>>>(pred_pop, E, 0);
+            FATE_HIP(hipGetLastError());
+        }
+        s = launch_route_mfma(st, x_bf16, Wg_bf16, bias, N, H, E, k, renorm != 0, topk_ids, topk_w, nullptr, nullptr,
+                              RouteSecond{static_cast<const uint16_t*>(Wg_next_bf16), bias_next, m, pred_ids, pred_w,
+                                          pred_pop},
+                              Wg_next_bf16 ? 2 : 1);
+        if (s != FATE_OK) return s;
+        permute_kernel<<<1, 1024, 0, st>>>(topk_ids, N * k, E, counts, offsets, perm, inv_perm, expert_order);
+        FATE_HIP(hipGetLastError());
+        return FATE_OK;
+    }
     const int nrows = Wg_next_bf16 ? 2 * E : E;
     const int grid = (nrows + 3) / 4;
     FusedRouteArgs a{static_cast<const uint16_t*>(x_bf16), static_cast<const uint16_t*>(Wg_bf16), bias,

@@ -56,7 +56,7 @@ class LayerBuffers:
         self.desc = B.make_ffn_desc(N, H, E, k, cfg.I, cfg.bits, cfg.group, cfg.n_shared, cfg.I_shared or 0,
                                     cfg.shared_bits, cfg.group, True, mode)
         self.ffn_ws = torch.zeros(B.fate_moe_ffn_q_workspace(self.desc), dtype=torch.uint8, device=device)
-        self.fused_ok = 1 <= N <= 16
+        self.fused_ok = 1 <= N <= 16 or (N >= 64 and cfg.H % 1024 == 0)
         self.route_ws = torch.zeros(B.fate_route_fused_workspace(max(N, 1), E), dtype=torch.uint8, device=device)
         # whole layer in one launch (small decode batches)
         self.one_launch_ok = 1 <= N <= 8 and N * k <= 64 and mode != 2

@@ -70,7 +70,8 @@ def test_permute_drops_out_of_range_ids():
     assert perm[:4].tolist() == [0, 5, 2, 4] and inv.tolist() == [0, -1, 2, -1, 3, 1]
 
 
-@pytest.mark.parametrize("name,N", [("tiny", 16), ("qwen", 1), ("qwen", 5), ("deepseek", 8), ("mixtral", 1), ("mixtral", 4)])
+@pytest.mark.parametrize("name,N", [("tiny", 16), ("qwen", 1), ("qwen", 5), ("deepseek", 8), ("mixtral", 1), ("mixtral", 4),
+                                    ("qwen", 512), ("qwen", 2047), ("deepseek", 1024), ("mixtral", 2048)])
 def test_route_fused_equals_the_three_calls(name, N):
     cfg = SHAPES[name]
     x = gen_hidden(cfg, N, device=DEV)
