@@ -261,20 +261,22 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
 #pragma unroll
         for (int u = 0; u < kWRing; ++u) request_w(u, u);
         load_x(0);
-        const int nfull = (nchunk - kWRing) / kWRing * kWRing;     // chunks whose refill and next x exist
+        // (near the end the requests are clamped to the last chunk instead of being skipped: a
+        // few redundant loads, no branch)
+        const int nfull = nchunk / kWRing * kWRing;
         for (int kc0 = 0; kc0 < nfull; kc0 += kWRing) {
 #pragma unroll
             for (int u = 0; u < kWRing; ++u) {
                 const int kc = kc0 + u;
                 lds_only_barrier();   // everyone is done reading the previous chunk
                 stage_x();
-                load_x(kc + 1);
+                load_x(min(kc + 1, nchunk - 1));
                 f16x8_t b[NMAT][kKC / 16];
 #pragma unroll
                 for (int i = 0; i < NMAT; ++i)
 #pragma unroll
                     for (int tl = 0; tl < TPC; ++tl) dequant_tile<BITS>(raw[u][i][tl], sbits[u][i][tl], &b[i][tl * SPT]);
-                request_w(u, kc + kWRing);
+                request_w(u, min(kc + kWRing, nchunk - 1));
                 lds_only_barrier();
                 multiply(b);
             }
