@@ -219,7 +219,7 @@ static fate_status launch_route_mfma(hipStream_t st, const void* x, const void* 
         attr_done = true;
     }
     // enough workgroups for the device before the tile is filled with tokens
-    const int ntok = N >= 8192 ? 32 : (N >= 4096 ? 16 : 8);
+    const int ntok = N > 4096 ? 32 : (N > 1024 ? 16 : 8);
     route_mfma_kernel<<<dim3((N + ntok - 1) / ntok, ngates), 512, lds_g, st>>>(
         static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(Wg), bias, N, H, E, m, renorm, ids, w, probs, pop,
         ntok, second);
