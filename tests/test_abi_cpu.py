@@ -47,12 +47,14 @@ def test_argument_validation_without_gpu():
     assert L.fate_cross_layer_predict(z, p16, p16, z, 4, 256, 8, 2, 9, p16, p16, p16) == 1   # m > E
     assert L.fate_permute(z, p16, 4, 0, 8, p16, p16, p16, p16, p16) == 1                  # k = 0
     assert L.fate_permute(z, p16, 4, 2, 8, z, p16, p16, p16, p16) == 1                    # NULL counts
-    # fused routing: workspace too small, N too large
+    # fused routing: workspace too small, N between the decode and the prefill range, prefill N with an unsuitable H
     nb = C.c_size_t(0)
     assert L.fate_route_fused_workspace(4, 60, C.byref(nb)) == 0 and nb.value == 256 + 2 * 4 * 60 * 4
     args = [z, p16, p16, z, p16, z, 4, 2048, 60, 4, 15, 0] + [p16] * 10
     assert L.fate_route_fused(*args, p16, C.c_size_t(16)) == 4
-    args[6] = 64
+    args[6] = 32
+    assert L.fate_route_fused(*args, p16, C.c_size_t(1 << 20)) == 2
+    args[6], args[7] = 64, 1536
     assert L.fate_route_fused(*args, p16, C.c_size_t(1 << 20)) == 2
     # packing
     assert L.fate_pack_weight(z, p16, 32, 64, 3, C.c_void_p(0x2000)) == 1
