@@ -85,3 +85,30 @@ def test_one_launch_layer_rejects_large_batches():
         B.fate_moe_layer_decode(d, x, lw.Wg, lw.bias, None, None, cfg.m, cfg.renorm, buf.ids, buf.w, None, None, None,
                                 buf.counts, buf.offsets, buf.perm, buf.inv_perm, buf.order, lw.table, None, None,
                                 buf.y, ws)
+
+@pytest.mark.parametrize("name,N", [("qwen", 1), ("qwen", 4), ("mixtral", 2)])
+def test_one_launch_layer_with_outlier_activations(name, N):
+    """Activations with a large common component and a few outlier channels: the one-launch body feeds
+    the matrix cores with codes + constant and removes the constant's share afterwards from the sum of
+    the activations of a group, which is where such inputs would cost accuracy."""
+    cfg = SHAPES[name]
+    print(f"case {name} N={N} outliers", flush=True)
+    g = torch.Generator(device="cpu").manual_seed(1234 + N)
+    xf = torch.randn(N, cfg.H, generator=g) + 3.0                       # common offset: every group sum is large
+    cols = torch.randperm(cfg.H, generator=g)[:8]
+    xf[:, cols] *= 40.0                                                  # outlier channels
+    x = xf.to(torch.bfloat16).to(DEV)
+    lw = LayerWeights(cfg, 0, DEV)
+    one = LayerBuffers(cfg, N, DEV)
+    layer_forward(cfg, lw, None, x, one, one_launch=True)
+    torch.cuda.synchronize()
+    assert one.status() == 0
+    ids_h = one.ids.cpu().numpy()
+    from workloads import gen_expert
+    experts = {int(e): oracle_expert(gen_expert(cfg, 0, int(e), device=DEV)) for e in set(ids_h.ravel().tolist())}
+    shared = [oracle_expert(gen_expert(cfg, 0, s, shared=True, device=DEV)) for s in range(cfg.n_shared)]
+    sg = None if lw.shared_gate is None else f32(lw.shared_gate)
+    y_ref = O.moe_ffn(f32(x), ids_h, one.w.cpu().numpy().astype(np.float64), experts, shared, sg)
+    err = ffn_rel_err(f32(one.y), y_ref).max()
+    print(f"  max row error vs oracle {err:.2e}")
+    assert err <= 2e-3
