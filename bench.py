@@ -284,6 +284,17 @@ def bench_decode(args):
                      "bytes_per_launch": layer_bytes, "us_per_launch": kern_us},
         "cpu_baseline": cpu,
     }
+    if not args.no_prefill:
+        # the metric's second figure: a 512-token prefill of the same model shape (its own weights: Zipf-skewed gate)
+        del stack, graph, bufs
+        torch.cuda.empty_cache()
+        import copy
+        pa = copy.copy(args)
+        pa.workload, pa.steps, pa.warmup, pa.no_cpu_baseline, pa.layers = "qwen_prefill512", 10, 2, True, 0
+        pre = bench_prefill(pa, emit=False)
+        out["config"]["prefill512"] = {"tokens_per_s": pre["value"], "ms_per_pass": pre["ms_per_step"],
+                                        "roofline": pre["roofline"], "ffn_mfma_frac": pre["config"]["ffn_mfma_frac"],
+                                        "workload": pre["config"]["workload"]}
     print(json.dumps(out), flush=True)
 
 
@@ -296,9 +307,11 @@ PREFILL_WORKLOADS = {
 }
 
 
-def bench_prefill(args):
+def bench_prefill(args, emit=True):
     """One step = one prefill pass of N tokens through every layer of the stack
-    (routing, prediction, permutation, MFMA expert FFN, cache accounting)."""
+    (routing, prediction, permutation, MFMA expert FFN, cache accounting).
+    emit=False: return the result instead of printing it (the decode run
+    embeds the 512-token prefill figures of the metric)."""
     import numpy as np
     import torch
     import paper_2502_12224_amd.binding as B
@@ -427,6 +440,8 @@ def bench_prefill(args):
                      "traffic": None, "flops_per_launch": up_flops, "us_per_launch": up_us},
         "cpu_baseline": cpu,
     }
+    if not emit:
+        return out
     print(json.dumps(out), flush=True)
 
 
@@ -553,6 +568,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=None, help="default 32 (decode) / 2 (prefill)")
     ap.add_argument("--workload", default="qwen_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true",
+                    help="decode: skip the 512-token prefill figures that the default run adds to its line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="decode: also run five 1 GiB device copies (reference for hardware-counter runs)")
     ap.add_argument("--n-max", type=int, default=None,
