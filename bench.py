@@ -131,9 +131,10 @@ def bench_decode(args):
     from paper_2502_12224_amd.stack import LayerBuffers, MoEStack, layer_forward
     from workloads import SHAPES
 
-    cfg = SHAPES["qwen"]
+    shape, N, S, desc = DECODE_WORKLOADS[args.workload]
+    qwen = args.workload == "qwen_decode"
+    cfg = SHAPES[shape]
     dev = "cuda"
-    N, S = 1, 128
     L, E, H = cfg.layers, cfg.E, cfg.H
     t0 = time.time()
     log(f"[bench] generating {L} layers x ({E} routed + {cfg.n_shared} shared) experts on the device ...")
@@ -225,8 +226,9 @@ def bench_decode(args):
 
     # roofline of the dominant kernel pair (the layer kernel and its small reduction): they stream every
     # byte the layer needs (activated routed experts, the shared expert, both gate matrices, x, y)
-    layer_bytes = cfg.k * expert_bytes(H, cfg.I, cfg.bits, cfg.group) + \
-        cfg.n_shared * expert_bytes(H, cfg.I_shared, cfg.shared_bits, cfg.group) + 2 * E * H * 2 + N * H * (2 + 4)
+    uniq = float(np.mean([len(set(t_ids[1, l].ravel().tolist())) for l in range(L)]))   # experts routed at the timed step
+    layer_bytes = uniq * expert_bytes(H, cfg.I, cfg.bits, cfg.group) + \
+        cfg.n_shared * expert_bytes(H, cfg.I_shared or 0, cfg.shared_bits, cfg.group) + 2 * E * H * 2 + N * H * (2 + 4)
     reps = 20
     blocker = torch.randn(8192, 8192, dtype=torch.float32, device=dev)   # keeps the queue busy while launches pile up
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -257,7 +259,7 @@ def bench_decode(args):
     if not args.no_cpu_baseline:
         ncores = len(os.sched_getaffinity(0))
         per, n_units, t_cpu = cpu_baseline_decode(cfg, xs, layers_sample=[0, 1, 6, 12, 18, 22],
-                                                  tokens_sample=list(range(12)))
+                                                  tokens_sample=list(range(12 if qwen else 2)))
         cpu = {"value": 1.0 / (per * L), "unit": "tokens/s", "cores": min(ncores, torch.get_num_threads()),
                "kind": "oracle",
                "sample": f"{n_units} (token, layer) units of the same stack (layers 0, 1, 6, 12, 18, 22; decode steps 0-11), "
@@ -269,10 +271,9 @@ def bench_decode(args):
         "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int4 weights, bf16/fp16 activations, fp32 accumulate", "data": "synthetic",
-        "config": {"workload": "configs[1]: Qwen1.5-MoE-shaped decode, 24 layers chained, batch 1, "
-                               "60 experts top-4 (I=1408) + gated shared expert (I=5632), int4 g128",
-                   "step": "one token through 24 MoE layers (route + predict + permute + FFN in one launch per "
-                           "layer, cache step on the host)",
+        "config": {"workload": desc,
+                   "step": f"one decode step of {N} token(s) through {L} MoE layers (route + predict + permute + FFN in "
+                           "one launch per layer, cache step on the host)",
                    "layers": L, "batch": N, "decode_steps_cycled": S,
                    "layer_us": ms_per_step * 1e3 / L, "layer_algorithmic_MB": layer_bytes / 1e6,
                    "layer_hbm_frac": layer_bytes / (ms_per_step * 1e-3 / L) / 1e9 / HBM_PEAK_GBS,
@@ -280,11 +281,11 @@ def bench_decode(args):
                    "cache_hit_rate": tot["hits"] / max(1, tot["hits"] + tot["misses"])},
         "roofline": {"bound": "hbm", "kernel": "moe_layer_decode_kernel + layer_reduce_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic("decode_qwen_b1_traffic.txt"),
+                     "traffic": measured_traffic("decode_qwen_b1_traffic.txt") if qwen else None,
                      "bytes_per_launch": layer_bytes, "us_per_launch": kern_us},
         "cpu_baseline": cpu,
     }
-    if not args.no_prefill:
+    if qwen and not args.no_prefill:
         # the metric's second figure: a 512-token prefill of the same model shape (its own weights: Zipf-skewed gate)
         del stack, graph, bufs
         torch.cuda.empty_cache()
@@ -297,6 +298,16 @@ def bench_decode(args):
                                         "workload": pre["config"]["workload"]}
     print(json.dumps(out), flush=True)
 
+
+DECODE_WORKLOADS = {
+    # name: (shape, batch, decode steps cycled, description); every expert resident on the device
+    "qwen_decode": ("qwen", 1, 128, "configs[1]: Qwen1.5-MoE-shaped decode, 24 layers chained, batch 1, "
+                                    "60 experts top-4 (I=1408) + gated shared expert (I=5632), int4 g128"),
+    "deepseek_decode8": ("deepseek", 8, 64, "configs[3]: DeepSeek-MoE-16B-shaped decode, 28 layers chained, batch 8, "
+                                            "all experts resident"),
+    "mixtral_decode": ("mixtral", 1, 128, "configs[4]: Mixtral-8x7B-shaped decode, 32 layers chained, batch 1, "
+                                          "all experts resident"),
+}
 
 PREFILL_WORKLOADS = {
     # name: (shape, tokens, description)
@@ -575,7 +586,7 @@ def main():
     ap.add_argument("--n-max", type=int, default=None,
                     help="offload workloads: cap on prefetched experts per layer (default: batch * m, at most E)")
     args = ap.parse_args()
-    decode = args.workload == "qwen_decode"
+    decode = args.workload in DECODE_WORKLOADS
     if args.steps is None:
         args.steps = 256 if decode else OFFLOAD_WORKLOADS[args.workload][3] if args.workload in OFFLOAD_WORKLOADS else 10
     if args.warmup is None:
@@ -588,15 +599,15 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the hot path has no CPU fallback.", file=sys.stderr)
         sys.exit(3)
-    if args.workload == "qwen_decode":
+    if args.workload in DECODE_WORKLOADS:
         bench_decode(args)
     elif args.workload in PREFILL_WORKLOADS:
         bench_prefill(args)
     elif args.workload in OFFLOAD_WORKLOADS:
         bench_offload(args)
     else:
-        print(f"bench.py: unknown workload {args.workload}; choose qwen_decode or one of "
-              f"{sorted(PREFILL_WORKLOADS) + sorted(OFFLOAD_WORKLOADS)}", file=sys.stderr)
+        print(f"bench.py: unknown workload {args.workload}; choose one of "
+              f"{sorted(DECODE_WORKLOADS) + sorted(PREFILL_WORKLOADS) + sorted(OFFLOAD_WORKLOADS)}", file=sys.stderr)
         sys.exit(2)
 
 
