@@ -28,6 +28,7 @@ struct LayerArgs {
     int y_is_fp32;
     int32_t* status;
     int32_t* sync;                 // [0] epoch of the previous call, [1] workgroups that have left
+    int nitems, nwork;             // work items (32-neuron blocks of shared experts, then of routed slots); work blocks in the launch
 };
 
 // byte offsets inside the workspace of fate_moe_layer_decode

@@ -1,0 +1,12 @@
+// One-call decode layer: the looping kernels (several work items per block) whose routed experts
+// are int4 with 2 tile(s) per group.
+#include "layer_decode_impl.h"
+
+namespace fate {
+
+fate_status launch_layer_loop_4_2(hipStream_t st, int bits_s, int tpg_s, int grid, int lds_bytes, int lds_max,
+                                   const LayerArgs& a) {
+    return launch_layer_routed<4, 2, true>(st, bits_s, tpg_s, grid, lds_bytes, lds_max, a);
+}
+
+}  // namespace fate
