@@ -155,6 +155,7 @@ __device__ __forceinline__ float bias_of_column(int bits, int col) {
 }
 
 struct WorkCtx {
+    int tid;
     int N, H, I, T, kb, wb, ntp, ldx;
     bool is_shared, defer_x;
     fate_qexpert ex;
@@ -226,7 +227,7 @@ __device__ __forceinline__ void body_fast(const WorkCtx& c, LoadX&& load_x, Stor
     constexpr int KT = QFmt<BITS>::KT, D = kUpRing, GR = D / TPG, NQ = DownPiece<BITS>::NQ;
     typedef typename DownPiece<BITS>::type piece_t;
     typedef const FATE_GLOBAL piece_t* gpiece_t;
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tid = c.tid, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, half = lane >> 5;
     const int H = c.H, I = c.I, T = c.T, N = c.N, kb = c.kb;
     const int tiles_k = H / KT;
@@ -400,7 +401,11 @@ __device__ __forceinline__ void body_fast(const WorkCtx& c, LoadX&& load_x, Stor
 // all tokens; bit 2 = a wait ran out, stop.  Without LOOP state is not used.
 template <int BR, int TR, int BS, int TS, bool LOOP>
 __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t tag, char* dyn, int& state) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int tid0 = threadIdx.x;
+    // (looping kernels: the thread index is made opaque per item, so that what is derived from it
+    // is recomputed instead of being kept in registers across the whole body of every item)
+    if constexpr (LOOP) asm volatile("" : "+v"(tid0));
+    const int tid = tid0, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, half = lane >> 5;
     const int N = a.r.N, H = a.r.H, E = a.r.E, k = a.r.k;
     const WorkLds L = work_lds(N, H, E, k);
@@ -645,6 +650,7 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
     // a whole number of rings per wave: the straight-line body
     const bool fast = H % (kLayerWaves * kUpRing * KT) == 0 && I % KT == 0;
     WorkCtx cx;
+    cx.tid = tid;
     cx.N = N; cx.H = H; cx.I = I; cx.T = T; cx.kb = kb; cx.wb = wb; cx.ntp = ntp; cx.ldx = ldx;
     cx.is_shared = is_shared; cx.defer_x = defer_x; cx.ex = ex; cx.xs = xs; cx.hs = hs; cx.red = red; cx.wtok = wtok;
     cx.cx = reinterpret_cast<float*>(dyn + L.cx); cx.ch = reinterpret_cast<float*>(dyn + L.ch);
