@@ -65,9 +65,9 @@ fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArg
     a.nkb_r = d.I_max / kLayerNeurons;
     a.nkb_s = d.n_shared ? d.I_shared_max / kLayerNeurons : 0;
     a.nact = min(d.E, d.N * d.k);
-    // work items: 32-neuron blocks of the shared experts, then of the routed slots.  With more than
-    // twice as many items as workgroups fit on the device (two per compute unit), the launch has
-    // that many work blocks and a block takes every nwork-th item.
+    // work items: 32-neuron blocks of the shared experts, then of the routed slots.  With more
+    // items than workgroups fit on the device (two per compute unit), the launch has that many
+    // work blocks and a block takes every nwork-th item.
     static int cu_count = 0;
     if (cu_count == 0) {
         int dev = 0;
@@ -76,7 +76,7 @@ fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArg
     }
     a.nitems = d.n_shared * a.nkb_s + a.nact * a.nkb_r;
     const int fit = std::max(1, 2 * cu_count - a.nb_route);
-    a.nwork = a.nitems > 2 * fit ? fit : a.nitems;      // up to two rounds: one item per block, scheduled by the hardware
+    a.nwork = a.nitems > fit ? fit : a.nitems;
     const int grid = a.nb_route + a.nwork;
     const int bits_s = d.n_shared ? d.shared_bits : d.bits, group_s = d.n_shared ? d.shared_group : d.group;
     const int tpg_r = d.group / (d.bits == 4 ? 64 : 32), tpg_s = group_s / (bits_s == 4 ? 64 : 32);

@@ -672,10 +672,10 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
 #undef FATE_LAYER_BODY
 }
 
-// LOOP: a work block takes every nwork-th item instead of exactly one (launches with several
-// times more items than the device holds workgroups: the routing of all tokens, x and the expert
-// table are then set up once per block, not once per item).  The loop keeps more values alive
-// and spills registers, so launches that fit (the batch-1 cases) use the kernel without it.
+// LOOP: a work block takes every nwork-th item instead of exactly one (launches with more items
+// than the device holds workgroups: the routing of all tokens, x and the expert table are then
+// set up once per block, not once per item).  The loop keeps more values alive and spills a few
+// registers, so launches that fit use the kernel without it.
 template <int BR, int TR, int BS, int TS, bool LOOP>
 __global__ __launch_bounds__(kLayerThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void moe_layer_decode_kernel(LayerArgs a) {
     extern __shared__ uint4 smem[];
