@@ -13,40 +13,38 @@ FLAGS = (["-DFATE_PROBE"] if os.environ.get("FATE_PROBE") else []) + ["-O3", "-s
          "-packed-fp32-ops", "-Wno-unused-result", "-Wno-unknown-warning-option"]
 
 
+def _compile(src, objdir):
+    path = os.path.join(CSRC, src)
+    obj = os.path.join(objdir, src + ".o")
+    cmd = [HIPCC, *FLAGS, "-x", "hip", "-c", path, "-o", obj]
+    p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in p.stdout.splitlines() if "packed-fp32-ops" not in l)
+    return src, obj, p.returncode, out
+
+
 def build(verbose=True, jobs=8):
+    """Compiles every source (the long ones first, `jobs` at a time) and links libfate.so."""
+    from concurrent.futures import ThreadPoolExecutor
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
-    procs = []
-    objs = []
-    for src in SOURCES:
-        path = os.path.join(CSRC, src)
-        if not os.path.exists(path):
-            continue
-        obj = os.path.join(objdir, src + ".o")
-        objs.append(obj)
-        cmd = [HIPCC, *FLAGS, "-x", "hip", "-c", path, "-o", obj]
-        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
-        if len(procs) >= jobs:
-            _drain(procs, verbose)
-    _drain(procs, verbose)
-    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs]
+    srcs = [s for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
+    order = sorted(srcs, key=lambda s: (not s.startswith("layer_decode"), s != "ffn_prefill.hip", srcs.index(s)))
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        results = list(pool.map(lambda s: _compile(s, objdir), order))
+    objs = {}
+    for src, obj, rc, out in results:
+        if rc != 0:
+            raise RuntimeError(f"hipcc failed on {src}:\n{out}")
+        if verbose and out.strip():
+            print(f"[{src}]\n{out}")
+        objs[src] = obj
+    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *[objs[s] for s in srcs]]
     out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if out.returncode != 0:
         raise RuntimeError("link failed:\n" + out.stdout)
     if verbose:
         print("built", LIB)
     return LIB
-
-
-def _drain(procs, verbose):
-    while procs:
-        src, p = procs.pop(0)
-        out, _ = p.communicate()
-        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
-        if p.returncode != 0:
-            raise RuntimeError(f"hipcc failed on {src}:\n{out}")
-        if verbose and out.strip():
-            print(f"[{src}]\n{out}")
 
 
 if __name__ == "__main__":
