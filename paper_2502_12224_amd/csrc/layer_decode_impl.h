@@ -483,20 +483,40 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
             for (int t = wave; t < N; t += kLayerWaves)
                 wave_softmax_topk_rounds(zl + t * E, E, k, a.r.renorm, ids + t * k, wv + t * k);
             __syncthreads();
-            if constexpr (LOOP) state |= 2;
+            if constexpr (LOOP) {
+                // every slot's expert and rows, once per block: the items only look them up
+                int32_t* slots = reinterpret_cast<int32_t*>(dyn + L.slots);
+                for (int i = tid; i < kLayerMaxP; i += kLayerThreads) slots[i * kSlotWords] = -1;
+                __syncthreads();
+                if (wave == 0) wave_slot_table(ids, wv, N * k, E, k, 0u, kTokPass, slots);
+                __syncthreads();
+                state |= 2;
+            }
         }
         const int rwb = wb - nsh;
         const int slot = rwb / a.nkb_r;
         kb = rwb - slot * a.nkb_r;
-        int pos;
-        const int e = wave_slot_expert(ids, N * k, E, slot, &T, &pos);     // same in every wave
-        if (e < 0) return;                    // fewer activated experts than slots: no pair, nothing to write
-        ex = reinterpret_cast<const fate_qexpert*>(tab)[e];
-        bits = a.bits_r; group = a.group_r;
-        if (wave == 0 && pos >= 0) {
-            tokid[pos] = lane / k;
-            wtok[pos] = wv[lane];
-            pairq[pos] = lane;
+        if constexpr (LOOP) {
+            int32_t* st = reinterpret_cast<int32_t*>(dyn + L.slots) + slot * kSlotWords;
+            const int e = st[0];
+            if (e < 0) return;                // fewer activated experts than slots: no pair, nothing to write
+            T = st[1];
+            tokid = st + 2;                   // this item's rows live in the slot's entry
+            pairq = st + 2 + kTokPass;
+            wtok = reinterpret_cast<float*>(st + 2 + 2 * kTokPass);
+            ex = reinterpret_cast<const fate_qexpert*>(tab)[e];
+            bits = a.bits_r; group = a.group_r;
+        } else {
+            int pos;
+            const int e = wave_slot_expert(ids, N * k, E, slot, &T, &pos);     // same in every wave
+            if (e < 0) return;                    // fewer activated experts than slots: no pair, nothing to write
+            ex = reinterpret_cast<const fate_qexpert*>(tab)[e];
+            bits = a.bits_r; group = a.group_r;
+            if (wave == 0 && pos >= 0) {
+                tokid[pos] = lane / k;
+                wtok[pos] = wv[lane];
+                pairq[pos] = lane;
+            }
         }
         part = a.part_r + (size_t)kb * H;
         part_stride = (size_t)a.nkb_r * H;    // row of pair q: part + q * part_stride

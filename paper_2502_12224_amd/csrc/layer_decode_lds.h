@@ -8,10 +8,11 @@
 namespace fate {
 
 constexpr int kHsLd = kLayerNeurons + kLdsPad;   // halves per row of h in LDS
+constexpr int kSlotWords = 2 + 3 * kTokPass;     // per routed slot: expert, row count, then token / pair / weight of each row
 
 // LDS carve of a work block (bytes from the start of dynamic shared memory)
 struct WorkLds {
-    int xs, hs, red, tab, zl, ids, w, pairq, tokid, wtok, cx, ch, bytes;
+    int xs, hs, red, tab, zl, ids, w, pairq, tokid, wtok, cx, ch, slots, bytes;
 };
 __host__ __device__ inline WorkLds work_lds(int N, int H, int E, int k) {
     auto up = [](int v) { return (v + 15) & ~15; };
@@ -31,6 +32,7 @@ __host__ __device__ inline WorkLds work_lds(int N, int H, int E, int k) {
     L.wtok = off; off += up(kTokPass * 4);
     L.cx = off; off += up((H / 64) * (kTokPass + 1) * 4);     // [group][token] bias sums of x (groups of >= 64 columns)
     L.ch = off; off += up(kTokPass * 4);                      // [row] bias sum of h
+    L.slots = off; off += up(kLayerMaxP * kSlotWords * 4);    // looping kernels: per routed slot its expert and rows
     L.bytes = off;
     return L;
 }

@@ -266,6 +266,39 @@ __device__ __forceinline__ int wave_slot_expert(const int32_t* ids, int P, int E
     return e;
 }
 
+// One wavefront, P <= 64 pairs: what wave_slot_expert gives for one slot, for every slot at once.
+// tab: [64 slots][2 + 3 * rows_max] words: expert (-1 past the activated ones), its pair count,
+// then the tokens, pair indices and weights (float bits) of its pairs in pair order.  The caller
+// has set every expert word to -1.  w: the pairs' routing weights.
+__device__ __forceinline__ void wave_slot_table(const int32_t* ids, const float* w, int P, int E, int k_magic_div,
+                                                uint32_t k_magic, int rows_max, int32_t* tab) {
+    const int lane = threadIdx.x & 63;
+    const int words = 2 + 3 * rows_max;
+    const int ei = (lane < P) ? ids[lane] : -1;
+    const bool valid = lane < P && ei >= 0 && ei < E;
+    const int key = valid ? ei : -1;
+    int cnt = 0, before = 0;
+    for (int src = 0; src < P; ++src) {
+        const int ej = lane_bcast(key, src);
+        const bool same = valid && ej == key;
+        cnt += same;
+        before += same && src < lane;
+    }
+    const int first = valid && before == 0;
+    int rank = 0;          // experts in front of this lane's expert in the order (pair count descending, id ascending)
+    for (int src = 0; src < P; ++src) {
+        const int cj = lane_bcast(cnt, src), ej = lane_bcast(key, src), fj = lane_bcast(first, src);
+        rank += fj && ((cj > cnt) || (cj == cnt && ej < key));
+    }
+    if (valid && before < rows_max) {
+        int32_t* t = tab + rank * words;
+        if (first) { t[0] = key; t[1] = cnt; }
+        t[2 + before] = k_magic ? (int)__umulhi((uint32_t)lane, k_magic) : lane / k_magic_div;
+        t[2 + rows_max + before] = lane;
+        t[2 + 2 * rows_max + before] = __float_as_int(w[lane]);
+    }
+}
+
 // Per-lane mask of the lanes in this wave that hold the same key (valid lanes only).
 __device__ __forceinline__ unsigned long long wave_match(int key, bool valid, int nbits) {
     unsigned long long mask = __ballot(valid);
