@@ -2,8 +2,11 @@
 // with hipMemcpyAsync on a side stream, one event per slot, and a device
 // table of fate_qexpert kept in step with what each slot holds.
 //
-// Ordering.  Copies run on copy_stream.  Before a step the caller hands in the
-// event it recorded after the previous layer's FFN; copy_stream waits for it,
+// Ordering.  Copies alternate between copy_stream and a second stream the
+// engine owns (default priority): an expert of a few megabytes does not fill
+// the link on its own, two copies in flight hide each other's start-up.
+// Before a step the caller hands in the
+// event it recorded after the previous layer's FFN; both streams wait for it,
 // so a slot released in the previous step is not overwritten while a kernel
 // may still read it.  After a step the compute stream waits for the events of
 // the slots the current layer uses.  Table entries are written by a one-thread
@@ -18,6 +21,8 @@ struct fate_hip_engine {
     const char* host;
     fate_qexpert* table;
     hipStream_t copy_stream, compute_stream;
+    hipStream_t copy2;             // the engine's own second copy stream
+    int flip;
     std::vector<hipEvent_t> ev;
     std::vector<uint8_t> ev_live;
     uint64_t bytes;
@@ -66,11 +71,18 @@ extern "C" fate_hip_engine* fate_hip_engine_create(int num_layers, int E, int to
     g->copy_stream = static_cast<hipStream_t>(copy_stream);
     g->compute_stream = static_cast<hipStream_t>(compute_stream);
     g->bytes = 0;
+    g->flip = 0;
+    if (hipStreamCreateWithFlags(&g->copy2, hipStreamNonBlocking) != hipSuccess) {
+        delete g;
+        set_error("hipStreamCreateWithFlags failed");
+        return nullptr;
+    }
     g->ev.resize(total_slots);
     g->ev_live.assign(total_slots, 0);
     for (int i = 0; i < total_slots; ++i) {
         if (hipEventCreateWithFlags(&g->ev[i], hipEventDisableTiming) != hipSuccess) {
             for (int j = 0; j < i; ++j) (void)hipEventDestroy(g->ev[j]);
+            (void)hipStreamDestroy(g->copy2);
             delete g;
             set_error("hipEventCreateWithFlags failed");
             return nullptr;
@@ -81,6 +93,8 @@ extern "C" fate_hip_engine* fate_hip_engine_create(int num_layers, int E, int to
 
 extern "C" void fate_hip_engine_destroy(fate_hip_engine* g) {
     if (!g) return;
+    (void)hipStreamSynchronize(g->copy2);
+    (void)hipStreamDestroy(g->copy2);
     for (hipEvent_t e : g->ev) (void)hipEventDestroy(e);
     delete g;
 }
@@ -92,10 +106,12 @@ extern "C" int fate_hip_engine_copy(void* engine, int layer, int expert, int slo
         slot >= g->total_slots)
         return 1;
     const size_t nb = g->lay.slot_bytes;
+    hipStream_t cs = g->flip ? g->copy2 : g->copy_stream;
+    g->flip ^= 1;
     if (hipMemcpyAsync(g->pool + (size_t)slot * nb, g->host + ((size_t)layer * g->E + expert) * nb, nb,
-                       hipMemcpyHostToDevice, g->copy_stream) != hipSuccess)
+                       hipMemcpyHostToDevice, cs) != hipSuccess)
         return 2;
-    if (hipEventRecord(g->ev[slot], g->copy_stream) != hipSuccess) return 3;
+    if (hipEventRecord(g->ev[slot], cs) != hipSuccess) return 3;
     g->ev_live[slot] = 1;
     g->bytes += nb;
     set_entry_kernel<<<1, 64, 0, g->compute_stream>>>(g->table + (size_t)layer * g->E + expert,
@@ -105,8 +121,10 @@ extern "C" int fate_hip_engine_copy(void* engine, int layer, int expert, int slo
 
 extern "C" fate_status fate_hip_engine_begin_step(fate_hip_engine* g, void* compute_done_event) {
     if (!g) FATE_FAIL(FATE_EINVAL, "engine is NULL");
-    if (compute_done_event)
+    if (compute_done_event) {
         FATE_HIP(hipStreamWaitEvent(g->copy_stream, static_cast<hipEvent_t>(compute_done_event), 0));
+        FATE_HIP(hipStreamWaitEvent(g->copy2, static_cast<hipEvent_t>(compute_done_event), 0));
+    }
     return FATE_OK;
 }
 
