@@ -310,9 +310,12 @@ fate_status fate_expert_cache_step_layers(fate_cache*, int layer_begin, int laye
  * expert (l,e) at ((l*E)+e)*slot_bytes, already in device-native layout with
  * the six arrays at the offsets given in `layout`.  table_dev: device array
  * [num_layers*E] of fate_qexpert maintained by the engine.  The engine enqueues
- * copies on copy_stream, makes compute_stream wait for the copies the current
- * layer needs, and makes copy_stream wait for `compute_done_event` (recorded
- * by the caller after the previous layer's FFN) before overwriting slots. */
+ * copies in turn on copy_stream and on a second stream of its own (default
+ * priority; destroyed, after a synchronise, by fate_hip_engine_destroy), makes
+ * compute_stream wait for the copies the current layer needs, and makes both
+ * copy streams wait for `compute_done_event` (recorded by the caller after the
+ * previous layer's FFN) before overwriting slots.  Whoever needs every copy to
+ * have finished waits for the device, not for copy_stream alone. */
 typedef struct {
     size_t slot_bytes;
     size_t off_w1, off_w3, off_w2, off_s1, off_s3, off_s2;
