@@ -112,3 +112,35 @@ def test_one_launch_layer_with_outlier_activations(name, N):
     err = ffn_rel_err(f32(one.y), y_ref).max()
     print(f"  max row error vs oracle {err:.2e}")
     assert err <= 2e-3
+
+@pytest.mark.parametrize("name,N", [("qwen", 1), ("qwen", 6), ("mixtral", 1)])
+def test_one_launch_layer_with_an_expert_that_is_not_resident(name, N):
+    """An activated expert whose table entry holds NULL pointers: status bit 0 is raised, its pairs
+    contribute nothing, everything else is as usual (one-item and looping kernels)."""
+    cfg = SHAPES[name]
+    print(f"case {name} N={N} one expert absent", flush=True)
+    x = gen_hidden(cfg, N, device=DEV)
+    lw = LayerWeights(cfg, 0, DEV)
+    one = LayerBuffers(cfg, N, DEV)
+    layer_forward(cfg, lw, None, x, one, one_launch=True)
+    torch.cuda.synchronize()
+    ids_h = one.ids.cpu().numpy()
+    gone = int(ids_h[0, 0])                                  # the first token's first expert
+    saved = lw.table.clone()
+    lw.table[gone * 64:(gone + 1) * 64].zero_()              # sizeof(fate_qexpert) = 64
+    one.y.fill_(float("nan"))
+    layer_forward(cfg, lw, None, x, one, one_launch=True)
+    torch.cuda.synchronize()
+    lw.table.copy_(saved)
+    assert one.status() == 1
+    assert np.array_equal(one.ids.cpu().numpy(), ids_h)
+    from workloads import gen_expert
+    experts = {int(e): oracle_expert(gen_expert(cfg, 0, int(e), device=DEV)) for e in set(ids_h.ravel().tolist())}
+    shared = [oracle_expert(gen_expert(cfg, 0, s, shared=True, device=DEV)) for s in range(cfg.n_shared)]
+    sg = None if lw.shared_gate is None else f32(lw.shared_gate)
+    w_ref = one.w.cpu().numpy().astype(np.float64)
+    w_ref[ids_h == gone] = 0.0
+    y_ref = O.moe_ffn(f32(x), ids_h, w_ref, experts, shared, sg)
+    err = ffn_rel_err(f32(one.y), y_ref).max()
+    print(f"  max row error vs oracle {err:.2e}")
+    assert err <= 2e-3
