@@ -176,6 +176,7 @@ __device__ __forceinline__ void up_round(uint4 (&raw)[2][kUpRing], uint32_t (&sc
                                          const gu16_t* sc, int srows, int round, const _Float16* xa, const float* cxg,
                                          const int (&ctok)[4], const BiasConst& bc, float (&out)[2][4], Mid&& mid) {
     constexpr int KT = QFmt<BITS>::KT, S = QFmt<BITS>::MSTEPS, D = kUpRing, GR = D / TPG;
+    static_assert(GR >= 2, "mid() runs between two groups of a ring");
     const f32x16_t zero = f32x16_zero();
 #pragma unroll
     for (int jg = 0; jg < GR; ++jg) {

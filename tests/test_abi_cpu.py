@@ -210,3 +210,15 @@ def test_cache_error_paths():
     assert cc.step(0, [1], [0])[0] == 1
     cc.close()
     assert not B.lib().fate_cache_create(0, 8, 4, 1, 1, 8, B.COPY_FN(0), None)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The bench line is a one-GPU figure: asking for more ends with a message, before any GPU work."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert p.returncode != 0
+    assert "one GPU" in p.stderr + p.stdout
+    assert not any(l.startswith("{") for l in p.stdout.splitlines())
