@@ -337,8 +337,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __shared__ __align__(16) __half xt[kBM * kLdsRow];
     __shared__ int arow[kBM];
     const int nseg = a.E + a.n_shared;
-    const int b = blockIdx.x;
-    if (b >= a.tile_start[nseg]) return;
+    // the shared experts' segments come last in the table and hold the fullest tiles: they go first
+    const int ntile = a.tile_start[nseg];
+    if ((int)blockIdx.x >= ntile) return;
+    const int b = ntile - 1 - (int)blockIdx.x;
     int lo = 0, hi = nseg;                 // last seg with tile_start[seg] <= b
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
