@@ -144,3 +144,46 @@ def test_one_launch_layer_with_an_expert_that_is_not_resident(name, N):
     err = ffn_rel_err(f32(one.y), y_ref).max()
     print(f"  max row error vs oracle {err:.2e}")
     assert err <= 2e-3
+
+
+@pytest.mark.parametrize("name,N", [("qwen", 1), ("deepseek", 8)])
+def test_one_launch_layer_replayed_from_a_graph(name, N):
+    """The layer call captured once and replayed with new inputs, with eager calls and synchronisations
+    between the replays: every replay gives what the eager call gives on the same input, bit for bit
+    (one-item and looping kernels; the call's epoch lives on the device, so a replay advances it)."""
+    cfg = SHAPES[name]
+    print(f"case {name} N={N} graph replays", flush=True)
+    lw = LayerWeights(cfg, 0, DEV)
+    ln = LayerWeights(cfg, 1, DEV, experts=[])
+    xs = [gen_hidden(cfg, N, step=s, device=DEV) for s in range(4)]
+    eager = LayerBuffers(cfg, N, DEV)
+    fields = ROUTE_FIELDS + PRED_FIELDS
+    want = []
+    for x in xs:
+        layer_forward(cfg, lw, ln, x, eager, one_launch=True)
+        torch.cuda.synchronize()
+        assert eager.status() == 0
+        want.append((_snapshot(eager, fields), eager.y.clone()))
+    cap = LayerBuffers(cfg, N, DEV)
+    x_in = torch.zeros_like(xs[0])
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        x_in.copy_(xs[0])
+        layer_forward(cfg, lw, ln, x_in, cap, one_launch=True)     # warm before capture
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            layer_forward(cfg, lw, ln, x_in, cap, one_launch=True)
+    torch.cuda.synchronize()
+    for s in (1, 3, 0, 2, 2):
+        x_in.copy_(xs[s])
+        cap.y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert cap.status() == 0
+        for f in fields:
+            assert torch.equal(getattr(cap, f), want[s][0][f]), f"{f} of a replay (input {s}) differs from the eager call"
+        assert torch.equal(cap.y, want[s][1]), f"y of a replay (input {s}) differs from the eager call"
+        # eager work of the program between the replays
+        layer_forward(cfg, lw, ln, xs[(s + 1) % 4], eager, one_launch=True)
+        torch.cuda.synchronize()
