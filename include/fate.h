@@ -201,6 +201,8 @@ fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, const void* x_b
  * evaluated; a work group owns 32 intermediate neurons of one expert, does
  * their up projection and multiplies the result into its columns of the down
  * projection, and leaves a partial output row that the reduction adds up.
+ * A call with more such items than work groups fit on the device at once
+ * launches as many as fit, and each takes every n-th item.
  *   out: device pointers for every routing output, sized as in the separate
  *        calls; pred_* may be NULL when Wg_next is NULL (last layer).
  *   d->mode must be 0 or 1, d->phases 0.
