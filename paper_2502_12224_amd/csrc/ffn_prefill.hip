@@ -229,12 +229,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
                 sbits[u][i][tl] = sc[i][(size_t)((tile * KT) / group) * Nout];
             }
     };
-    auto stage_x = [&]() {
+    // two activation tiles in LDS: chunk kc is multiplied from tile kc & 1 while chunk kc + 1 is
+    // written into the other one, so a chunk costs one barrier and a wave's dequantisation is
+    // not fenced off from its matrix products
+    auto stage_x = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < kBM / 16; ++i)
-            *reinterpret_cast<uint4*>(xt + (r0 + 16 * i) * kLdsRow + cp * 8) = xr[i];
+            *reinterpret_cast<uint4*>(xt + buf * (kBM * kLdsRow) + (r0 + 16 * i) * kLdsRow + cp * 8) = xr[i];
     };
-    auto multiply = [&](f16x8_t (&b)[NMAT][kKC / 16]) {
+    auto multiply = [&](f16x8_t (&b)[NMAT][kKC / 16], int buf) {
+        const __half* xb = xt + buf * (kBM * kLdsRow);
 #pragma unroll
         for (int mt = 0; mt < kBM / 32; ++mt) {
             if (mt < nmt) {
@@ -243,7 +247,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
 #pragma unroll
                     for (int d = 0; d < SPT; ++d) {
                         const int kl = tl * KT + half * (KT / 2) + 8 * d;
-                        const f16x8_t av = *reinterpret_cast<const f16x8_t*>(xt + (mt * 32 + n) * kLdsRow + kl);
+                        const f16x8_t av = *reinterpret_cast<const f16x8_t*>(xb + (mt * 32 + n) * kLdsRow + kl);
 #pragma unroll
                         for (int i = 0; i < NMAT; ++i)
                             acc[i][mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, b[i][tl * SPT + d], acc[i][mt], 0, 0, 0);
@@ -251,42 +255,48 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
             }
         }
     };
+    // At the top of iteration kc: tile kc & 1 holds chunk kc (a barrier has passed since it was
+    // written), xr holds chunk kc + 1, the weights of chunks kc .. kc + kWRing - 1 are requested.
+    static_assert(kWRing == 2, "ring slot and LDS tile of a chunk are both kc & 1");
     int kc_done = 0;
+    const bool steady = BITS == 4 && wlive && nchunk >= kWRing;
     // (int4 only: the int8 instantiation holds twice the tiles per chunk and has no registers
     // left for a second copy of the loop)
-    if (BITS == 4 && wlive && nchunk >= kWRing) {
-        // Steady state without a branch around any load: weights kWRing chunks ahead, the next
-        // activations requested before the refill (loads return in order, and the next
-        // iteration must not wait for that refill).
+    if (steady) {
 #pragma unroll
         for (int u = 0; u < kWRing; ++u) request_w(u, u);
-        load_x(0);
-        // (near the end the requests are clamped to the last chunk instead of being skipped: a
-        // few redundant loads, no branch)
+    } else {
+#pragma unroll
+        for (int u = 0; u < kWRing; ++u)
+            if (wlive && u < nchunk) request_w(u, u);
+    }
+    load_x(0);
+    stage_x(0);
+    load_x(min(1, nchunk - 1));
+    lds_only_barrier();
+    if (steady) {
+        // Steady state without a branch around any load: weights kWRing chunks ahead, the
+        // activations after next requested before the refill (loads return in order, and the
+        // next iteration must not wait for that refill).  Near the end the requests are clamped
+        // to the last chunk instead of being skipped: a few redundant loads, no branch.
         const int nfull = nchunk / kWRing * kWRing;
         for (int kc0 = 0; kc0 < nfull; kc0 += kWRing) {
 #pragma unroll
             for (int u = 0; u < kWRing; ++u) {
                 const int kc = kc0 + u;
-                lds_only_barrier();   // everyone is done reading the previous chunk
-                stage_x();
-                load_x(min(kc + 1, nchunk - 1));
+                stage_x(u ^ 1);
+                load_x(min(kc + 2, nchunk - 1));
                 f16x8_t b[NMAT][kKC / 16];
 #pragma unroll
                 for (int i = 0; i < NMAT; ++i)
 #pragma unroll
                     for (int tl = 0; tl < TPC; ++tl) dequant_tile<BITS>(raw[u][i][tl], sbits[u][i][tl], &b[i][tl * SPT]);
                 request_w(u, min(kc + kWRing, nchunk - 1));
-                lds_only_barrier();
-                multiply(b);
+                multiply(b, u);
+                lds_only_barrier();   // chunk kc + 1 is visible, everyone is done reading chunk kc
             }
         }
         kc_done = nfull;
-    } else {
-#pragma unroll
-        for (int u = 0; u < kWRing; ++u)
-            if (wlive && u < nchunk) request_w(u, u);
-        load_x(0);
     }
     // the last chunks (and shapes with a short K, or a wave without weight rows)
     for (int kc0 = kc_done; kc0 < nchunk; kc0 += kWRing) {
@@ -294,9 +304,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
         for (int u = 0; u < kWRing; ++u) {
             const int kc = kc0 + u;
             if (kc < nchunk) {
-                lds_only_barrier();
-                stage_x();
-                if (kc + 1 < nchunk) load_x(kc + 1);
+                if (kc + 1 < nchunk) stage_x(u ^ 1);
+                if (kc + 2 < nchunk) load_x(kc + 2);
                 f16x8_t b[NMAT][kKC / 16];
                 if (wlive) {
 #pragma unroll
@@ -305,9 +314,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
                         for (int tl = 0; tl < TPC; ++tl)
                             dequant_tile<BITS>(raw[u][i][tl], sbits[u][i][tl], &b[i][tl * SPT]);
                     if (kc + kWRing < nchunk) request_w(u, kc + kWRing);
+                    multiply(b, u);
                 }
                 lds_only_barrier();
-                if (wlive) multiply(b);
             }
         }
     }
@@ -334,7 +343,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
 template <int NMAT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void grouped_gemm_kernel(GemmArgs a) {
     constexpr int kBM = NMAT == 2 ? kBMUp : kBMDown;
-    __shared__ __align__(16) __half xt[kBM * kLdsRow];
+    __shared__ __align__(16) __half xt[2 * kBM * kLdsRow];
     __shared__ int arow[kBM];
     const int nseg = a.E + a.n_shared;
     // the shared experts' segments come last in the table and hold the fullest tiles: they go first
