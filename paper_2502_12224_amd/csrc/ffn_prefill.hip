@@ -106,17 +106,35 @@ __global__ __launch_bounds__(256) void prefill_prep_kernel(const uint16_t* __res
         __syncthreads();
         if (tid == 0) sgate[t] = 1.0f / (1.0f + expf(-((red[0] + red[1]) + (red[2] + red[3]))));
     }
-    if (t == 0 && tid == 0) {
+    if (t == 0 && wave == 0) {
+        // tile tables: exclusive prefix sums over the segments, 64 segments per step of one wave
+        const int nseg = E + n_shared;
         int ru = 0, rd = 0;
-        for (int s = 0; s < E + n_shared; ++s) {
-            const int T = s < E ? offsets[s + 1] - offsets[s] : N;
-            tab_up[s] = ru;
-            tab_down[s] = rd;
-            ru += ((T + kBMUp - 1) / kBMUp) * (s < E ? nb_r_up : nb_s_up);
-            rd += ((T + kBMDown - 1) / kBMDown) * (s < E ? nb_r_down : nb_s_down);
+        for (int s0 = 0; s0 < nseg; s0 += 64) {
+            const int s = s0 + lane;
+            int cu = 0, cd = 0;
+            if (s < nseg) {
+                const int T = s < E ? offsets[s + 1] - offsets[s] : N;
+                cu = ((T + kBMUp - 1) / kBMUp) * (s < E ? nb_r_up : nb_s_up);
+                cd = ((T + kBMDown - 1) / kBMDown) * (s < E ? nb_r_down : nb_s_down);
+            }
+            int iu = cu, id = cd;
+#pragma unroll
+            for (int sh = 1; sh < 64; sh <<= 1) {
+                const int pu = __shfl_up(iu, sh, 64), pd = __shfl_up(id, sh, 64);
+                if (lane >= sh) { iu += pu; id += pd; }
+            }
+            if (s < nseg) {
+                tab_up[s] = ru + iu - cu;
+                tab_down[s] = rd + id - cd;
+            }
+            ru += __shfl(iu, 63, 64);
+            rd += __shfl(id, 63, 64);
         }
-        tab_up[E + n_shared] = ru;
-        tab_down[E + n_shared] = rd;
+        if (lane == 0) {
+            tab_up[nseg] = ru;
+            tab_down[nseg] = rd;
+        }
     }
 }
 
