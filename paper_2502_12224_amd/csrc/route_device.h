@@ -331,14 +331,28 @@ __device__ inline void block_permute(const int32_t* ids, int P, int E, int32_t* 
     const int end = min(P, beg + chunk);
     const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 
+    // the wave's first kPermCache * 64 ids stay in registers for both passes, requested at once
+    constexpr int kPermCache = 8;
+    int ec[kPermCache];
+#pragma unroll
+    for (int it = 0; it < kPermCache; ++it) {
+        const int i = beg + 64 * it + lane;
+        ec[it] = (i < end) ? ids[i] : -1;
+    }
     for (int i = tid; i < nw * E; i += nthreads) wc[i] = 0;
     __syncthreads();
-    for (int base = beg; base < end; base += 64) {
+    auto count_step = [&](int base, int e) {
         int i = base + lane;
-        int e = (i < end) ? ids[i] : -1;
         bool valid = (i < end) && e >= 0 && e < E;
         unsigned long long mk = wave_match(e, valid, nbits);
         if (valid && (mk & lt) == 0) wc[wave * E + e] += __popcll(mk);
+    };
+#pragma unroll
+    for (int it = 0; it < kPermCache; ++it)
+        if (beg + 64 * it < end) count_step(beg + 64 * it, ec[it]);
+    for (int base = beg + 64 * kPermCache; base < end; base += 64) {
+        int i = base + lane;
+        count_step(base, (i < end) ? ids[i] : -1);
     }
     __syncthreads();
     for (int e = tid; e < E; e += nthreads) {
@@ -380,9 +394,8 @@ __device__ inline void block_permute(const int32_t* ids, int P, int E, int32_t* 
         if (lane == 63) offsets[E] = inc;
     }
     __syncthreads();
-    for (int base = beg; base < end; base += 64) {
+    auto place_step = [&](int base, int e) {
         int i = base + lane;
-        int e = (i < end) ? ids[i] : -1;
         bool valid = (i < end) && e >= 0 && e < E;
         unsigned long long mk = wave_match(e, valid, nbits);
         int b = valid ? wc[wave * E + e] : 0;
@@ -394,14 +407,26 @@ __device__ inline void block_permute(const int32_t* ids, int P, int E, int32_t* 
             inv_perm[i] = -1;
         }
         if (valid && (mk & lt) == 0) wc[wave * E + e] = b + __popcll(mk);
+    };
+#pragma unroll
+    for (int it = 0; it < kPermCache; ++it)
+        if (beg + 64 * it < end) place_step(beg + 64 * it, ec[it]);
+    for (int base = beg + 64 * kPermCache; base < end; base += 64) {
+        int i = base + lane;
+        place_step(base, (i < end) ? ids[i] : -1);
     }
-    for (int e = tid; e < E; e += nthreads) {
-        int c = tot[e], r = 0;
-        for (int o = 0; o < E; ++o) {
-            int co = tot[o];
-            r += (co > c) || (co == c && o < e);
-        }
-        order[r] = e;
+    // experts by (count descending, id ascending): lane o holds the totals of experts o, o + 64,
+    // ..; an expert's rank is the number of experts that come before it, counted by ballots
+    int cl[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) cl[g] = (lane + 64 * g < E) ? tot[lane + 64 * g] : -1;
+    for (int e = wave; e < E; e += nw) {
+        const int c = tot[e];
+        int r = 0;
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            r += __popcll(__ballot(cl[g] > c || (cl[g] == c && lane + 64 * g < e)));
+        if (lane == 0) order[r] = e;
     }
 }
 
