@@ -90,6 +90,10 @@ __global__ __launch_bounds__(512) void route_mfma_kernel(const uint16_t* __restr
     // ntok <= 32 tokens per workgroup: with few tokens in the call, fewer rows of the 32-row
     // product are live but more workgroups share the work (each still reads all of Wg)
     extern __shared__ float zs[];                 // [4 quarters][32 tokens][Epad]
+    // popularity counts of this workgroup's tokens: added up here first, so that the device-wide
+    // histogram takes one atomic per workgroup and expert instead of one per token and expert
+    // (atomics on one address are served one after the other, and popular experts are popular)
+    __shared__ int32_t pop_s[kMaxE];
     if (blockIdx.y == 1) {                        // the second gate of the same launch (next layer's)
         Wg = g2.Wg; bias = g2.bias; m = g2.m; renorm = 0; ids = g2.ids; w = g2.w; probs = nullptr; pop = g2.pop;
     }
@@ -149,12 +153,19 @@ __global__ __launch_bounds__(512) void route_mfma_kernel(const uint16_t* __restr
         const size_t o = (size_t)t * Epad + e, q = (size_t)kGemmTok * Epad;
         zs[o] = ((zs[o] + zs[o + q]) + (zs[o + 2 * q] + zs[o + 3 * q])) + (bias ? bias[e] : 0.f);
     }
+    if (pop)
+        for (int i = threadIdx.x; i < E; i += 512) pop_s[i] = 0;
     __syncthreads();
     for (int t = wave; t < ntok; t += 8) {
         const int tk = t0 + t;
         if (tk < N)
             wave_softmax_topm(zs + (size_t)t * Epad, E, m, renorm, ids + (size_t)tk * m, w + (size_t)tk * m,
-                              probs ? probs + (size_t)tk * E : nullptr, pop);
+                              probs ? probs + (size_t)tk * E : nullptr, pop ? pop_s : nullptr);
+    }
+    if (pop) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < E; i += 512)
+            if (pop_s[i]) atomicAdd(&pop[i], pop_s[i]);
     }
 }
 
