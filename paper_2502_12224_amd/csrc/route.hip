@@ -76,6 +76,8 @@ __global__ __launch_bounds__(256) void route_rows_kernel(const uint16_t* __restr
 // per token does softmax and selection as in the other kernels.
 struct RouteSecond {             // arguments of the second gate (grid.y = 2); unused when grid.y = 1
     const uint16_t* Wg; const float* bias; int m; int32_t* ids; float* w; int32_t* pop;
+    int32_t* pop_part;           // [workgroups][E]: when set, a workgroup leaves its counts here (plain stores)
+                                 // for the permutation kernel to add up, and pop needs neither zeroing nor atomics
 };
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float rf32x16_t;
@@ -94,8 +96,10 @@ __global__ __launch_bounds__(512) void route_mfma_kernel(const uint16_t* __restr
     // histogram takes one atomic per workgroup and expert instead of one per token and expert
     // (atomics on one address are served one after the other, and popular experts are popular)
     __shared__ int32_t pop_s[kMaxE];
+    int32_t* pop_part = nullptr;
     if (blockIdx.y == 1) {                        // the second gate of the same launch (next layer's)
         Wg = g2.Wg; bias = g2.bias; m = g2.m; renorm = 0; ids = g2.ids; w = g2.w; probs = nullptr; pop = g2.pop;
+        pop_part = g2.pop_part;
     }
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, half = lane >> 5;
@@ -164,15 +168,36 @@ __global__ __launch_bounds__(512) void route_mfma_kernel(const uint16_t* __restr
     }
     if (pop) {
         __syncthreads();
-        for (int i = threadIdx.x; i < E; i += 512)
-            if (pop_s[i]) atomicAdd(&pop[i], pop_s[i]);
+        if (pop_part) {
+            for (int i = threadIdx.x; i < E; i += 512) pop_part[(size_t)blockIdx.x * E + i] = pop_s[i];
+        } else {
+            for (int i = threadIdx.x; i < E; i += 512)
+                if (pop_s[i]) atomicAdd(&pop[i], pop_s[i]);
+        }
     }
 }
 
 __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict__ ids, int P, int E,
                                                        int32_t* counts, int32_t* offsets, int32_t* perm,
-                                                       int32_t* inv_perm, int32_t* order) {
+                                                       int32_t* inv_perm, int32_t* order,
+                                                       const int32_t* __restrict__ pop_part, int nparts,
+                                                       int32_t* __restrict__ pop_out) {
     __shared__ int32_t sm[kPermSmemInts];
+    if (pop_part) {
+        // predicted popularity: the routing workgroups' partial histograms [nparts][E] added up
+        // (lane = expert within a group of 64, wave = every 16th partial row)
+        __shared__ int32_t hist[kMaxE];
+        const int lane = threadIdx.x & 63, row = threadIdx.x >> 6;
+        for (int i = threadIdx.x; i < E; i += 1024) hist[i] = 0;
+        __syncthreads();
+        for (int e = lane; e < E; e += 64) {
+            int sum = 0;
+            for (int p = row; p < nparts; p += 16) sum += pop_part[(size_t)p * E + e];
+            if (sum) atomicAdd(&hist[e], sum);
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < E; i += 1024) pop_out[i] = hist[i];
+    }
     if (P <= 64) {
         if (threadIdx.x < 64) wave_permute_small(ids, P, E, counts, offsets, perm, inv_perm, order);
         return;
@@ -219,6 +244,10 @@ static int pick_tpw(int N, int H, int E) {
     return 1;
 }
 
+// tokens per workgroup of the gate GEMM: enough workgroups for the device before the tile is
+// filled with tokens
+static int route_mfma_ntok(int N) { return N > 4096 ? 32 : (N > 1024 ? 16 : 8); }
+
 static fate_status launch_route_mfma(hipStream_t st, const void* x, const void* Wg, const float* bias, int N, int H,
                                      int E, int m, bool renorm, int32_t* ids, float* w, float* probs, int32_t* pop,
                                      RouteSecond second, int ngates) {
@@ -229,8 +258,7 @@ static fate_status launch_route_mfma(hipStream_t st, const void* x, const void* 
                                      hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kGemmTok * kMaxE * 4));
         attr_done = true;
     }
-    // enough workgroups for the device before the tile is filled with tokens
-    const int ntok = N > 4096 ? 32 : (N > 1024 ? 16 : 8);
+    const int ntok = route_mfma_ntok(N);
     route_mfma_kernel<<<dim3((N + ntok - 1) / ntok, ngates), 512, lds_g, st>>>(
         static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(Wg), bias, N, H, E, m, renorm, ids, w, probs, pop,
         ntok, second);
@@ -297,7 +325,7 @@ extern "C" fate_status fate_permute(void* stream, const int32_t* topk_ids, int N
     if (N > 0 && (topk_ids == nullptr || perm == nullptr || inv_perm == nullptr))
         FATE_FAIL(FATE_EINVAL, "topk_ids, perm and inv_perm must not be NULL when N > 0");
     permute_kernel<<<1, 1024, 0, static_cast<hipStream_t>(stream)>>>(topk_ids, N * k, E, counts, offsets, perm,
-                                                                    inv_perm, expert_order);
+                                                                    inv_perm, expert_order, nullptr, 0, nullptr);
     FATE_HIP(hipGetLastError());
     return FATE_OK;
 }
@@ -335,16 +363,17 @@ extern "C" fate_status fate_route_fused(void* stream, const void* x_bf16, const 
     FATE_CHECK_PTR(workspace);
     if (big) {
         hipStream_t st = static_cast<hipStream_t>(stream);
-        if (Wg_next_bf16) {
-            fill_i32_kernel<<<(E + 255) / 256, 256, 0, st>>>(pred_pop, E, 0);
-            FATE_HIP(hipGetLastError());
-        }
+        // the workgroups' popularity counts go through the workspace and are added up by the
+        // permutation kernel: no zeroing launch, no atomics on the device-wide histogram
+        const int ntok = route_mfma_ntok(N), nparts = (N + ntok - 1) / ntok;
+        int32_t* pop_part = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + 256);
         s = launch_route_mfma(st, x_bf16, Wg_bf16, bias, N, H, E, k, renorm != 0, topk_ids, topk_w, nullptr, nullptr,
                               RouteSecond{static_cast<const uint16_t*>(Wg_next_bf16), bias_next, m, pred_ids, pred_w,
-                                          pred_pop},
+                                          pred_pop, pop_part},
                               Wg_next_bf16 ? 2 : 1);
         if (s != FATE_OK) return s;
-        permute_kernel<<<1, 1024, 0, st>>>(topk_ids, N * k, E, counts, offsets, perm, inv_perm, expert_order);
+        permute_kernel<<<1, 1024, 0, st>>>(topk_ids, N * k, E, counts, offsets, perm, inv_perm, expert_order,
+                                           Wg_next_bf16 ? pop_part : nullptr, nparts, pred_pop);
         FATE_HIP(hipGetLastError());
         return FATE_OK;
     }
