@@ -19,6 +19,7 @@
 // (exact code, one rounding in code*scale), which is the B operand of
 // v_mfma_f32_32x32x16_f16.  Accumulation is fp32.
 #include <hip/hip_fp16.h>
+#include <algorithm>
 #include "common.h"
 #include "qformat.h"
 #include "ffn_internal.h"
@@ -459,6 +460,11 @@ fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs d
     if (d.H % kKC || d.I_max % kKC || (d.n_shared && d.I_shared_max % kKC))
         FATE_FAIL(FATE_ESHAPE, "the MFMA path needs H and I to be multiples of %d", kKC);
     const int P = d.N * d.k;
+    // the GEMM addresses activation rows with 32-bit element offsets
+    const long long amax = std::max({(long long)d.N * d.H, (long long)P * da.ldh_r,
+                                     (long long)d.n_shared * d.N * da.ldh_s});
+    if (amax >= (1LL << 31))
+        FATE_FAIL(FATE_ESHAPE, "the MFMA path needs activation matrices of fewer than 2^31 elements (%lld)", amax);
     const int nseg = d.E + d.n_shared;
     const int nb_r_up = (d.I_max + kBN - 1) / kBN, nb_s_up = d.n_shared ? (d.I_shared_max + kBN - 1) / kBN : 0;
     const int nb_down = (d.H + kBN - 1) / kBN;
