@@ -169,7 +169,9 @@ typedef struct {
  * routed experts and of the shared experts are passed host-side as well and
  * must match the table entries.
  * mode: 0 = choose (decode kernels if N <= 16, else MFMA), 1 = decode
- * dequant-GEMV kernels, 2 = MFMA grouped GEMM.
+ * dequant-GEMV kernels, 2 = MFMA grouped GEMM (H and the intermediate sizes
+ * multiples of 128; N*H, N*k*I_max and n_shared*N*I_shared_max below 2^31;
+ * FATE_ESHAPE otherwise).
  * Activated experts whose w1 is NULL are skipped and flagged: the int32 at
  * workspace offset 0 is set non-zero (check with fate_moe_ffn_q_status).
  * ---------------------------------------------------------------------- */
