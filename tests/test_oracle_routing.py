@@ -140,3 +140,38 @@ def test_near_tie_rows():
     z = np.array([[3.0, 2.0, 1.0, 0.0], [3.0, 2.0, 2.0 - 1e-6, 0.0], [3.0, 3.0 - 1e-7, 1.0, 0.0]])
     assert O.near_tie_rows(z, 2).tolist() == [1, 2]
     assert O.near_tie_rows(z, 1).tolist() == [2]
+
+
+def test_prediction_accuracy_on_the_papers_near_miss_example():
+    """Section 4.2, "Similar Routing Weights": the true top-4 of a token is
+    [5, 21, 31, 36], the prediction [5, 11, 21, 36]; three of four are right,
+    and the missed expert 31 ranks fifth in the prediction, so a set widened
+    to five recovers it."""
+    true = np.array([[5, 21, 31, 36]])
+    acc_k, rec_m = O.prediction_accuracy(np.array([[5, 11, 21, 36]]), true, 4)
+    assert (acc_k, rec_m) == (0.75, 0.75)
+    acc_k, rec_m = O.prediction_accuracy(np.array([[5, 11, 21, 36, 31]]), true, 4)
+    assert (acc_k, rec_m) == (0.75, 1.0)
+    # the denominator is k (not the width of the prediction) and the mean runs over tokens:
+    # a second token predicted perfectly, and a third with nothing right
+    true3 = np.array([[5, 21, 31, 36], [0, 1, 2, 3], [0, 1, 2, 3]])
+    pred3 = np.array([[5, 11, 21, 36, 31, 7], [3, 2, 1, 0, 9, 8], [4, 5, 6, 7, 8, 9]])
+    acc_k, rec_m = O.prediction_accuracy(pred3, true3, 4)
+    assert acc_k == pytest.approx((0.75 + 1.0 + 0.0) / 3) and rec_m == pytest.approx((1.0 + 1.0 + 0.0) / 3)
+    # only the first k true entries count as the true top-k; the arguments are not interchangeable
+    assert O.prediction_accuracy(np.array([[9, 8, 5, 21]]), np.array([[5, 21, 9, 8]]), 2) == (0.0, 1.0)
+    assert O.prediction_accuracy(np.array([[5, 21, 9, 8]]), np.array([[9, 8, 5, 21]]), 2) == (0.0, 1.0)
+    assert O.prediction_accuracy(np.array([[5, 21, 9]]), np.array([[9, 8]]), 2) == (0.0, 0.5)
+    assert O.prediction_accuracy(np.array([[9, 8]]), np.array([[5, 21, 9]]), 2) == (0.0, 0.0)
+
+
+def test_prefill_set_accuracy_hand_case():
+    """Prefill metric of section 4.2 / table 1 (set level): the share of the experts
+    a layer really activates, over all tokens, that the prediction's union holds."""
+    true = np.array([[1, 2], [2, 3], [3, 4]])            # union {1,2,3,4}
+    pred = np.array([[1, 2, 9], [2, 9, 8], [3, 9, 7]])   # union {1,2,3,7,8,9}: 3 of the 4 true ones
+    assert O.prefill_set_accuracy(pred, true) == 0.75
+    # not symmetric: 3 of the 6 predicted are true
+    assert O.prefill_set_accuracy(true, pred) == 0.5
+    assert O.prefill_set_accuracy(true, true) == 1.0
+    assert O.prefill_set_accuracy(np.array([[5, 6]]), true) == 0.0
