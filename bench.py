@@ -147,14 +147,12 @@ def bench_decode(args):
     log(f"[bench] chained {S} decode steps ({time.time() - t0:.0f}s)")
     t_ids = true_ids.cpu().numpy()       # [S, L, N, k]
     p_ids = pred_ids.cpu().numpy()       # [S, L, N, m]  (prediction made at layer l for layer l+1)
-    acc_k = rec_m = 0.0
-    for s in range(S):
-        for l in range(L - 1):
-            tr = set(t_ids[s, l + 1, 0].tolist())
-            acc_k += len(tr & set(p_ids[s, l, 0, :cfg.k].tolist())) / cfg.k
-            rec_m += len(tr & set(p_ids[s, l, 0].tolist())) / cfg.k
-    acc_k /= S * (L - 1)
-    rec_m /= S * (L - 1)
+    # reporting (untimed): the oracle's definitions of the accuracy figures, the prediction made
+    # at layer l against the true routing of layer l+1
+    from oracle import moe as O
+    acc = [O.prediction_accuracy(p_ids[s, l], t_ids[s, l + 1], cfg.k) for s in range(S) for l in range(L - 1)]
+    acc_k = float(np.mean([v[0] for v in acc]))
+    rec_m = float(np.mean([v[1] for v in acc]))
 
     # per-layer buffers whose counts / predicted popularity sit in one arena
     bufs = [LayerBuffers(cfg, N, dev) for _ in range(L)]
@@ -341,10 +339,10 @@ def bench_prefill(args, emit=True):
     xs, true_ids, pred_ids = stack.chain(N, 1)          # gate inputs of every layer (untimed chain)
     torch.cuda.synchronize()
     t_ids, p_ids = true_ids.cpu().numpy()[0], pred_ids.cpu().numpy()[0]
-    set_acc = np.mean([len(set(p_ids[l].ravel()) & set(t_ids[l + 1].ravel())) / len(set(t_ids[l + 1].ravel()))
-                       for l in range(L - 1)]) if L > 1 else None
-    tok_acc = np.mean([np.mean([len(set(p_ids[l, t, :cfg.k]) & set(t_ids[l + 1, t])) / cfg.k for t in range(N)])
-                       for l in range(L - 1)]) if L > 1 else None
+    from oracle import moe as O      # reporting (untimed): the oracle's definitions of the accuracy figures
+    set_acc = float(np.mean([O.prefill_set_accuracy(p_ids[l], t_ids[l + 1]) for l in range(L - 1)])) if L > 1 else None
+    tok_acc = float(np.mean([O.prediction_accuracy(p_ids[l], t_ids[l + 1], cfg.k)[0]
+                             for l in range(L - 1)])) if L > 1 else None
     active = float(np.mean([len(set(t_ids[l].ravel())) for l in range(L)]))
 
     bufs = [LayerBuffers(cfg, N, dev, mode=2) for _ in range(L)]

@@ -20,7 +20,9 @@ Pins (tests/test_oracle_*.py): softmax against scipy and its invariants,
 top-k against a full sort and constructed ties, prediction identity,
 permutation against numpy's stable argsort and bijection properties,
 dequantisation round trips and a hand-computed group, FFN against a torch
-fp64 dense SwiGLU MLP in the one-expert case plus linearity properties.
+fp64 dense SwiGLU MLP in the one-expert case plus linearity properties,
+the expert-by-expert form of the FFN against the pair-by-pair definition,
+the accuracy metrics against the paper's near-miss example and hand cases.
 """
 import numpy as np
 
@@ -231,6 +233,34 @@ def moe_ffn(x, ids, w, experts, shared=(), shared_gate=None):
         if shared_gate is not None:
             sg = np.asarray(shared_gate, dtype=np.float64)
             g = 1.0 / (1.0 + np.exp(-(x @ sg)))
+        else:
+            g = np.ones(N, dtype=np.float64)
+        for ex in shared:
+            out, _ = expert_ffn(x, ex)
+            y += g[:, None] * out
+    return y
+
+
+def moe_ffn_grouped(x, ids, w, experts, shared=(), shared_gate=None):
+    """The same sum as moe_ffn, taken expert by expert instead of token by token:
+    the rows routed to an expert go through it as one fp64 matrix product, and
+    their outputs are scattered back with their routing weights.  Nothing else
+    changes (same dequantised matrices, same SwiGLU body), so it agrees with
+    moe_ffn up to the order of the fp64 additions; it exists because the
+    pair-by-pair form takes minutes on a full prefill layer.  Pinned against
+    moe_ffn in tests/test_oracle_ffn.py."""
+    x = np.asarray(x, dtype=np.float64)
+    N, H = x.shape
+    ids = np.asarray(ids)
+    w = np.asarray(w, dtype=np.float64)
+    y = np.zeros((N, H), dtype=np.float64)
+    for e in sorted(set(int(v) for v in ids.ravel())):
+        t_idx, j_idx = np.nonzero(ids == e)
+        out, _ = expert_ffn(x[t_idx], experts[e])
+        np.add.at(y, t_idx, w[t_idx, j_idx][:, None] * out)
+    if len(shared):
+        if shared_gate is not None:
+            g = 1.0 / (1.0 + np.exp(-(x @ np.asarray(shared_gate, dtype=np.float64))))
         else:
             g = np.ones(N, dtype=np.float64)
         for ex in shared:

@@ -146,3 +146,42 @@ def test_ffn_rows_subset():
     experts = {e: _oracle_expert(gen_expert(cfg, 0, e)) for e in range(cfg.E)}
     y = O.moe_ffn(x, ids, w, experts)
     assert np.array_equal(O.moe_ffn_rows(x, ids, w, experts, rows=[5, 2]), y[[5, 2]])
+
+
+def _grouped_vs_pairs(name, N, layer=0):
+    cfg = SHAPES[name]
+    x = _f(gen_hidden(cfg, N))
+    Wg, b = gen_gate(cfg, layer)
+    ids, w, _, _ = O.gate_route(x, _f(Wg), None if b is None else b.numpy(), cfg.k, cfg.renorm)
+    experts = {e: _oracle_expert(gen_expert(cfg, layer, e)) for e in sorted(set(ids.ravel().tolist()))}
+    shared = [_oracle_expert(gen_expert(cfg, layer, s, shared=True)) for s in range(cfg.n_shared)]
+    sg = gen_shared_gate(cfg, layer)
+    sg = None if sg is None else _f(sg)
+    y_pairs = O.moe_ffn(x, ids, w, experts, shared, sg)
+    y_grouped = O.moe_ffn_grouped(x, ids, w, experts, shared, sg)
+    return y_pairs, y_grouped, ids
+
+
+def test_grouped_ffn_form_equals_the_pairwise_definition_tiny():
+    y_pairs, y_grouped, ids = _grouped_vs_pairs("tiny", 16)
+    assert len(set(ids.ravel().tolist())) > 2
+    assert np.allclose(y_grouped, y_pairs, rtol=1e-12, atol=1e-16)
+    # a dropped routing weight or a scatter to the wrong token would not pass
+    assert not np.allclose(y_grouped[::-1], y_pairs, rtol=1e-3)
+
+
+def test_grouped_ffn_form_equals_the_pairwise_definition_qwen_rows():
+    """Eight token rows of the Qwen1.5-MoE-shaped layer (60 experts top-4, gated shared expert)."""
+    y_pairs, y_grouped, ids = _grouped_vs_pairs("qwen", 8)
+    assert np.allclose(y_grouped, y_pairs, rtol=1e-12, atol=1e-16)
+
+
+def test_grouped_ffn_repeated_expert_and_empty_cases():
+    cfg = SHAPES["tiny"]
+    x = _f(gen_hidden(cfg, 4))
+    experts = {e: _oracle_expert(gen_expert(cfg, 0, e)) for e in (1, 2)}
+    ids = np.array([[1, 2], [2, 1], [1, 2], [2, 1]], dtype=np.int32)
+    w = np.random.default_rng(1).uniform(0.1, 1.0, size=(4, 2))
+    assert np.allclose(O.moe_ffn_grouped(x, ids, w, experts), O.moe_ffn(x, ids, w, experts), rtol=1e-12, atol=1e-16)
+    empty = O.moe_ffn_grouped(x[:0], ids[:0], w[:0], experts)
+    assert empty.shape == (0, cfg.H)
