@@ -8,7 +8,9 @@
 // Before a step the caller hands in the
 // event it recorded after the previous layer's FFN; both streams wait for it,
 // so a slot released in the previous step is not overwritten while a kernel
-// may still read it.  After a step the compute stream waits for the events of
+// may still read it.  A slot whose last copy was never waited for (an unused
+// prefetch) is re-targeted only after a wait for that copy's event on the
+// stream of the new copy.  After a step the compute stream waits for the events of
 // the slots the current layer uses.  Table entries are written by a one-thread
 // kernel on the compute stream (arguments travel by value with the launch).
 #include <vector>
@@ -108,6 +110,9 @@ extern "C" int fate_hip_engine_copy(void* engine, int layer, int expert, int slo
     const size_t nb = g->lay.slot_bytes;
     hipStream_t cs = g->flip ? g->copy2 : g->copy_stream;
     g->flip ^= 1;
+    // An earlier copy into this slot that nobody waited for (a prefetch that went unused) may
+    // still be in flight on the other stream: order this copy after it.
+    if (g->ev_live[slot] && hipStreamWaitEvent(cs, g->ev[slot], 0) != hipSuccess) return 5;
     if (hipMemcpyAsync(g->pool + (size_t)slot * nb, g->host + ((size_t)layer * g->E + expert) * nb, nb,
                        hipMemcpyHostToDevice, cs) != hipSuccess)
         return 2;

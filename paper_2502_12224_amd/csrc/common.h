@@ -63,8 +63,13 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
 // Relaxed atomics at device scope: the accesses go past the per-XCD L2 to the
 // point where all compute dies agree, so no cache-wide write-back or
 // invalidate is needed around them.  Ordering comes from the producer waiting
-// for its stores (a workgroup barrier does that) before it bumps a counter,
-// and from the consumer reading the counter before the data.
+// for its stores before it bumps a counter, and from the consumer reading the
+// counter before the data.  A workgroup barrier alone does not wait for a
+// wave's outstanding global stores (waves of one workgroup share their vector
+// cache, so a workgroup-scope release needs no such wait): every wave calls
+// wait_own_stores() before the barrier that precedes the counter update, or
+// the data validates itself (values tagged with the call's epoch).
+__device__ __forceinline__ void wait_own_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void st_dev(int32_t* p, int32_t v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

@@ -213,7 +213,8 @@ __global__ __launch_bounds__(256) void route_fused_kernel(FusedRouteArgs a, int3
     __shared__ int32_t sm_perm[kPermSmemInts];
     __shared__ int sm_last;
     fused_gate_rows(a, blockIdx.x, ZbufStore{a.zbuf, a.N, a.E});
-    __syncthreads();        // every wave's logit stores have completed
+    wait_own_stores();      // this wave's device-scope logit stores have been acknowledged
+    __syncthreads();        // ... and so have every other wave's
     if (threadIdx.x == 0) sm_last = (atomicAdd(ticket, 1) == (int)gridDim.x - 1);
     __syncthreads();
     if (!sm_last) return;

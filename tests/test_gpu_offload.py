@@ -55,3 +55,75 @@ def test_offloaded_stack_matches_resident_and_oracle(N, cache_total, n_max, L_sh
     if cache_total >= L * E:
         assert misses == 0
     off.close()
+
+
+def _offload_case(cfg, L, cache_total, L_shallow, n_max, N, steps, check_steps):
+    """Offloaded stack at a model's real expert size: decisions against the cache oracle on every
+    step, y against the FFN oracle (fed by the oracle's own routing) on the first `check_steps`
+    steps.  No device-wide synchronisation inside a step: the copy streams keep their backlog
+    while the next layers run, and y of every layer is compared after the step."""
+    from oracle import moe as O
+    from workloads import gen_expert
+    from helpers import bias_np, f32, ffn_rel_err, oracle_expert
+    E = cfg.E
+    staging = 2 * E + n_max
+    off = OffloadedStack(cfg, cache_total, n_max, staging, DEV, layers=L, L_shallow=L_shallow)
+    off.keep_trace = True
+    sim = OC.CacheOracle(L, E, cache_total, L_shallow, n_max, staging)
+    assert off.caps == sim.caps and off.total_slots == sim.total_slots
+    print(f"{cfg.name}: {L} layers, capacities {off.caps}, slot {off.slot_bytes / 1e6:.2f} MB, n_max {n_max}", flush=True)
+    buf = LayerBuffers(cfg, N, DEV)
+    worst = 0.0
+    loads_total = 0
+    for step in range(steps):
+        h = gen_hidden(cfg, N, step=step, device=DEV).float()
+        kept = []
+        for l in range(L):
+            x = unit_rmsnorm_bf16(h)
+            ntr = len(off.trace)
+            y = off.layer(l, x, buf)
+            status = buf.ffn_ws[:4].view(torch.int32).clone()
+            kept.append((x, buf.ids.clone(), buf.w.clone(), buf.counts.clone(), buf.pred_pop.clone(), y.clone(),
+                         status, off.trace[ntr]))
+            h = chain_next_hidden(h, y)
+        torch.cuda.current_stream().synchronize()
+        for l, (x, ids, w, counts, pop, y, status, (tl, order, loads)) in enumerate(kept):
+            assert int(status[0]) == 0, "an activated expert was not resident"
+            counts, pop = counts.cpu().numpy(), pop.cpu().numpy()
+            aids = [e for e in range(E) if counts[e] > 0]
+            pids = [e for e in range(E) if pop[e] > 0] if l + 1 < L else []
+            r = sim.step(l, aids, [int(counts[e]) for e in aids], pids, [int(pop[e]) for e in pids])
+            assert tl == l and order == r.compute_order and loads == r.loads, (step, l)
+            loads_total += len(loads)
+            if step < check_steps:
+                Wg, bias = off.gates[l]
+                rid, rw, _, rz = O.gate_route(f32(x), f32(Wg), bias_np(bias), cfg.k, cfg.renorm)
+                assert len(O.near_tie_rows(rz, cfg.k)) == 0
+                assert np.array_equal(ids.cpu().numpy(), rid)
+                experts = {int(e): oracle_expert(gen_expert(cfg, l, int(e), device=DEV)) for e in set(rid.ravel().tolist())}
+                shared = [oracle_expert(gen_expert(cfg, l, s, shared=True, device=DEV)) for s in range(cfg.n_shared)]
+                sg = None if off.shared_gates[l] is None else f32(off.shared_gates[l])
+                y_ref = O.moe_ffn(f32(x), rid, rw, experts, shared, sg)
+                err = ffn_rel_err(f32(y), y_ref).max()
+                worst = max(worst, err)
+                assert err <= 2e-3, (step, l, err)
+        print(f"  step {step}: decisions equal the cache oracle's; worst FFN row error so far {worst:.2e}", flush=True)
+    torch.cuda.synchronize()
+    s = off.stats
+    assert off.bytes_copied() == loads_total * off.slot_bytes == (s["miss"] + s["prefetch"]) * off.slot_bytes
+    assert s["miss"] > 0 and s["hit_cache"] > 0
+    off.close()
+
+
+def test_offloaded_deepseek_shape_against_both_oracles():
+    """configs[3] geometry on five layers: one fully cached shallow layer and four deep layers with the
+    14 / 13 slots the 30 % budget gives the real 28-layer stack; 4.46 MB experts, batch 8."""
+    cfg = SHAPES["deepseek"]
+    _offload_case(cfg, L=5, cache_total=64 + 14 + 14 + 13 + 13, L_shallow=1, n_max=8, N=8, steps=5, check_steps=2)
+
+
+def test_offloaded_mixtral_shape_against_both_oracles():
+    """configs[4] geometry on three layers: 90.8 MB experts, one shallow layer full and two of eight
+    experts cached in each deep layer (25 %), batch 1."""
+    cfg = SHAPES["mixtral"]
+    _offload_case(cfg, L=3, cache_total=8 + 2 + 2, L_shallow=1, n_max=1, N=1, steps=6, check_steps=2)
