@@ -406,15 +406,16 @@ def bench_prefill(args, emit=True):
         e0.record()
         for _ in range(reps):
             for l in range(L):
-                bufs[l].desc.phases = phase
-                B.fate_moe_ffn_q(bufs[l].desc, x_in[l], stack.layers[l].table, bufs[l].counts, bufs[l].offsets,
-                                 bufs[l].perm, bufs[l].inv_perm, bufs[l].order, bufs[l].w,
-                                 stack.layers[l].shared_table, stack.layers[l].shared_gate, bufs[l].y, bufs[l].ffn_ws)
+                a = (x_in[l], stack.layers[l].table, bufs[l].counts, bufs[l].offsets, bufs[l].perm, bufs[l].inv_perm,
+                     bufs[l].order, bufs[l].w, stack.layers[l].shared_table, stack.layers[l].shared_gate, bufs[l].y,
+                     bufs[l].ffn_ws)
+                if phase:
+                    B.fate_profile_ffn_mfma_phase(bufs[l].desc, phase, *a)
+                else:
+                    B.fate_moe_ffn_q(bufs[l].desc, *a)
         e1.record()
         torch.cuda.synchronize()
         times.append(e0.elapsed_time(e1) * 1e3 / (reps * L))
-    for b in bufs:
-        b.desc.phases = 0
     up_us, ffn_us = times
     achieved = up_flops / (up_us * 1e-6) / 1e12
     log(f"[bench] prep+up GEMM {up_us:.1f} us/layer ({achieved:.0f} TFLOP/s), whole FFN {ffn_us:.1f} us/layer "

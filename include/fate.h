@@ -181,8 +181,7 @@ typedef struct {
     int32_t n_shared, I_shared_max, shared_bits, shared_group;
     int32_t y_is_fp32;
     int32_t mode;
-    int32_t phases;   /* profiling aid: 0 = whole FFN; 1 = first half only (up/gate
-                         projections + SwiGLU into scratch); 2 = second half only */
+    int32_t reserved; /* must be 0 */
 } fate_ffn_desc;
 
 fate_status fate_moe_ffn_q_workspace(const fate_ffn_desc* d, size_t* bytes);
@@ -207,7 +206,7 @@ fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, const void* x_b
  * launches as many as fit, and each takes every n-th item.
  *   out: device pointers for every routing output, sized as in the separate
  *        calls; pred_* may be NULL when Wg_next is NULL (last layer).
- *   d->mode must be 0 or 1, d->phases 0.
+ *   d->mode must be 0 or 1.
  *   workspace: fate_moe_layer_decode_workspace bytes, 256-byte aligned,
  *        zero-filled once by the caller before the first use (each call
  *        leaves its counters at zero).  Calls that share a workspace must be

@@ -20,7 +20,7 @@ STATUS_NAMES = {0: "FATE_OK", 1: "FATE_EINVAL", 2: "FATE_ESHAPE", 3: "FATE_EALIG
 EXPORTS = [
     "fate_last_error", "fate_version", "fate_gate_route", "fate_cross_layer_predict", "fate_permute",
     "fate_route_fused_workspace", "fate_route_fused", "fate_pack_weight", "fate_pack_scales", "fate_moe_ffn_q_workspace",
-    "fate_moe_ffn_q", "fate_moe_layer_decode_workspace", "fate_moe_layer_decode", "fate_cache_total_from_budget", "fate_n_max_from_times", "fate_cache_layer_capacities",
+    "fate_moe_ffn_q", "fate_profile_ffn_mfma_phase", "fate_moe_layer_decode_workspace", "fate_moe_layer_decode", "fate_cache_total_from_budget", "fate_n_max_from_times", "fate_cache_layer_capacities",
     "fate_cache_create", "fate_cache_destroy", "fate_cache_total_slots", "fate_cache_set_n_max", "fate_cache_slot_of",
     "fate_cache_resident", "fate_expert_cache_step", "fate_expert_cache_step_dense",
     "fate_expert_cache_step_layers", "fate_hip_engine_create", "fate_hip_engine_destroy",
@@ -38,7 +38,7 @@ class FateError(RuntimeError):
 class fate_ffn_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("N", "H", "E", "k", "I_max", "bits", "group", "n_shared",
                                          "I_shared_max", "shared_bits", "shared_group", "y_is_fp32", "mode",
-                                         "phases")]
+                                         "reserved")]
 
 
 class fate_qexpert(C.Structure):
@@ -197,6 +197,14 @@ def fate_moe_layer_decode(desc, x, Wg, bias, Wg_next, bias_next, m, renorm, topk
                                        C.c_size_t(workspace.numel() * workspace.element_size())))
 
 
+def fate_profile_ffn_mfma_phase(desc, phase, x, experts_dev, counts, offsets, perm, inv_perm, expert_order, topk_w,
+                                shared_dev, shared_gate, y, workspace, stream=None):
+    _check(lib().fate_profile_ffn_mfma_phase(_stream(stream), C.byref(desc), int(phase), _p(x), _p(experts_dev),
+                                             _p(counts), _p(offsets), _p(perm), _p(inv_perm), _p(expert_order),
+                                             _p(topk_w), _p(shared_dev), _p(shared_gate), _p(y), _p(workspace),
+                                             C.c_size_t(workspace.numel() * workspace.element_size())))
+
+
 def fate_moe_ffn_q_workspace(desc):
     b = C.c_size_t(0)
     _check(lib().fate_moe_ffn_q_workspace(C.byref(desc), C.byref(b)))
@@ -256,6 +264,6 @@ def expert_table(structs, device="cuda"):
 
 
 def make_ffn_desc(N, H, E, k, I_max, bits, group, n_shared=0, I_shared_max=0, shared_bits=4, shared_group=128,
-                  y_is_fp32=True, mode=0, phases=0):
+                  y_is_fp32=True, mode=0):
     return fate_ffn_desc(N, H, E, k, I_max, bits, group, n_shared, I_shared_max, shared_bits, shared_group,
-                         int(y_is_fp32), mode, phases)
+                         int(y_is_fp32), mode, 0)

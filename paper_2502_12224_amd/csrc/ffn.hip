@@ -2,6 +2,7 @@
 #include "common.h"
 #include "ffn_internal.h"
 #include "layer_decode.h"
+#include "../../include/fate_profile.h"
 
 namespace fate {
 
@@ -26,7 +27,7 @@ static fate_status check_desc(const fate_ffn_desc* d) {
             FATE_FAIL(FATE_ESHAPE, "I_shared_max = %d / H must be multiples of 64 and of the shared group", d->I_shared_max);
     }
     if (d->mode < 0 || d->mode > 2) FATE_FAIL(FATE_EINVAL, "mode = %d", d->mode);
-    if (d->phases < 0 || d->phases > 3) FATE_FAIL(FATE_EINVAL, "phases = %d", d->phases);
+    if (d->reserved != 0) FATE_FAIL(FATE_EINVAL, "the descriptor's reserved field must be 0");
     if ((long long)d->N * d->k > 0x3fffffffLL) FATE_FAIL(FATE_ESHAPE, "N*k too large");
     return FATE_OK;
 }
@@ -68,7 +69,7 @@ extern "C" fate_status fate_moe_ffn_q_workspace(const fate_ffn_desc* d, size_t* 
     return FATE_OK;
 }
 
-extern "C" fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, const void* x_bf16,
+static fate_status ffn_q_phase(int phase, void* stream, const fate_ffn_desc* d, const void* x_bf16,
                                       const fate_qexpert* experts_dev, const int32_t* counts,
                                       const int32_t* offsets, const int32_t* perm, const int32_t* inv_perm,
                                       const int32_t* expert_order, const float* topk_w, const fate_qexpert* shared_dev,
@@ -103,8 +104,33 @@ extern "C" fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, cons
     a.status = w.status;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int mode = d->mode ? d->mode : (d->N <= 16 ? 1 : 2);
-    if (mode == 1) return launch_ffn_decode(st, *d, a, y);
-    return launch_ffn_mfma(st, *d, a, w.ms, y);
+    if (mode == 1) {
+        if (phase != 0) FATE_FAIL(FATE_EINVAL, "the decode kernels run the whole FFN only (phase = %d)", phase);
+        return launch_ffn_decode(st, *d, a, y);
+    }
+    return launch_ffn_mfma(st, *d, a, w.ms, y, phase);
+}
+
+extern "C" fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, const void* x_bf16,
+                                      const fate_qexpert* experts_dev, const int32_t* counts,
+                                      const int32_t* offsets, const int32_t* perm, const int32_t* inv_perm,
+                                      const int32_t* expert_order, const float* topk_w, const fate_qexpert* shared_dev,
+                                      const void* shared_gate_bf16, void* y, void* workspace,
+                                      size_t workspace_bytes) {
+    return ffn_q_phase(0, stream, d, x_bf16, experts_dev, counts, offsets, perm, inv_perm, expert_order, topk_w,
+                       shared_dev, shared_gate_bf16, y, workspace, workspace_bytes);
+}
+
+extern "C" fate_status fate_profile_ffn_mfma_phase(void* stream, const fate_ffn_desc* d, int phase,
+                                                   const void* x_bf16, const fate_qexpert* experts_dev,
+                                                   const int32_t* counts, const int32_t* offsets,
+                                                   const int32_t* perm, const int32_t* inv_perm,
+                                                   const int32_t* expert_order, const float* topk_w,
+                                                   const fate_qexpert* shared_dev, const void* shared_gate_bf16,
+                                                   void* y, void* workspace, size_t workspace_bytes) {
+    if (phase != 1 && phase != 2) FATE_FAIL(FATE_EINVAL, "phase = %d (1 = up half, 2 = down half)", phase);
+    return ffn_q_phase(phase, stream, d, x_bf16, experts_dev, counts, offsets, perm, inv_perm, expert_order, topk_w,
+                       shared_dev, shared_gate_bf16, y, workspace, workspace_bytes);
 }
 
 extern "C" fate_status fate_moe_layer_decode_workspace(const fate_ffn_desc* d, size_t* bytes,
@@ -118,16 +144,17 @@ extern "C" fate_status fate_moe_layer_decode_workspace(const fate_ffn_desc* d, s
     return FATE_OK;
 }
 
-extern "C" fate_status fate_moe_layer_decode(void* stream, const fate_ffn_desc* d, const void* x_bf16,
-                                             const void* Wg_bf16, const float* bias, const void* Wg_next_bf16,
-                                             const float* bias_next, int m, int renorm, const fate_route_out* out,
-                                             const fate_qexpert* experts_dev, const fate_qexpert* shared_dev,
-                                             const void* shared_gate_bf16, void* y, void* workspace,
-                                             size_t workspace_bytes) {
-    fate_status s = check_desc(d);
-    if (s != FATE_OK) return s;
+namespace fate {
+
+// Everything of fate_moe_layer_decode after the descriptor check; `status` may point outside
+// the workspace.
+static fate_status layer_decode_checked(void* stream, const fate_ffn_desc* d, const void* x_bf16,
+                                        const void* Wg_bf16, const float* bias, const void* Wg_next_bf16,
+                                        const float* bias_next, int m, int renorm, const fate_route_out* out,
+                                        const fate_qexpert* experts_dev, const fate_qexpert* shared_dev,
+                                        const void* shared_gate_bf16, void* y, void* workspace,
+                                        size_t workspace_bytes, int32_t* status) {
     if (d->mode == 2) FATE_FAIL(FATE_EINVAL, "the fused layer call has no MFMA-GEMM mode");
-    if (d->phases != 0) FATE_FAIL(FATE_EINVAL, "the fused layer call runs all phases");
     if (d->N < 1) FATE_FAIL(FATE_ESHAPE, "fused layer: N = %d < 1", d->N);
     if (m < d->k || m > d->E || m > kMaxM) FATE_FAIL(FATE_EINVAL, "need k <= m <= min(E, %d) (m = %d)", kMaxM, m);
     FATE_CHECK_PTR(x_bf16);
@@ -164,7 +191,21 @@ extern "C" fate_status fate_moe_layer_decode(void* stream, const fate_ffn_desc* 
     a.part_s = reinterpret_cast<float*>(base + w.part_s);
     a.y = y;
     a.y_is_fp32 = d->y_is_fp32;
-    a.status = reinterpret_cast<int32_t*>(base + w.status);
+    a.status = status ? status : reinterpret_cast<int32_t*>(base + w.status);
     a.sync = reinterpret_cast<int32_t*>(base + w.sync);
     return launch_layer_decode(static_cast<hipStream_t>(stream), *d, a);
+}
+
+}  // namespace fate
+
+extern "C" fate_status fate_moe_layer_decode(void* stream, const fate_ffn_desc* d, const void* x_bf16,
+                                             const void* Wg_bf16, const float* bias, const void* Wg_next_bf16,
+                                             const float* bias_next, int m, int renorm, const fate_route_out* out,
+                                             const fate_qexpert* experts_dev, const fate_qexpert* shared_dev,
+                                             const void* shared_gate_bf16, void* y, void* workspace,
+                                             size_t workspace_bytes) {
+    fate_status s = check_desc(d);
+    if (s != FATE_OK) return s;
+    return layer_decode_checked(stream, d, x_bf16, Wg_bf16, bias, Wg_next_bf16, bias_next, m, renorm, out,
+                                experts_dev, shared_dev, shared_gate_bf16, y, workspace, workspace_bytes, nullptr);
 }

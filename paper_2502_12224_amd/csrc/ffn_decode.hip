@@ -280,10 +280,10 @@ fate_status launch_ffn_decode(hipStream_t st, const fate_ffn_desc& d, DecodeArgs
     const int grid_up = a.nact * a.rb_r + d.n_shared * a.rb_s;
     const int nrb = d.H / 32;
     const int grid_down = a.nact * nrb * a.nchunk_r + d.n_shared * nrb * a.nchunk_s;
-    if (d.phases != 2) ffn_up_decode_kernel<<<grid_up, 256, lu, st>>>(a);
-    if (d.phases != 1) ffn_down_decode_kernel<<<grid_down, 256, ld, st>>>(a);
+    ffn_up_decode_kernel<<<grid_up, 256, lu, st>>>(a);
+    ffn_down_decode_kernel<<<grid_down, 256, ld, st>>>(a);
     FATE_HIP(hipGetLastError());
-    if (!d.y_is_fp32 && d.phases != 1) {
+    if (!d.y_is_fp32) {
         const long long n = (long long)d.N * d.H;
         f32_to_bf16_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(a.y, static_cast<uint16_t*>(y_out), n);
         FATE_HIP(hipGetLastError());

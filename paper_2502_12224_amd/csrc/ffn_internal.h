@@ -48,7 +48,8 @@ struct FfnWorkspace {
 };
 
 fate_status launch_ffn_decode(hipStream_t st, const fate_ffn_desc& d, DecodeArgs a, void* y_out);
+// phase: 0 = whole FFN, 1 = prep + up/gate GEMM only, 2 = down GEMM + combine only (timing aid)
 fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs a, const MfmaScratch& ms,
-                            void* y_out);
+                            void* y_out, int phase);
 
 }  // namespace fate

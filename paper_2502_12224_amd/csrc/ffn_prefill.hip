@@ -456,7 +456,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const __half* __restrict__
 }
 
 fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs da, const MfmaScratch& ms,
-                            void* y_out) {
+                            void* y_out, int phase) {
     if (d.H % kKC || d.I_max % kKC || (d.n_shared && d.I_shared_max % kKC))
         FATE_FAIL(FATE_ESHAPE, "the MFMA path needs H and I to be multiples of %d", kKC);
     const int P = d.N * d.k;
@@ -468,7 +468,7 @@ fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs d
     const int nseg = d.E + d.n_shared;
     const int nb_r_up = (d.I_max + kBN - 1) / kBN, nb_s_up = d.n_shared ? (d.I_shared_max + kBN - 1) / kBN : 0;
     const int nb_down = (d.H + kBN - 1) / kBN;
-    const bool do_up = d.phases != 2, do_down = d.phases != 1;
+    const bool do_up = phase != 2, do_down = phase != 1;
     (void)nseg;
     if (do_up) {
         prefill_prep_kernel<<<d.N, 256, 0, st>>>(da.x, d.N, d.H, d.E, d.n_shared, da.offsets, da.shared_gate,

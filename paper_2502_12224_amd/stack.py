@@ -69,10 +69,9 @@ class LayerBuffers:
         return int(self.layer_ws[self.status_offset:self.status_offset + 4].view(torch.int32)[0])
 
 
-def layer_forward(cfg: MoEShape, lw: LayerWeights, lw_next, x, buf: LayerBuffers, fused=None, phases=0,
-                  one_launch=None):
+def layer_forward(cfg: MoEShape, lw: LayerWeights, lw_next, x, buf: LayerBuffers, fused=None, one_launch=None):
     """One MoE layer: route, predict the next layer's experts, permute, FFN."""
-    one_launch = (buf.one_launch_ok and phases == 0 and fused is None) if one_launch is None else one_launch
+    one_launch = (buf.one_launch_ok and fused is None) if one_launch is None else one_launch
     if one_launch:
         B.fate_moe_layer_decode(buf.desc, x, lw.Wg, lw.bias, None if lw_next is None else lw_next.Wg,
                                 None if lw_next is None else lw_next.bias, cfg.m, cfg.renorm, buf.ids, buf.w,
@@ -92,7 +91,6 @@ def layer_forward(cfg: MoEShape, lw: LayerWeights, lw_next, x, buf: LayerBuffers
             B.fate_cross_layer_predict(x, lw_next.Wg, lw_next.bias, cfg.k, cfg.m, buf.pred_ids, buf.pred_w,
                                        buf.pred_pop)
         B.fate_permute(buf.ids, cfg.E, buf.counts, buf.offsets, buf.perm, buf.inv_perm, buf.order)
-    buf.desc.phases = phases
     B.fate_moe_ffn_q(buf.desc, x, lw.table, buf.counts, buf.offsets, buf.perm, buf.inv_perm, buf.order, buf.w,
                      lw.shared_table, lw.shared_gate, buf.y, buf.ffn_ws)
     return buf.y
