@@ -229,6 +229,32 @@ fate_status fate_moe_layer_decode(void* stream, const fate_ffn_desc* d, const vo
                                   const void* shared_gate_bf16, void* y, void* workspace, size_t workspace_bytes);
 
 /* ------------------------------------------------------------------------
+ * fate_moe_layer_decode for callers that cannot allocate device memory or
+ * bring a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  Same arguments, kernels and results as
+ * fate_moe_layer_decode, except that the kernels' workspace (call epoch and
+ * exit counter, tagged logits, partial output rows) is a device array built
+ * into the library, FATE_NOALLOC_SCRATCH_BYTES long, one copy per GPU, held
+ * until the process ends; the call allocates nothing and calls no allocating
+ * routine.  A shape whose workspace (fate_moe_layer_decode_workspace) exceeds
+ * that size is rejected with FATE_EWORKSPACE.
+ *   status_dev: device int32 owned by the caller, 16-byte aligned; the kernels
+ *        OR the status bits of fate_moe_layer_decode into it (bit 0: an
+ *        activated expert had NULL weights, bit 1: a wait ran out) and never
+ *        clear it.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (different streams, or a graph replayed while another call runs)
+ * race and give wrong results; order them on one stream.
+ * ---------------------------------------------------------------------- */
+#define FATE_NOALLOC_SCRATCH_BYTES (32u << 20)
+fate_status fate_moe_layer_decode_noalloc(void* stream, const fate_ffn_desc* d, const void* x_bf16,
+                                          const void* Wg_bf16, const float* bias,
+                                          const void* Wg_next_bf16, const float* bias_next, int m, int renorm,
+                                          const fate_route_out* out,
+                                          const fate_qexpert* experts_dev, const fate_qexpert* shared_dev,
+                                          const void* shared_gate_bf16, void* y, int32_t* status_dev);
+
+/* ------------------------------------------------------------------------
  * Expert cache (paper section 4.4: memory budget -> cache_total; boundary L;
  * shallow layers cached fully, the rest split evenly over deep layers; ARC
  * per layer.  Section 4.1 steps 3-4, 7-8: residency check, transfer of

@@ -20,7 +20,8 @@ STATUS_NAMES = {0: "FATE_OK", 1: "FATE_EINVAL", 2: "FATE_ESHAPE", 3: "FATE_EALIG
 EXPORTS = [
     "fate_last_error", "fate_version", "fate_gate_route", "fate_cross_layer_predict", "fate_permute",
     "fate_route_fused_workspace", "fate_route_fused", "fate_pack_weight", "fate_pack_scales", "fate_moe_ffn_q_workspace",
-    "fate_moe_ffn_q", "fate_profile_ffn_mfma_phase", "fate_moe_layer_decode_workspace", "fate_moe_layer_decode", "fate_cache_total_from_budget", "fate_n_max_from_times", "fate_cache_layer_capacities",
+    "fate_moe_ffn_q", "fate_profile_ffn_mfma_phase", "fate_moe_layer_decode_workspace", "fate_moe_layer_decode",
+    "fate_moe_layer_decode_noalloc", "fate_cache_total_from_budget", "fate_n_max_from_times", "fate_cache_layer_capacities",
     "fate_cache_create", "fate_cache_destroy", "fate_cache_total_slots", "fate_cache_set_n_max", "fate_cache_slot_of",
     "fate_cache_resident", "fate_expert_cache_step", "fate_expert_cache_step_dense",
     "fate_expert_cache_step_layers", "fate_hip_engine_create", "fate_hip_engine_destroy",
@@ -195,6 +196,18 @@ def fate_moe_layer_decode(desc, x, Wg, bias, Wg_next, bias_next, m, renorm, topk
                                        _p(bias_next), int(m), int(bool(renorm)), C.byref(out), _p(experts_dev),
                                        _p(shared_dev), _p(shared_gate), _p(y), _p(workspace),
                                        C.c_size_t(workspace.numel() * workspace.element_size())))
+
+
+def fate_moe_layer_decode_noalloc(desc, x, Wg, bias, Wg_next, bias_next, m, renorm, topk_ids, topk_w, pred_ids,
+                                  pred_w, pred_pop, counts, offsets, perm, inv_perm, expert_order, experts_dev,
+                                  shared_dev, shared_gate, y, status_dev, stream=None):
+    out = fate_route_out(*[None if t is None else t.data_ptr() for t in
+                           (topk_ids, topk_w, pred_ids, pred_w, pred_pop, counts, offsets, perm, inv_perm,
+                            expert_order)])
+    _check(lib().fate_moe_layer_decode_noalloc(_stream(stream), C.byref(desc), _p(x), _p(Wg), _p(bias),
+                                               _p(Wg_next), _p(bias_next), int(m), int(bool(renorm)),
+                                               C.byref(out), _p(experts_dev), _p(shared_dev), _p(shared_gate),
+                                               _p(y), _p(status_dev)))
 
 
 def fate_profile_ffn_mfma_phase(desc, phase, x, experts_dev, counts, offsets, perm, inv_perm, expert_order, topk_w,

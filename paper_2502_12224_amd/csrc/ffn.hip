@@ -1,4 +1,5 @@
 // fate_moe_ffn_q: argument checks, workspace carving, dispatch.
+#include <mutex>
 #include "common.h"
 #include "ffn_internal.h"
 #include "layer_decode.h"
@@ -208,4 +209,53 @@ extern "C" fate_status fate_moe_layer_decode(void* stream, const fate_ffn_desc* 
     if (s != FATE_OK) return s;
     return layer_decode_checked(stream, d, x_bf16, Wg_bf16, bias, Wg_next_bf16, bias_next, m, renorm, out,
                                 experts_dev, shared_dev, shared_gate_bf16, y, workspace, workspace_bytes, nullptr);
+}
+
+// ---- the same call for callers that cannot allocate ---------------------------
+// The layer kernels' workspace (epoch and exit counters, tagged logits, partial output rows)
+// lives in a file-scope device array; each device holds its own copy at its own address,
+// looked up once per device.  Zero-initialised when the code object is loaded, which is the
+// state the kernels expect before their first call; every call leaves the counters at zero
+// and overwrites the rest.
+namespace fate {
+constexpr size_t kScratchBytes = FATE_NOALLOC_SCRATCH_BYTES;
+constexpr int kScratchMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+static void* g_scratch_ptr[kScratchMaxDevices];
+static std::mutex g_scratch_mutex;
+
+static fate_status scratch_of_current_device(void** out) {
+    int dev = -1;
+    FATE_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kScratchMaxDevices) FATE_FAIL(FATE_EINVAL, "device index %d not supported", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        FATE_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (p == nullptr) FATE_FAIL(FATE_EHIP, "hipGetSymbolAddress returned no address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return FATE_OK;
+}
+}  // namespace fate
+
+extern "C" fate_status fate_moe_layer_decode_noalloc(void* stream, const fate_ffn_desc* d, const void* x_bf16,
+                                                     const void* Wg_bf16, const float* bias,
+                                                     const void* Wg_next_bf16, const float* bias_next, int m,
+                                                     int renorm, const fate_route_out* out,
+                                                     const fate_qexpert* experts_dev, const fate_qexpert* shared_dev,
+                                                     const void* shared_gate_bf16, void* y, int32_t* status_dev) {
+    fate_status s = check_desc(d);
+    if (s != FATE_OK) return s;
+    if (status_dev == nullptr) FATE_FAIL(FATE_EINVAL, "status_dev is NULL");
+    const LayerWorkspace w = layer_workspace(*d);
+    if (w.bytes > kScratchBytes)
+        FATE_FAIL(FATE_EWORKSPACE, "this shape needs %zu bytes of scratch, the built-in array holds %zu "
+                  "(use fate_moe_layer_decode with a workspace of your own)", w.bytes, kScratchBytes);
+    void* ptr = nullptr;
+    s = scratch_of_current_device(&ptr);
+    if (s != FATE_OK) return s;
+    return layer_decode_checked(stream, d, x_bf16, Wg_bf16, bias, Wg_next_bf16, bias_next, m, renorm, out,
+                                experts_dev, shared_dev, shared_gate_bf16, y, ptr, kScratchBytes, status_dev);
 }
