@@ -6,16 +6,26 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfate.so")
-SOURCES = ["api.cpp", "route.hip", "pack.hip", "ffn.hip", "ffn_decode.hip", "layer_decode.hip", "layer_decode_loop_r41.hip", "layer_decode_loop_r42.hip", "layer_decode_loop_r44.hip", "layer_decode_loop_r82.hip", "layer_decode_loop_r84.hip", "ffn_prefill.hip", "cache.cpp",
+SOURCES = ["api.cpp", "route.hip", "pack.hip", "ffn.hip", "ffn_decode.hip", "layer_decode.hip", "layer_decode_b1.hip", "layer_decode_loop_r41.hip", "layer_decode_loop_r42.hip", "layer_decode_loop_r44.hip", "layer_decode_loop_r82.hip", "layer_decode_loop_r84.hip", "ffn_prefill.hip", "cache.cpp",
            "cache_hip.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = (["-DFATE_PROBE"] if os.environ.get("FATE_PROBE") else []) + ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-result", "-Wno-unknown-warning-option"]
 
 
+def _newest_header():
+    hdrs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    hdrs += [os.path.join(HERE, "..", "include", f) for f in os.listdir(os.path.join(HERE, "..", "include"))]
+    return max(os.path.getmtime(h) for h in hdrs)
+
+
 def _compile(src, objdir):
     path = os.path.join(CSRC, src)
     obj = os.path.join(objdir, src + ".o")
+    # FATE_INCREMENTAL=1 (development only): keep objects newer than their source and every header
+    if os.environ.get("FATE_INCREMENTAL") and os.path.exists(obj) and \
+            os.path.getmtime(obj) > max(os.path.getmtime(path), _newest_header()):
+        return src, obj, 0, ""
     cmd = [HIPCC, *FLAGS, "-x", "hip", "-c", path, "-o", obj]
     p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in p.stdout.splitlines() if "packed-fp32-ops" not in l)

@@ -190,6 +190,8 @@ static fate_status layer_decode_checked(void* stream, const fate_ffn_desc* d, co
     a.bits_s = d->n_shared ? d->shared_bits : d->bits; a.group_s = d->n_shared ? d->shared_group : d->group;
     a.part_r = reinterpret_cast<float*>(base + w.part_r);
     a.part_s = reinterpret_cast<float*>(base + w.part_s);
+    a.hq = reinterpret_cast<unsigned long long*>(base + w.hq);
+    a.yq = reinterpret_cast<unsigned long long*>(base + w.yq);
     a.y = y;
     a.y_is_fp32 = d->y_is_fp32;
     a.status = status ? status : reinterpret_cast<int32_t*>(base + w.status);

@@ -11,6 +11,7 @@ constexpr int kLayerThreads = 64 * kLayerWaves;
 constexpr int kLayerNeurons = 32;               // intermediate neurons per work block
 constexpr int kLayerMaxN = 8;                   // tokens per call
 constexpr int kLayerMaxP = 64;                  // (token, expert) pairs per call
+constexpr int kLayerMaxParts = 16;              // one-token kernel: down blocks per output row block
 
 struct LayerArgs {
     FusedRouteArgs r;              // x, gates, sizes, routing outputs (its zbuf is not used)
@@ -28,12 +29,14 @@ struct LayerArgs {
     int y_is_fp32;
     int32_t* status;
     int32_t* sync;                 // [0] epoch of the previous call, [1] workgroups that have left
+    unsigned long long* hq;        // one-token kernel: tagged pairs of h, shared experts [n_shared][I_s_max / 2] then routed slots [k][I_max / 2]
+    unsigned long long* yq;        // one-token kernel: [parts - 1][H] tagged partial outputs
     int nitems, nwork;             // work items (32-neuron blocks of shared experts, then of routed slots); work blocks in the launch
 };
 
 // byte offsets inside the workspace of fate_moe_layer_decode
 struct LayerWorkspace {
-    size_t sync, zq, status, part_r, part_s, bytes;
+    size_t sync, zq, status, part_r, part_s, hq, yq, bytes;
 };
 
 inline LayerWorkspace layer_workspace(const fate_ffn_desc& d) {
@@ -47,6 +50,11 @@ inline LayerWorkspace layer_workspace(const fate_ffn_desc& d) {
     w.part_r = off; off += up((size_t)N * d.k * (d.I_max / kLayerNeurons) * H * sizeof(float));
     w.part_s = off;
     off += up((size_t)d.n_shared * (d.n_shared ? d.I_shared_max / kLayerNeurons : 0) * N * H * sizeof(float));
+    // one-token kernel: h words and partial outputs of up to kLayerMaxParts down blocks per row block
+    w.hq = off;
+    off += N == 1 ? up(((size_t)d.n_shared * (d.n_shared ? d.I_shared_max : 0) + (size_t)d.k * d.I_max) / 2 * 8) : 0;
+    w.yq = off;
+    off += N == 1 ? up((size_t)kLayerMaxParts * H * 8) : 0;
     w.bytes = off;
     return w;
 }

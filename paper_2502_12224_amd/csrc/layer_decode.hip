@@ -2,6 +2,7 @@
 // host side (checks, launch geometry, dispatch) and the small reduction kernel that adds up the
 // partial output rows.  The looping kernels live in layer_decode_loop_r*.hip.
 #include "layer_decode_impl.h"
+#include "layer_decode_b1.h"
 
 namespace fate {
 
@@ -65,6 +66,11 @@ fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArg
     a.nkb_r = d.I_max / kLayerNeurons;
     a.nkb_s = d.n_shared ? d.I_shared_max / kLayerNeurons : 0;
     a.nact = min(d.E, d.N * d.k);
+    {   // one token: the kernel that hands h over between workgroups instead of partial output rows
+        B1Args b1;
+        int nblocks = 0;
+        if (b1_plan(d, a, &b1, &nblocks)) return launch_layer_decode_b1(st, d, b1, nblocks);
+    }
     // work items: 32-neuron blocks of the shared experts, then of the routed slots.  With more
     // items than workgroups fit on the device (two per compute unit), the launch has that many
     // work blocks and a block takes every nwork-th item.

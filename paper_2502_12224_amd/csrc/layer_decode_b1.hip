@@ -1,0 +1,571 @@
+// fate_moe_layer_decode for one token: one launch, no partial output rows.
+//
+// Block ids, in order:
+//   routing blocks      gate rows of this layer and of the next one, logits published as
+//                       epoch-tagged words; the last one writes the API's routing outputs
+//   shared up blocks    32 intermediate neurons of a shared expert: W1 / W3 row block, SwiGLU,
+//                       h published as tagged pairs of fp16
+//   shared down blocks  32 output rows: each wave fetches its K range of W2 of a shared expert
+//                       first, then polls the h of that range, multiplies, and the block
+//                       publishes a tagged partial output
+//   routed up blocks    as the shared ones, after polling the logits and redoing the selection
+//                       (slot j = the expert with the j-th largest logit)
+//   routed down blocks  as the shared ones; the last block of an output row block polls the
+//                       other blocks' partial outputs, adds them in a fixed order and writes y
+// Every wait is on data of blocks with lower ids, bounded, and turns into status bit 1.
+// Requests that do not depend on the routing (shared W1 / W3 / W2) all go out at the start;
+// W2 of the routed experts goes out as soon as a down block knows the selection, long before
+// the routed h exists.
+#include "layer_decode_impl.h"
+#include "layer_decode_b1.h"
+
+namespace fate {
+
+#ifdef FATE_PROBE
+__device__ unsigned long long g_probe_b1[1024 * 8];
+#define B1_TS(i) do { if (threadIdx.x == 0) g_pts[i] = wall_clock64(); } while (0)
+#else
+#define B1_TS(i) do { } while (0)
+#endif
+
+// ---- LDS of a down block -----------------------------------------------------------------
+constexpr int kB1HRegion = kB1MaxTiles * 64;          // halves of h per wave (tiles of at most 64 columns)
+struct B1DownLds {
+    int hl, zrow, red, tab, zl, ids, w, gate, bytes;
+};
+__host__ __device__ inline B1DownLds b1_down_lds(int E, int k) {
+    auto up = [](int v) { return (v + 15) & ~15; };
+    B1DownLds L;
+    int off = 0;
+    L.hl = off; off += up(kLayerWaves * kB1HRegion * 2);
+    L.zrow = off; off += up(kB1HRegion * 2);
+    L.red = off; off += up(kLayerWaves * 32 * 4);
+    L.tab = off; off += up(E * (int)sizeof(fate_qexpert));
+    L.zl = off; off += up(2 * E * 4);
+    L.ids = off; off += up(k * 4);
+    L.w = off; off += up(k * 4);
+    L.gate = off; off += 16;
+    L.bytes = off;
+    return L;
+}
+
+// ---- up block: 32 neurons of one expert, one token -----------------------------------------
+// The straight-line up projection of the general kernel (register ring, codes + constant on the
+// matrix cores, constant removed per group), then h goes out as 16 tagged words.
+template <int BITS, int TPG, class LoadX, class StoreX>
+__device__ __forceinline__ void b1_up(const WorkCtx& c, LoadX&& load_x, StoreX&& store_x,
+                                      unsigned long long* hq_dst, uint32_t tag) {
+    constexpr int KT = QFmt<BITS>::KT, D = kUpRing, GR = D / TPG;
+    const int tid = c.tid, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 31, half = lane >> 5;
+    const int H = c.H, I = c.I, kb = c.kb;
+    const int tiles_k = H / KT;
+    const int tw = tiles_k / kLayerWaves;
+    const int rounds = tw / D;
+    const int g_beg = wave * (tw / TPG);
+    const gu4_t wt[2] = {as_global<uint4>(c.ex.w1) + ((size_t)kb * tiles_k + wave * tw) * 64 + lane,
+                         as_global<uint4>(c.ex.w3) + ((size_t)kb * tiles_k + wave * tw) * 64 + lane};
+    const gu16_t sc[2] = {as_global<uint16_t>(c.ex.s1) + (size_t)g_beg * I + kb * 32 + n,
+                          as_global<uint16_t>(c.ex.s3) + (size_t)g_beg * I + kb * 32 + n};
+    if (c.defer_x) load_x();
+    uint4 raw[2][D];
+    uint32_t scr[2][GR];
+#pragma unroll
+    for (int j = 0; j < D; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) raw[i][j] = wt[i][(size_t)j * 64];
+#pragma unroll
+    for (int jg = 0; jg < GR; ++jg)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) scr[i][jg] = sc[i][(size_t)jg * I];
+    B1_TS(2);
+    if (c.defer_x) store_x(true);
+    lds_barrier();            // x and the zero row are in LDS
+    B1_TS(3);
+    {   // sums of x times the codes' constant for this wave's groups: 8 lanes per token row
+        constexpr int per = KT * TPG / 8;
+        const int t = lane >> 3, sub = lane & 7;
+        const _Float16* xp = c.xs + (t < 1 ? t : 1) * c.ldx + (size_t)g_beg * (KT * TPG) + sub * per;
+        for (int g = 0; g < tw / TPG; ++g) {
+            float sum = 0.f;
+#pragma unroll
+            for (int v = 0; v < per / 8; ++v)
+                sum = bias_dot8<BITS>(*reinterpret_cast<const uint4*>(xp + (size_t)g * (KT * TPG) + 8 * v), sum);
+            sum += __shfl_xor(sum, 1, 64);
+            sum += __shfl_xor(sum, 2, 64);
+            sum += __shfl_xor(sum, 4, 64);
+            if (sub == 0) c.cx[(g_beg + g) * kCxLd + t] = sum;
+            if (lane == 1) c.cx[(g_beg + g) * kCxLd + kTokPass] = 0.f;
+        }
+    }
+    const BiasConst bc = bias_const();
+    float out[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    const int arow = n < 1 ? 0 : 1;                  // row 0 = the token, row 1 = zeros
+    int ctok[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) ctok[j] = 4 * half + j < 1 ? 0 : kTokPass;
+    const _Float16* xa = c.xs + arow * c.ldx + half * (KT / 2) + (size_t)wave * tw * KT;
+    const float* cxg = c.cx + g_beg * kCxLd;
+    for (int r = 0; r + 1 < rounds; ++r)
+        up_round<BITS, TPG, true>(raw, scr, wt, sc, I, r, xa, cxg, ctok, bc, out, [] {});
+    up_round<BITS, TPG, false>(raw, scr, wt, sc, I, rounds - 1, xa, cxg, ctok, bc, out, [] {});
+    B1_TS(4);
+    if (half == 0) {
+        c.red[(wave * 2 + 0) * 32 + n] = out[0][0];
+        c.red[(wave * 2 + 1) * 32 + n] = out[1][0];
+    }
+    lds_barrier();
+    if (tid < 32) {
+        float a1 = 0.f, a3 = 0.f;
+#pragma unroll
+        for (int w = 0; w < kLayerWaves; ++w) {
+            a1 += c.red[(w * 2) * 32 + n];
+            a3 += c.red[(w * 2 + 1) * 32 + n];
+        }
+        const _Float16 hv = (_Float16)(a1 / (1.0f + expf(-a1)) * a3);
+        const uint32_t mine = (uint32_t)__builtin_bit_cast(unsigned short, hv);
+        const uint32_t next = (uint32_t)__shfl_down((int)mine, 1, 64);
+        if ((n & 1) == 0)
+            __hip_atomic_store(hq_dst + (n >> 1), ((unsigned long long)tag << 32) | (unsigned long long)(mine | (next << 16)),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+__device__ __forceinline__ void b1_publish_zero_h(unsigned long long* hq_dst, uint32_t tag) {
+    if (threadIdx.x < 16)
+        __hip_atomic_store(hq_dst + threadIdx.x, (unsigned long long)tag << 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Routed blocks: poll the logits, redo softmax / top-k (wave 0), leave ids and weights in LDS.
+// The expert table travels to LDS while the logits are awaited.
+__device__ __forceinline__ bool b1_selection(const B1Args& A, uint32_t tag, uint4* tab, float* zl, int32_t* ids, float* wv) {
+    const LayerArgs& a = A.a;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int E = a.r.E;
+    const uint4* src = reinterpret_cast<const uint4*>(a.experts);
+    for (int i = tid; i < E * (int)(sizeof(fate_qexpert) / 16); i += kLayerThreads) tab[i] = src[i];
+    if (!wait_logits(a.zq, E, tag, zl)) {
+        if (tid == 0) atomicOr(a.status, 2);
+        return false;
+    }
+    if (wave == 0) wave_softmax_topk_rounds(zl, E, a.r.k, a.r.renorm, ids, wv);
+    __syncthreads();
+    return true;
+}
+
+template <int BR, int TR, int BS, int TS>
+__device__ __forceinline__ void b1_up_role(const B1Args& A, int ub, bool is_shared, uint32_t tag, char* dyn) {
+    const LayerArgs& a = A.a;
+    const int tid = threadIdx.x;
+    const int H = a.r.H, E = a.r.E, k = a.r.k;
+    const WorkLds L = work_lds(1, H, E, k);
+    _Float16* xs = reinterpret_cast<_Float16*>(dyn + L.xs);
+    const int ldx = H + kLdsPad, nvec = H >> 3;
+    const bool x_one = nvec <= kLayerThreads;
+    uint4 xv = make_uint4(0, 0, 0, 0);
+    auto load_x = [&]() {
+        if (tid < nvec) xv = reinterpret_cast<const uint4*>(a.r.x)[tid];
+    };
+    auto store_x = [&](bool from_reg) {
+        if (from_reg) {
+            if (tid < nvec) *reinterpret_cast<uint4*>(xs + tid * 8) = bf16x8_to_f16x8(xv);
+        } else {
+            const uint4* xg = reinterpret_cast<const uint4*>(a.r.x);
+            for (int idx = tid; idx < nvec; idx += kLayerThreads)
+                *reinterpret_cast<uint4*>(xs + idx * 8) = bf16x8_to_f16x8(xg[idx]);
+        }
+        for (int c = tid; c < (ldx >> 3); c += kLayerThreads)
+            *reinterpret_cast<uint4*>(xs + ldx + c * 8) = make_uint4(0, 0, 0, 0);
+    };
+    const bool defer_x = is_shared && x_one;
+    if (!defer_x) store_x(false);
+
+    fate_qexpert ex;
+    int kb;
+    unsigned long long* hq_dst;
+    if (is_shared) {
+        const int s = ub / a.nkb_s;
+        kb = ub - s * a.nkb_s;
+        ex = a.shared[s];
+        hq_dst = A.a.hq + ((size_t)s * a.nkb_s + kb) * 16;
+    } else {
+        const int slot = ub / a.nkb_r;
+        kb = ub - slot * a.nkb_r;
+        hq_dst = A.a.hq + ((size_t)a.n_shared * a.nkb_s + (size_t)slot * a.nkb_r + kb) * 16;
+        uint4* tab = reinterpret_cast<uint4*>(dyn + L.tab);
+        float* zl = reinterpret_cast<float*>(dyn + L.zl);
+        int32_t* ids = reinterpret_cast<int32_t*>(dyn + L.ids);
+        float* wv = reinterpret_cast<float*>(dyn + L.w);
+        if (!b1_selection(A, tag, tab, zl, ids, wv)) {
+            b1_publish_zero_h(hq_dst, tag);
+            return;
+        }
+        ex = reinterpret_cast<const fate_qexpert*>(tab)[ids[slot]];
+    }
+    B1_TS(1);
+    const bool absent = ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr;
+    if (kb * kLayerNeurons >= ex.I || absent) {
+        if (absent && tid == 0) atomicOr(a.status, 1);
+        b1_publish_zero_h(hq_dst, tag);
+        return;
+    }
+    WorkCtx cx;
+    cx.tid = tid;
+    cx.N = 1; cx.H = H; cx.I = ex.I; cx.T = 1; cx.kb = kb; cx.wb = ub; cx.ntp = 1; cx.ldx = ldx;
+    cx.is_shared = is_shared; cx.defer_x = defer_x; cx.ex = ex; cx.xs = xs;
+    cx.hs = reinterpret_cast<_Float16*>(dyn + L.hs);
+    cx.red = reinterpret_cast<float*>(dyn + L.red);
+    cx.wtok = nullptr; cx.cx = reinterpret_cast<float*>(dyn + L.cx); cx.ch = nullptr;
+    cx.tokid = nullptr; cx.pairq = nullptr; cx.part = nullptr; cx.part_stride = 0;
+    if (is_shared) b1_up<BS, TS>(cx, load_x, store_x, hq_dst, tag);
+    else b1_up<BR, TR>(cx, load_x, store_x, hq_dst, tag);
+}
+
+// ---- down block: 32 output rows, four wave items --------------------------------------------
+// Requests of one wave item: its W2 tiles of output row block rb and their scales.  Returns the
+// number of groups the expert really has in the item's range (0: nothing requested).
+template <int BITS, int TPG>
+__device__ __forceinline__ int b1_down_request(const fate_qexpert& ex, int H, int rb, int g0, int ng,
+                                               uint4 (&raw)[kB1MaxTiles], uint32_t (&sc)[kB1MaxTiles / TPG]) {
+    constexpr int KT = QFmt<BITS>::KT, MAXG = kB1MaxTiles / TPG;
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 31;
+    const int group = KT * TPG;
+    const int tiles_k2 = ex.I / KT;
+    const int gmax = ex.I / group;
+    ng = g0 + ng <= gmax ? ng : (gmax > g0 ? gmax - g0 : 0);
+    if (ng <= 0 || ex.w2 == nullptr) return 0;
+    const int nt = ng * TPG;
+    gu4_t w2 = as_global<uint4>(ex.w2) + ((size_t)rb * tiles_k2 + (size_t)g0 * TPG) * 64 + lane;
+    gu16_t s2 = as_global<uint16_t>(ex.s2) + (size_t)g0 * H + rb * 32 + n;
+#pragma unroll
+    for (int j = 0; j < kB1MaxTiles; ++j) raw[j] = w2[(size_t)(j < nt ? j : nt - 1) * 64];
+#pragma unroll
+    for (int jg = 0; jg < MAXG; ++jg) sc[jg] = s2[(size_t)(jg < ng ? jg : ng - 1) * H];
+    return ng;
+}
+
+// Polls the h of the item's K range, then multiplies.  The codes enter the matrix cores as
+// u + C (one v_and_or_b32 per pair); the constant's share, C + zero times the sum of the group's h,
+// leaves per group - every lane holds one tagged word of a group of 128, so that sum is one wave
+// reduction per group.  Returns the item's contribution to output row rb*32 + n in lanes 0..31.
+template <int BITS, int TPG>
+__device__ __forceinline__ float b1_down_product(const uint4 (&raw)[kB1MaxTiles], const uint32_t (&sc)[kB1MaxTiles / TPG],
+                                                 int ng, const unsigned long long* hq_src, uint32_t tag, _Float16* hl,
+                                                 const _Float16* zrow, bool* failed) {
+    constexpr int KT = QFmt<BITS>::KT, S = QFmt<BITS>::MSTEPS, MAXG = kB1MaxTiles / TPG;
+    static_assert(KT * TPG == 128, "one tagged word of a group per lane");
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 31, half = lane >> 5;
+    float ch[MAXG];
+    {
+        const unsigned long long tagw = (unsigned long long)tag << 32;
+        bool done = false;
+        for (int it = 0; it < kSpinMax && !done; ++it) {
+            unsigned long long v[MAXG];
+#pragma unroll
+            for (int j = 0; j < MAXG; ++j) v[j] = j < ng ? ld_dev(hq_src + lane + 64 * j) : tagw;
+            bool good = true;
+#pragma unroll
+            for (int j = 0; j < MAXG; ++j) good = good && (uint32_t)(v[j] >> 32) == tag;
+            if (__all(good)) {
+                const float cc = BITS == 4 ? ((lane & 1) ? 72.f : 1032.f) : 1152.f;
+#pragma unroll
+                for (int j = 0; j < MAXG; ++j) {
+                    const uint32_t w = (uint32_t)v[j];
+                    reinterpret_cast<uint32_t*>(hl)[lane + 64 * j] = w;
+                    const f16x2_t hv = __builtin_bit_cast(f16x2_t, w);
+                    ch[j] = wave_sum(cc * ((float)hv.x + (float)hv.y));
+                }
+                done = true;
+            } else {
+                __builtin_amdgcn_s_sleep(2);
+            }
+        }
+        if (!done) {
+            *failed = true;
+            return 0.f;
+        }
+    }
+    B1_TS(3);
+    const _Float16* ha = (n == 0 ? hl : zrow) + half * (KT / 2);
+    const BiasConst bc = bias_const();
+    const f32x16_t zero = f32x16_zero();
+    float out = 0.f;
+    f16x8_t av[S], avn[S];
+#pragma unroll
+    for (int st = 0; st < S; ++st) av[st] = *reinterpret_cast<const f16x8_t*>(ha + 8 * st);
+#pragma unroll
+    for (int jg = 0; jg < MAXG; ++jg) {
+        f32x16_t acc;
+#pragma unroll
+        for (int tl = 0; tl < TPG; ++tl) {
+            const int j = jg * TPG + tl;
+            if (j + 1 < kB1MaxTiles) {
+#pragma unroll
+                for (int st = 0; st < S; ++st) avn[st] = *reinterpret_cast<const f16x8_t*>(ha + (j + 1) * KT + 8 * st);
+            }
+            f16x8_t b[S];
+            biased_tile<BITS>(raw[j], bc, b);
+#pragma unroll
+            for (int st = 0; st < S; ++st)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[st], b[st], (tl == 0 && st == 0) ? zero : acc, 0, 0, 0);
+#pragma unroll
+            for (int st = 0; st < S; ++st) av[st] = avn[st];
+        }
+        // groups past the item's end multiply stale h with repeated tiles: they do not count
+        if (jg < ng) out = fmaf(half_bits_to_float(sc[jg]), acc[0] - ch[jg], out);
+    }
+    return out;
+}
+
+template <int BR, int TR, int BS, int TS>
+__device__ __forceinline__ void b1_down_role(const B1Args& A, int part, int rb, uint32_t tag, char* dyn) {
+    const LayerArgs& a = A.a;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int H = a.r.H, E = a.r.E, k = a.r.k;
+    const B1DownLds L = b1_down_lds(E, k);
+    _Float16* hl = reinterpret_cast<_Float16*>(dyn + L.hl) + wave * kB1HRegion;
+    _Float16* zrow = reinterpret_cast<_Float16*>(dyn + L.zrow);
+    float* red = reinterpret_cast<float*>(dyn + L.red);
+    float* gate = reinterpret_cast<float*>(dyn + L.gate);
+    const bool is_shared = part < A.nparts_s;
+    const B1Item it = A.items[part * kLayerWaves + wave];
+    for (int c = tid; c < kB1HRegion / 8; c += kLayerThreads)
+        *reinterpret_cast<uint4*>(zrow + c * 8) = make_uint4(0, 0, 0, 0);
+    lds_barrier();
+    fate_qexpert ex;
+    float wsrc = 1.f;
+    const unsigned long long* hq_src;
+    bool failed = false;
+    if (is_shared) {
+        ex = a.shared[it.ng > 0 ? it.src : 0];
+        hq_src = A.a.hq + (size_t)it.src * a.nkb_s * 16;
+    } else {
+        uint4* tab = reinterpret_cast<uint4*>(dyn + L.tab);
+        float* zl = reinterpret_cast<float*>(dyn + L.zl);
+        int32_t* ids = reinterpret_cast<int32_t*>(dyn + L.ids);
+        float* wv = reinterpret_cast<float*>(dyn + L.w);
+        const int slot = it.ng > 0 ? it.src - a.n_shared : 0;
+        hq_src = A.a.hq + ((size_t)a.n_shared * a.nkb_s + (size_t)slot * a.nkb_r) * 16;
+        if (!b1_selection(A, tag, tab, zl, ids, wv)) {
+            failed = true;
+            ex = fate_qexpert{};
+        } else {
+            ex = reinterpret_cast<const fate_qexpert*>(tab)[ids[slot]];
+            wsrc = wv[slot];
+        }
+    }
+    B1_TS(1);
+    float out = 0.f;
+    // (the gate of the shared experts is evaluated behind the W2 requests, before the wait for h)
+    auto shared_gate = [&]() {
+        if (a.shared_gate != nullptr) {
+            if (wave == 0) {
+                const float g = wave_sigmoid_dot_bf16(reinterpret_cast<const uint4*>(a.r.x),
+                                                      reinterpret_cast<const uint4*>(a.shared_gate), H >> 3);
+                if (lane == 0) gate[0] = g;
+            }
+        } else if (tid == 0) {
+            gate[0] = 1.f;
+        }
+    };
+#define FATE_B1_DOWN(BITS, TPG)                                                                          \
+    {                                                                                                     \
+        uint4 raw[kB1MaxTiles];                                                                           \
+        uint32_t sc[kB1MaxTiles / TPG];                                                                   \
+        const int ng = (!failed && it.ng > 0) ? b1_down_request<BITS, TPG>(ex, H, rb, it.g0, it.ng, raw, sc) : 0; \
+        B1_TS(2);                                                                                         \
+        if (is_shared) shared_gate();                                                                     \
+        if (ng > 0)                                                                                       \
+            out = b1_down_product<BITS, TPG>(raw, sc, ng, hq_src + (size_t)it.g0 * 64, tag, hl, zrow, &failed); \
+    }
+    if (is_shared) FATE_B1_DOWN(BS, TS)
+    else FATE_B1_DOWN(BR, TR)
+#undef FATE_B1_DOWN
+    B1_TS(4);
+    if (failed && lane == 0) atomicOr(a.status, 2);
+    if (lane < 32) red[wave * 32 + lane] = wsrc * out;
+    __syncthreads();
+    const float gsh = is_shared ? gate[0] : 1.f;
+    if (tid < 32) {
+        float v = gsh * ((red[tid] + red[32 + tid]) + (red[64 + tid] + red[96 + tid]));
+        const int row = rb * 32 + tid;
+        if (part + 1 < A.nparts) {
+            __hip_atomic_store(A.a.yq + (size_t)part * H + row,
+                               ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            // the block that writes y: the other blocks' partial outputs, in block order, then its own
+            float sum = 0.f;
+            bool good = true;
+            for (int p = 0; p + 1 < A.nparts; ++p) {
+                const unsigned long long* src = A.a.yq + (size_t)p * H + row;
+                unsigned long long w = 0;
+                int spin = 0;
+                for (; spin < kSpinMax; ++spin) {
+                    w = ld_dev(src);
+                    if ((uint32_t)(w >> 32) == tag) break;
+                    __builtin_amdgcn_s_sleep(4);
+                }
+                good = good && spin < kSpinMax;
+                sum += __uint_as_float((uint32_t)w);
+            }
+            if (!good) atomicOr(a.status, 2);
+            v += sum;
+            if (a.y_is_fp32) static_cast<float*>(a.y)[row] = v;
+            else static_cast<uint16_t*>(a.y)[row] = (uint16_t)f32_to_bf16_bits(v);
+        }
+    }
+}
+
+template <int BR, int TR, int BS, int TS>
+__global__ __launch_bounds__(kLayerThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void moe_layer_decode_b1_kernel(B1Args A) {
+    extern __shared__ uint4 smem[];
+    __shared__ FusedRouteSmem rsm;
+    char* dyn = reinterpret_cast<char*>(smem);
+    const LayerArgs& a = A.a;
+    uint32_t tag = (uint32_t)ld_dev(a.sync) + 1u;
+    if (tag == 0u) tag = 1u;
+#ifdef FATE_PROBE
+    const unsigned long long t_start = wall_clock64();
+    if (threadIdx.x < 8) g_pts[threadIdx.x] = 0;
+    __syncthreads();
+#endif
+    int b = blockIdx.x;
+    const int nd_s = A.nparts_s * A.nrb, nd_r = (A.nparts - A.nparts_s) * A.nrb;
+    if (b < a.nb_route) {
+        route_role(a, b, tag, dyn, rsm);
+    } else if ((b -= a.nb_route) < A.n_up_s) {
+        b1_up_role<BR, TR, BS, TS>(A, b, true, tag, dyn);
+    } else if ((b -= A.n_up_s) < nd_s) {
+        b1_down_role<BR, TR, BS, TS>(A, b / A.nrb, b % A.nrb, tag, dyn);
+    } else if ((b -= nd_s) < A.n_up_r) {
+        b1_up_role<BR, TR, BS, TS>(A, b, false, tag, dyn);
+    } else if ((b -= A.n_up_r) < nd_r) {
+        b1_down_role<BR, TR, BS, TS>(A, A.nparts_s + b / A.nrb, b % A.nrb, tag, dyn);
+    }
+    // the workgroup that leaves last opens the next epoch
+    __syncthreads();
+    B1_TS(6);
+#ifdef FATE_PROBE
+    if (threadIdx.x < 8 && blockIdx.x < 1024)
+        g_probe_b1[blockIdx.x * 8 + threadIdx.x] = threadIdx.x == 0 ? t_start : g_pts[threadIdx.x];
+#endif
+    if (threadIdx.x == 0 && atomicAdd(a.sync + 1, 1) == (int)gridDim.x - 1) {
+        st_dev(a.sync + 1, 0);
+        st_dev(a.sync, (int32_t)tag);
+    }
+}
+
+// ---- host side ----------------------------------------------------------------------------------
+static bool b1_format(int bits, int group) { return (bits == 4 && group == 128) || (bits == 8 && group == 128); }
+
+static int b1_lds_bytes(const fate_ffn_desc& d) {
+    return std::max(work_lds(1, d.H, d.E, d.k).bytes, b1_down_lds(d.E, d.k).bytes);
+}
+
+template <int BR, int TR, int BS, int TS>
+static int b1_occupancy(int lds) {
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(
+            &nb, reinterpret_cast<const void*>(moe_layer_decode_b1_kernel<BR, TR, BS, TS>), kLayerThreads,
+            (size_t)lds) != hipSuccess)
+        return 0;
+    return nb;
+}
+
+#define FATE_B1_SWITCH(bits_r, bits_s, BODY)          \
+    if ((bits_r) == 4 && (bits_s) == 4) { BODY(4, 2, 4, 2) }      \
+    else if ((bits_r) == 4) { BODY(4, 2, 8, 4) }                   \
+    else if ((bits_s) == 4) { BODY(8, 4, 4, 2) }                   \
+    else { BODY(8, 4, 8, 4) }
+
+int b1_resident_blocks(const fate_ffn_desc& d) {
+    static int cached_cu = 0;
+    if (cached_cu == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cached_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return 0;
+    }
+    const int bits_s = d.n_shared ? d.shared_bits : d.bits;
+    const int lds = b1_lds_bytes(d);
+    // the occupancy query is not free: one answer per format pair and LDS size is kept
+    static int key_lds[4] = {-1, -1, -1, -1}, val[4] = {0, 0, 0, 0};
+    const int key = (d.bits == 8 ? 2 : 0) + (bits_s == 8 ? 1 : 0);
+    if (key_lds[key] != lds) {
+        int per_cu = 0;
+#define FATE_B1_OCC(BR, TR, BS, TS) per_cu = b1_occupancy<BR, TR, BS, TS>(lds);
+        FATE_B1_SWITCH(d.bits, bits_s, FATE_B1_OCC)
+#undef FATE_B1_OCC
+        val[key] = per_cu;
+        key_lds[key] = lds;
+    }
+    return val[key] * cached_cu;
+}
+
+// Splits G groups of a source into wave items of at most maxg groups, as evenly as possible.
+static int b1_add_items(B1Item* items, int n, int src, int G, int maxg) {
+    const int pieces = (G + maxg - 1) / maxg;
+    int g0 = 0;
+    for (int p = 0; p < pieces; ++p) {
+        const int ng = G / pieces + (p < G % pieces ? 1 : 0);
+        if (n >= kB1MaxItems) return -1;
+        items[n++] = B1Item{(int16_t)src, (int16_t)g0, (int16_t)ng, 0};
+        g0 += ng;
+    }
+    return n;
+}
+
+bool b1_plan(const fate_ffn_desc& d, const LayerArgs& a, B1Args* b, int* nblocks) {
+    if (d.N != 1) return false;
+    const int bits_s = d.n_shared ? d.shared_bits : d.bits, group_s = d.n_shared ? d.shared_group : d.group;
+    if (!b1_format(d.bits, d.group) || !b1_format(bits_s, group_s)) return false;
+    // the straight-line up projection: a whole number of register rings per wave
+    const int kt_r = d.bits == 4 ? 64 : 32, kt_s = bits_s == 4 ? 64 : 32;
+    if (d.H % (kLayerWaves * kUpRing * kt_r) || d.H % (kLayerWaves * kUpRing * kt_s)) return false;
+    if (d.I_max % 128 || (d.n_shared && d.I_shared_max % 128)) return false;
+    b->a = a;
+    b->nrb = d.H / 32;
+    b->n_up_s = d.n_shared * a.nkb_s;
+    b->n_up_r = d.k * a.nkb_r;
+    for (int i = 0; i < kB1MaxItems; ++i) b->items[i] = B1Item{0, 0, 0, 0};
+    int n = 0;
+    const int maxg_s = kB1MaxTiles / (group_s / kt_s), maxg_r = kB1MaxTiles / (d.group / kt_r);
+    for (int s = 0; s < d.n_shared; ++s)
+        if ((n = b1_add_items(b->items, n, s, d.I_shared_max / group_s, maxg_s)) < 0) return false;
+    n = (n + kLayerWaves - 1) / kLayerWaves * kLayerWaves;        // routed items start in a block of their own
+    b->nparts_s = n / kLayerWaves;
+    for (int j = 0; j < d.k; ++j)
+        if ((n = b1_add_items(b->items, n, d.n_shared + j, d.I_max / d.group, maxg_r)) < 0) return false;
+    b->nparts = (n + kLayerWaves - 1) / kLayerWaves;
+    if (b->nparts > kB1MaxItems / kLayerWaves) return false;
+    *nblocks = a.nb_route + b->n_up_s + b->n_up_r + b->nparts * b->nrb;
+    // The routing blocks and everything of the shared experts must be on the device from the start
+    // (their requests do not wait for anything); the routed blocks have nothing to do before the
+    // logits exist and may start as earlier blocks leave (a block only waits for lower ids).  A
+    // launch several times larger than the device is left to the general kernel.
+    const int resident = b1_resident_blocks(d);
+    const int early = a.nb_route + b->n_up_s + b->nparts_s * b->nrb;
+    return resident > 0 && early <= resident && *nblocks <= 2 * resident;
+}
+
+fate_status launch_layer_decode_b1(hipStream_t st, const fate_ffn_desc& d, const B1Args& b, int nblocks) {
+    const int bits_s = d.n_shared ? d.shared_bits : d.bits;
+    const int lds = b1_lds_bytes(d);
+#define FATE_B1_LAUNCH(BR, TR, BS, TS) \
+    moe_layer_decode_b1_kernel<BR, TR, BS, TS><<<nblocks, kLayerThreads, lds, st>>>(b);
+    FATE_B1_SWITCH(d.bits, bits_s, FATE_B1_LAUNCH)
+#undef FATE_B1_LAUNCH
+    FATE_HIP(hipGetLastError());
+    return FATE_OK;
+}
+
+#ifdef FATE_PROBE
+extern "C" int fate_debug_probe_b1(unsigned long long* host_out, int nblocks) {
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_probe_b1), (size_t)nblocks * 8 * sizeof(unsigned long long));
+}
+#endif
+
+}  // namespace fate

@@ -21,7 +21,8 @@ def _snapshot(buf, fields):
 
 @pytest.mark.parametrize("name,N,last", [("tiny", 1, False), ("tiny", 8, False), ("tiny", 5, True),
                                          ("qwen", 1, False), ("qwen", 1, True), ("qwen", 6, False),
-                                         ("deepseek", 8, False), ("mixtral", 1, False), ("mixtral", 4, False)])
+                                         ("deepseek", 8, False), ("deepseek", 1, False), ("mixtral", 1, False),
+                                         ("mixtral", 4, False)])
 def test_one_launch_layer_equals_separate_calls_and_oracle(name, N, last):
     cfg = SHAPES[name]
     print(f"case {name} N={N} last={last}", flush=True)
