@@ -165,8 +165,11 @@ def bench_decode(args):
     host_counts = [torch.zeros(2, L, E, dtype=torch.int32).pin_memory() for _ in range(2)]
 
     def enqueue_token():
+        # layer l's call gets, as a prefetch hint, what layer l-1's call predicted for it (section 4.3)
         for l in range(L):
-            layer_forward(cfg, stack.layers[l], stack.layers[l + 1] if l + 1 < L else None, x_in[l], bufs[l])
+            hint = bufs[l - 1].pred_ids if (l > 0 and N == 1 and args.hint) else None
+            layer_forward(cfg, stack.layers[l], stack.layers[l + 1] if l + 1 < L else None, x_in[l], bufs[l],
+                          hint_ids=hint)
 
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):
@@ -580,6 +583,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true",
                     help="decode: skip the 512-token prefill figures that the default run adds to its line")
+    ap.add_argument("--hint", action="store_true",
+                    help="decode: hand layer l the previous layer's prediction as a prefetch hint (measured slower "
+                         "at this prediction accuracy: a wrong hint costs a second pass)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="decode: also run five 1 GiB device copies (reference for hardware-counter runs)")
     ap.add_argument("--n-max", type=int, default=None,

@@ -204,6 +204,14 @@ fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, const void* x_b
  * projection, and leaves a partial output row that the reduction adds up.
  * A call with more such items than work groups fit on the device at once
  * launches as many as fit, and each takes every n-th item.
+ *   hint_ids: NULL, or a device array of k expert ids predicted for THIS layer
+ *        by the previous layer's call (the first k entries of its pred_ids; for
+ *        N == 1 only, ignored otherwise).  A prefetch hint in the sense of
+ *        section 4.3: the work groups of routed slot j start fetching expert
+ *        hint_ids[j] before this layer's gate is known and keep it if the gate
+ *        selects it; a wrong, repeated or out-of-range id only costs time.  The
+ *        results do not depend on the hint except for the order of the fp32
+ *        additions in y.
  *   out: device pointers for every routing output, sized as in the separate
  *        calls; pred_* may be NULL when Wg_next is NULL (last layer).
  *   d->mode must be 0 or 1.
@@ -224,7 +232,7 @@ fate_status fate_moe_layer_decode_workspace(const fate_ffn_desc* d, size_t* byte
 fate_status fate_moe_layer_decode(void* stream, const fate_ffn_desc* d, const void* x_bf16,
                                   const void* Wg_bf16, const float* bias,
                                   const void* Wg_next_bf16, const float* bias_next, int m, int renorm,
-                                  const fate_route_out* out,
+                                  const int32_t* hint_ids, const fate_route_out* out,
                                   const fate_qexpert* experts_dev, const fate_qexpert* shared_dev,
                                   const void* shared_gate_bf16, void* y, void* workspace, size_t workspace_bytes);
 
@@ -250,7 +258,7 @@ fate_status fate_moe_layer_decode(void* stream, const fate_ffn_desc* d, const vo
 fate_status fate_moe_layer_decode_noalloc(void* stream, const fate_ffn_desc* d, const void* x_bf16,
                                           const void* Wg_bf16, const float* bias,
                                           const void* Wg_next_bf16, const float* bias_next, int m, int renorm,
-                                          const fate_route_out* out,
+                                          const int32_t* hint_ids, const fate_route_out* out,
                                           const fate_qexpert* experts_dev, const fate_qexpert* shared_dev,
                                           const void* shared_gate_bf16, void* y, int32_t* status_dev);
 

@@ -188,25 +188,25 @@ def fate_moe_layer_decode_workspace(desc):
 
 def fate_moe_layer_decode(desc, x, Wg, bias, Wg_next, bias_next, m, renorm, topk_ids, topk_w, pred_ids, pred_w,
                           pred_pop, counts, offsets, perm, inv_perm, expert_order, experts_dev, shared_dev,
-                          shared_gate, y, workspace, stream=None):
+                          shared_gate, y, workspace, stream=None, hint_ids=None):
     out = fate_route_out(*[None if t is None else t.data_ptr() for t in
                            (topk_ids, topk_w, pred_ids, pred_w, pred_pop, counts, offsets, perm, inv_perm,
                             expert_order)])
     _check(lib().fate_moe_layer_decode(_stream(stream), C.byref(desc), _p(x), _p(Wg), _p(bias), _p(Wg_next),
-                                       _p(bias_next), int(m), int(bool(renorm)), C.byref(out), _p(experts_dev),
+                                       _p(bias_next), int(m), int(bool(renorm)), _p(hint_ids), C.byref(out), _p(experts_dev),
                                        _p(shared_dev), _p(shared_gate), _p(y), _p(workspace),
                                        C.c_size_t(workspace.numel() * workspace.element_size())))
 
 
 def fate_moe_layer_decode_noalloc(desc, x, Wg, bias, Wg_next, bias_next, m, renorm, topk_ids, topk_w, pred_ids,
                                   pred_w, pred_pop, counts, offsets, perm, inv_perm, expert_order, experts_dev,
-                                  shared_dev, shared_gate, y, status_dev, stream=None):
+                                  shared_dev, shared_gate, y, status_dev, stream=None, hint_ids=None):
     out = fate_route_out(*[None if t is None else t.data_ptr() for t in
                            (topk_ids, topk_w, pred_ids, pred_w, pred_pop, counts, offsets, perm, inv_perm,
                             expert_order)])
     _check(lib().fate_moe_layer_decode_noalloc(_stream(stream), C.byref(desc), _p(x), _p(Wg), _p(bias),
                                                _p(Wg_next), _p(bias_next), int(m), int(bool(renorm)),
-                                               C.byref(out), _p(experts_dev), _p(shared_dev), _p(shared_gate),
+                                               _p(hint_ids), C.byref(out), _p(experts_dev), _p(shared_dev), _p(shared_gate),
                                                _p(y), _p(status_dev)))
 
 

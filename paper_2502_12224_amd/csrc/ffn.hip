@@ -151,7 +151,8 @@ namespace fate {
 // the workspace.
 static fate_status layer_decode_checked(void* stream, const fate_ffn_desc* d, const void* x_bf16,
                                         const void* Wg_bf16, const float* bias, const void* Wg_next_bf16,
-                                        const float* bias_next, int m, int renorm, const fate_route_out* out,
+                                        const float* bias_next, int m, int renorm, const int32_t* hint_ids,
+                                        const fate_route_out* out,
                                         const fate_qexpert* experts_dev, const fate_qexpert* shared_dev,
                                         const void* shared_gate_bf16, void* y, void* workspace,
                                         size_t workspace_bytes, int32_t* status) {
@@ -192,6 +193,7 @@ static fate_status layer_decode_checked(void* stream, const fate_ffn_desc* d, co
     a.part_s = reinterpret_cast<float*>(base + w.part_s);
     a.hq = reinterpret_cast<unsigned long long*>(base + w.hq);
     a.yq = reinterpret_cast<unsigned long long*>(base + w.yq);
+    a.hint = hint_ids;
     a.y = y;
     a.y_is_fp32 = d->y_is_fp32;
     a.status = status ? status : reinterpret_cast<int32_t*>(base + w.status);
@@ -203,13 +205,14 @@ static fate_status layer_decode_checked(void* stream, const fate_ffn_desc* d, co
 
 extern "C" fate_status fate_moe_layer_decode(void* stream, const fate_ffn_desc* d, const void* x_bf16,
                                              const void* Wg_bf16, const float* bias, const void* Wg_next_bf16,
-                                             const float* bias_next, int m, int renorm, const fate_route_out* out,
+                                             const float* bias_next, int m, int renorm, const int32_t* hint_ids,
+                                             const fate_route_out* out,
                                              const fate_qexpert* experts_dev, const fate_qexpert* shared_dev,
                                              const void* shared_gate_bf16, void* y, void* workspace,
                                              size_t workspace_bytes) {
     fate_status s = check_desc(d);
     if (s != FATE_OK) return s;
-    return layer_decode_checked(stream, d, x_bf16, Wg_bf16, bias, Wg_next_bf16, bias_next, m, renorm, out,
+    return layer_decode_checked(stream, d, x_bf16, Wg_bf16, bias, Wg_next_bf16, bias_next, m, renorm, hint_ids, out,
                                 experts_dev, shared_dev, shared_gate_bf16, y, workspace, workspace_bytes, nullptr);
 }
 
@@ -245,7 +248,7 @@ static fate_status scratch_of_current_device(void** out) {
 extern "C" fate_status fate_moe_layer_decode_noalloc(void* stream, const fate_ffn_desc* d, const void* x_bf16,
                                                      const void* Wg_bf16, const float* bias,
                                                      const void* Wg_next_bf16, const float* bias_next, int m,
-                                                     int renorm, const fate_route_out* out,
+                                                     int renorm, const int32_t* hint_ids, const fate_route_out* out,
                                                      const fate_qexpert* experts_dev, const fate_qexpert* shared_dev,
                                                      const void* shared_gate_bf16, void* y, int32_t* status_dev) {
     fate_status s = check_desc(d);
@@ -258,6 +261,6 @@ extern "C" fate_status fate_moe_layer_decode_noalloc(void* stream, const fate_ff
     void* ptr = nullptr;
     s = scratch_of_current_device(&ptr);
     if (s != FATE_OK) return s;
-    return layer_decode_checked(stream, d, x_bf16, Wg_bf16, bias, Wg_next_bf16, bias_next, m, renorm, out,
+    return layer_decode_checked(stream, d, x_bf16, Wg_bf16, bias, Wg_next_bf16, bias_next, m, renorm, hint_ids, out,
                                 experts_dev, shared_dev, shared_gate_bf16, y, ptr, kScratchBytes, status_dev);
 }

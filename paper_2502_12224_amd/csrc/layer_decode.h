@@ -29,6 +29,7 @@ struct LayerArgs {
     int y_is_fp32;
     int32_t* status;
     int32_t* sync;                 // [0] epoch of the previous call, [1] workgroups that have left
+    const int32_t* hint;           // one-token kernel: k expert ids predicted for this layer, or NULL
     unsigned long long* hq;        // one-token kernel: tagged pairs of h, shared experts [n_shared][I_s_max / 2] then routed slots [k][I_max / 2]
     unsigned long long* yq;        // one-token kernel: [parts - 1][H] tagged partial outputs
     int nitems, nwork;             // work items (32-neuron blocks of shared experts, then of routed slots); work blocks in the launch

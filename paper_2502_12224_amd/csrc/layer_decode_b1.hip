@@ -31,7 +31,7 @@ __device__ unsigned long long g_probe_b1[1024 * 8];
 // ---- LDS of a down block -----------------------------------------------------------------
 constexpr int kB1HRegion = kB1MaxTiles * 64;          // halves of h per wave (tiles of at most 64 columns)
 struct B1DownLds {
-    int hl, zrow, red, tab, zl, ids, w, gate, bytes;
+    int hl, zrow, red, tab, zl, ids, w, src_e, src_w, gate, bytes;
 };
 __host__ __device__ inline B1DownLds b1_down_lds(int E, int k) {
     auto up = [](int v) { return (v + 15) & ~15; };
@@ -44,6 +44,8 @@ __host__ __device__ inline B1DownLds b1_down_lds(int E, int k) {
     L.zl = off; off += up(2 * E * 4);
     L.ids = off; off += up(k * 4);
     L.w = off; off += up(k * 4);
+    L.src_e = off; off += up(k * 4);
+    L.src_w = off; off += up(k * 4);
     L.gate = off; off += 16;
     L.bytes = off;
     return L;
@@ -52,9 +54,9 @@ __host__ __device__ inline B1DownLds b1_down_lds(int E, int k) {
 // ---- up block: 32 neurons of one expert, one token -----------------------------------------
 // The straight-line up projection of the general kernel (register ring, codes + constant on the
 // matrix cores, constant removed per group), then h goes out as 16 tagged words.
+// Returns, in lanes 0..31 of wave 0, the fp16 bits of h of neuron kb*32 + lane.
 template <int BITS, int TPG, class LoadX, class StoreX>
-__device__ __forceinline__ void b1_up(const WorkCtx& c, LoadX&& load_x, StoreX&& store_x,
-                                      unsigned long long* hq_dst, uint32_t tag) {
+__device__ __forceinline__ uint32_t b1_up(const WorkCtx& c, LoadX&& load_x, StoreX&& store_x) {
     constexpr int KT = QFmt<BITS>::KT, D = kUpRing, GR = D / TPG;
     const int tid = c.tid, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, half = lane >> 5;
@@ -115,6 +117,7 @@ __device__ __forceinline__ void b1_up(const WorkCtx& c, LoadX&& load_x, StoreX&&
         c.red[(wave * 2 + 1) * 32 + n] = out[1][0];
     }
     lds_barrier();
+    uint32_t mine = 0;
     if (tid < 32) {
         float a1 = 0.f, a3 = 0.f;
 #pragma unroll
@@ -123,22 +126,69 @@ __device__ __forceinline__ void b1_up(const WorkCtx& c, LoadX&& load_x, StoreX&&
             a3 += c.red[(w * 2 + 1) * 32 + n];
         }
         const _Float16 hv = (_Float16)(a1 / (1.0f + expf(-a1)) * a3);
-        const uint32_t mine = (uint32_t)__builtin_bit_cast(unsigned short, hv);
+        mine = (uint32_t)__builtin_bit_cast(unsigned short, hv);
+    }
+    return mine;
+}
+
+// 32 values of h (fp16 bits in lanes 0..31 of wave 0) go out as 16 tagged words
+__device__ __forceinline__ void b1_publish_h(unsigned long long* hq_dst, uint32_t tag, uint32_t mine) {
+    if (threadIdx.x < 32) {
         const uint32_t next = (uint32_t)__shfl_down((int)mine, 1, 64);
-        if ((n & 1) == 0)
-            __hip_atomic_store(hq_dst + (n >> 1), ((unsigned long long)tag << 32) | (unsigned long long)(mine | (next << 16)),
+        if ((threadIdx.x & 1) == 0)
+            __hip_atomic_store(hq_dst + (threadIdx.x >> 1),
+                               ((unsigned long long)tag << 32) | (unsigned long long)(mine | (next << 16)),
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
-__device__ __forceinline__ void b1_publish_zero_h(unsigned long long* hq_dst, uint32_t tag) {
-    if (threadIdx.x < 16)
-        __hip_atomic_store(hq_dst + threadIdx.x, (unsigned long long)tag << 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 // Routed blocks: poll the logits, redo softmax / top-k (wave 0), leave ids and weights in LDS.
 // The expert table travels to LDS while the logits are awaited.
-__device__ __forceinline__ bool b1_selection(const B1Args& A, uint32_t tag, uint4* tab, float* zl, int32_t* ids, float* wv) {
+// Which expert each routed slot works on.  Without a hint slot j takes the expert of rank j.
+// With a hint (k expert ids predicted for this layer, from the previous layer's call) the
+// blocks of slot j have started on expert hint[j] before the gate was known: slot j keeps it
+// if it is among the selected ones (first occurrence only), and the selected experts that
+// no slot holds go, in rank order, to the slots whose hint missed.  One wave; k <= 64.
+__device__ __forceinline__ void b1_assign_slots(const int32_t* hint, const int32_t* ids, const float* wv, int k,
+                                                int E, int32_t* src_e, float* src_w) {
+    const int lane = threadIdx.x & 63;
+    const int mine = lane < k ? ids[lane] : -1;          // lane r: the expert of rank r
+    int hj = -1;
+    if (hint != nullptr && lane < k) {
+        hj = hint[lane];
+        if (hj < 0 || hj >= E) hj = -1;
+    }
+    int rank_of_hint = -1;                                // slot `lane`: rank of its hinted expert, if selected
+    bool dup = false;
+    for (int r = 0; r < k; ++r) {
+        const int er = lane_bcast(mine, r), hr = lane_bcast(hj, r);
+        if (hj >= 0 && er == hj) rank_of_hint = r;
+        if (r < lane && hr == hj) dup = true;
+    }
+    const bool hit = lane < k && hj >= 0 && rank_of_hint >= 0 && !dup;
+    const unsigned long long hitmask = __ballot(hit);
+    bool taken = false;                                   // lane r: does a hit slot hold the expert of rank r?
+    for (int j = 0; j < k; ++j) {
+        const int rj = lane_bcast(rank_of_hint, j);
+        if (((hitmask >> j) & 1ull) && rj == lane) taken = true;
+    }
+    const unsigned long long freemask = __ballot(lane < k && !taken);    // ranks still to be placed
+    int r_mine = rank_of_hint;
+    if (lane < k && !hit) {
+        int nth = __popcll(~hitmask & ((1ull << lane) - 1ull));           // this slot is the nth missing one
+        unsigned long long fm = freemask;
+        for (int i = 0; i < nth; ++i) fm &= fm - 1;                       // drop the nth lowest set bits
+        r_mine = __ffsll((long long)fm) - 1;
+    }
+    const int e_mine = __shfl(mine, r_mine < 0 ? 0 : r_mine, 64);
+    if (lane < k) {
+        src_e[lane] = e_mine;
+        src_w[lane] = wv[r_mine < 0 ? 0 : r_mine];
+    }
+}
+
+__device__ __forceinline__ bool b1_selection(const B1Args& A, uint32_t tag, uint4* tab, float* zl, int32_t* ids, float* wv,
+                                             int32_t* src_e, float* src_w) {
     const LayerArgs& a = A.a;
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int E = a.r.E;
@@ -148,7 +198,11 @@ __device__ __forceinline__ bool b1_selection(const B1Args& A, uint32_t tag, uint
         if (tid == 0) atomicOr(a.status, 2);
         return false;
     }
-    if (wave == 0) wave_softmax_topk_rounds(zl, E, a.r.k, a.r.renorm, ids, wv);
+    if (wave == 0) {
+        wave_softmax_topk_rounds(zl, E, a.r.k, a.r.renorm, ids, wv);
+        __builtin_amdgcn_wave_barrier();
+        b1_assign_slots(a.hint, ids, wv, a.r.k, E, src_e, src_w);
+    }
     __syncthreads();
     return true;
 }
@@ -180,45 +234,79 @@ __device__ __forceinline__ void b1_up_role(const B1Args& A, int ub, bool is_shar
     const bool defer_x = is_shared && x_one;
     if (!defer_x) store_x(false);
 
-    fate_qexpert ex;
-    int kb;
-    unsigned long long* hq_dst;
-    if (is_shared) {
-        const int s = ub / a.nkb_s;
-        kb = ub - s * a.nkb_s;
-        ex = a.shared[s];
-        hq_dst = A.a.hq + ((size_t)s * a.nkb_s + kb) * 16;
-    } else {
-        const int slot = ub / a.nkb_r;
-        kb = ub - slot * a.nkb_r;
-        hq_dst = A.a.hq + ((size_t)a.n_shared * a.nkb_s + (size_t)slot * a.nkb_r + kb) * 16;
-        uint4* tab = reinterpret_cast<uint4*>(dyn + L.tab);
-        float* zl = reinterpret_cast<float*>(dyn + L.zl);
-        int32_t* ids = reinterpret_cast<int32_t*>(dyn + L.ids);
-        float* wv = reinterpret_cast<float*>(dyn + L.w);
-        if (!b1_selection(A, tag, tab, zl, ids, wv)) {
-            b1_publish_zero_h(hq_dst, tag);
-            return;
-        }
-        ex = reinterpret_cast<const fate_qexpert*>(tab)[ids[slot]];
-    }
-    B1_TS(1);
-    const bool absent = ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr;
-    if (kb * kLayerNeurons >= ex.I || absent) {
-        if (absent && tid == 0) atomicOr(a.status, 1);
-        b1_publish_zero_h(hq_dst, tag);
-        return;
-    }
     WorkCtx cx;
     cx.tid = tid;
-    cx.N = 1; cx.H = H; cx.I = ex.I; cx.T = 1; cx.kb = kb; cx.wb = ub; cx.ntp = 1; cx.ldx = ldx;
-    cx.is_shared = is_shared; cx.defer_x = defer_x; cx.ex = ex; cx.xs = xs;
+    cx.N = 1; cx.H = H; cx.T = 1; cx.wb = ub; cx.ntp = 1; cx.ldx = ldx;
+    cx.is_shared = is_shared; cx.defer_x = defer_x; cx.xs = xs;
     cx.hs = reinterpret_cast<_Float16*>(dyn + L.hs);
     cx.red = reinterpret_cast<float*>(dyn + L.red);
     cx.wtok = nullptr; cx.cx = reinterpret_cast<float*>(dyn + L.cx); cx.ch = nullptr;
     cx.tokid = nullptr; cx.pairq = nullptr; cx.part = nullptr; cx.part_stride = 0;
-    if (is_shared) b1_up<BS, TS>(cx, load_x, store_x, hq_dst, tag);
-    else b1_up<BR, TR>(cx, load_x, store_x, hq_dst, tag);
+    if (is_shared) {
+        const int s = ub / a.nkb_s;
+        const int kb = ub - s * a.nkb_s;
+        unsigned long long* hq_dst = A.a.hq + ((size_t)s * a.nkb_s + kb) * 16;
+        const fate_qexpert ex = a.shared[s];
+        B1_TS(1);
+        const bool absent = ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr;
+        uint32_t hbits = 0;
+        if (absent && tid == 0) atomicOr(a.status, 1);
+        if (!absent && kb * kLayerNeurons < ex.I) {
+            cx.I = ex.I; cx.kb = kb; cx.ex = ex;
+            hbits = b1_up<BS, TS>(cx, load_x, store_x);
+        }
+        b1_publish_h(hq_dst, tag, hbits);
+        return;
+    }
+    // Routed slot.  With a hint the block starts on the hinted expert at once (the paper's
+    // cross-layer prediction used as a prefetch: section 4.3) and only checks it against the gate's
+    // selection afterwards; a wrong hint costs a second pass with the right expert.
+    const int slot = ub / a.nkb_r;
+    const int kb = ub - slot * a.nkb_r;
+    unsigned long long* hq_dst = A.a.hq + ((size_t)a.n_shared * a.nkb_s + (size_t)slot * a.nkb_r + kb) * 16;
+    uint4* tab = reinterpret_cast<uint4*>(dyn + L.tab);
+    float* zl = reinterpret_cast<float*>(dyn + L.zl);
+    int32_t* ids = reinterpret_cast<int32_t*>(dyn + L.ids);
+    float* wv = reinterpret_cast<float*>(dyn + L.w);
+    int32_t* src_e = reinterpret_cast<int32_t*>(dyn + L.pairq);     // (regions the one-token kernel has no other use for)
+    float* src_w = reinterpret_cast<float*>(dyn + L.wtok);
+    int e_cur = -1;
+    fate_qexpert ex{};
+    if (a.hint != nullptr) {
+        e_cur = a.hint[slot];
+        if (e_cur < 0 || e_cur >= E) e_cur = -1;
+        if (e_cur >= 0) ex = a.experts[e_cur];
+    }
+    bool selected = false;
+    uint32_t hbits = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        bool absent = true;
+        if (e_cur >= 0) {
+            absent = ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr;
+            hbits = 0;
+            if (!absent && kb * kLayerNeurons < ex.I) {
+                cx.I = ex.I; cx.kb = kb; cx.ex = ex;
+                hbits = b1_up<BR, TR>(cx, load_x, store_x);
+            }
+        }
+        if (!selected) {
+            if (!b1_selection(A, tag, tab, zl, ids, wv, src_e, src_w)) {
+                b1_publish_h(hq_dst, tag, 0);
+                return;
+            }
+            selected = true;
+        }
+        const int e_true = src_e[slot];
+        if (e_cur == e_true) {
+            if (absent && tid == 0) atomicOr(a.status, 1);
+            break;
+        }
+        e_cur = e_true;
+        ex = reinterpret_cast<const fate_qexpert*>(tab)[e_true];
+        lds_barrier();          // every wave is done with the first pass's sums
+    }
+    B1_TS(1);
+    b1_publish_h(hq_dst, tag, hbits);
 }
 
 // ---- down block: 32 output rows, four wave items --------------------------------------------
@@ -292,29 +380,32 @@ __device__ __forceinline__ float b1_down_product(const uint4 (&raw)[kB1MaxTiles]
     const BiasConst bc = bias_const();
     const f32x16_t zero = f32x16_zero();
     float out = 0.f;
-    f16x8_t av[S], avn[S];
+    // two groups at a time, each with an accumulator of its own: the dependent matrix-core steps
+    // of one group run under those of the other
+    static_assert(MAXG % 2 == 0, "groups are taken in pairs");
 #pragma unroll
-    for (int st = 0; st < S; ++st) av[st] = *reinterpret_cast<const f16x8_t*>(ha + 8 * st);
-#pragma unroll
-    for (int jg = 0; jg < MAXG; ++jg) {
-        f32x16_t acc;
+    for (int jg = 0; jg < MAXG; jg += 2) {
+        f32x16_t acc0, acc1;
 #pragma unroll
         for (int tl = 0; tl < TPG; ++tl) {
-            const int j = jg * TPG + tl;
-            if (j + 1 < kB1MaxTiles) {
+            const int j0 = jg * TPG + tl, j1 = (jg + 1) * TPG + tl;
+            f16x8_t a0[S], a1[S], b0[S], b1[S];
 #pragma unroll
-                for (int st = 0; st < S; ++st) avn[st] = *reinterpret_cast<const f16x8_t*>(ha + (j + 1) * KT + 8 * st);
+            for (int st = 0; st < S; ++st) {
+                a0[st] = *reinterpret_cast<const f16x8_t*>(ha + j0 * KT + 8 * st);
+                a1[st] = *reinterpret_cast<const f16x8_t*>(ha + j1 * KT + 8 * st);
             }
-            f16x8_t b[S];
-            biased_tile<BITS>(raw[j], bc, b);
+            biased_tile<BITS>(raw[j0], bc, b0);
+            biased_tile<BITS>(raw[j1], bc, b1);
 #pragma unroll
-            for (int st = 0; st < S; ++st)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[st], b[st], (tl == 0 && st == 0) ? zero : acc, 0, 0, 0);
-#pragma unroll
-            for (int st = 0; st < S; ++st) av[st] = avn[st];
+            for (int st = 0; st < S; ++st) {
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0[st], b0[st], (tl == 0 && st == 0) ? zero : acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1[st], b1[st], (tl == 0 && st == 0) ? zero : acc1, 0, 0, 0);
+            }
         }
         // groups past the item's end multiply stale h with repeated tiles: they do not count
-        if (jg < ng) out = fmaf(half_bits_to_float(sc[jg]), acc[0] - ch[jg], out);
+        if (jg < ng) out = fmaf(half_bits_to_float(sc[jg]), acc0[0] - ch[jg], out);
+        if (jg + 1 < ng) out = fmaf(half_bits_to_float(sc[jg + 1]), acc1[0] - ch[jg + 1], out);
     }
     return out;
 }
@@ -334,32 +425,18 @@ __device__ __forceinline__ void b1_down_role(const B1Args& A, int part, int rb, 
     for (int c = tid; c < kB1HRegion / 8; c += kLayerThreads)
         *reinterpret_cast<uint4*>(zrow + c * 8) = make_uint4(0, 0, 0, 0);
     lds_barrier();
-    fate_qexpert ex;
     float wsrc = 1.f;
-    const unsigned long long* hq_src;
     bool failed = false;
-    if (is_shared) {
-        ex = a.shared[it.ng > 0 ? it.src : 0];
-        hq_src = A.a.hq + (size_t)it.src * a.nkb_s * 16;
-    } else {
-        uint4* tab = reinterpret_cast<uint4*>(dyn + L.tab);
-        float* zl = reinterpret_cast<float*>(dyn + L.zl);
-        int32_t* ids = reinterpret_cast<int32_t*>(dyn + L.ids);
-        float* wv = reinterpret_cast<float*>(dyn + L.w);
-        const int slot = it.ng > 0 ? it.src - a.n_shared : 0;
-        hq_src = A.a.hq + ((size_t)a.n_shared * a.nkb_s + (size_t)slot * a.nkb_r) * 16;
-        if (!b1_selection(A, tag, tab, zl, ids, wv)) {
-            failed = true;
-            ex = fate_qexpert{};
-        } else {
-            ex = reinterpret_cast<const fate_qexpert*>(tab)[ids[slot]];
-            wsrc = wv[slot];
-        }
-    }
-    B1_TS(1);
     float out = 0.f;
-    // (the gate of the shared experts is evaluated behind the W2 requests, before the wait for h)
-    auto shared_gate = [&]() {
+    if (is_shared) {
+        const fate_qexpert ex = a.shared[it.ng > 0 ? it.src : 0];
+        const unsigned long long* hq_src = A.a.hq + (size_t)it.src * a.nkb_s * 16 + (size_t)it.g0 * 64;
+        B1_TS(1);
+        uint4 raw[kB1MaxTiles];
+        uint32_t sc[kB1MaxTiles / TS];
+        const int ng = it.ng > 0 ? b1_down_request<BS, TS>(ex, H, rb, it.g0, it.ng, raw, sc) : 0;
+        B1_TS(2);
+        // the gate of the shared experts, evaluated behind the W2 requests, before the wait for h
         if (a.shared_gate != nullptr) {
             if (wave == 0) {
                 const float g = wave_sigmoid_dot_bf16(reinterpret_cast<const uint4*>(a.r.x),
@@ -369,20 +446,42 @@ __device__ __forceinline__ void b1_down_role(const B1Args& A, int part, int rb, 
         } else if (tid == 0) {
             gate[0] = 1.f;
         }
-    };
-#define FATE_B1_DOWN(BITS, TPG)                                                                          \
-    {                                                                                                     \
-        uint4 raw[kB1MaxTiles];                                                                           \
-        uint32_t sc[kB1MaxTiles / TPG];                                                                   \
-        const int ng = (!failed && it.ng > 0) ? b1_down_request<BITS, TPG>(ex, H, rb, it.g0, it.ng, raw, sc) : 0; \
-        B1_TS(2);                                                                                         \
-        if (is_shared) shared_gate();                                                                     \
-        if (ng > 0)                                                                                       \
-            out = b1_down_product<BITS, TPG>(raw, sc, ng, hq_src + (size_t)it.g0 * 64, tag, hl, zrow, &failed); \
+        if (ng > 0) out = b1_down_product<BS, TS>(raw, sc, ng, hq_src, tag, hl, zrow, &failed);
+    } else {
+        uint4* tab = reinterpret_cast<uint4*>(dyn + L.tab);
+        float* zl = reinterpret_cast<float*>(dyn + L.zl);
+        int32_t* ids = reinterpret_cast<int32_t*>(dyn + L.ids);
+        float* wv = reinterpret_cast<float*>(dyn + L.w);
+        int32_t* src_e = reinterpret_cast<int32_t*>(dyn + L.src_e);
+        float* src_w = reinterpret_cast<float*>(dyn + L.src_w);
+        const int slot = it.ng > 0 ? it.src - a.n_shared : 0;
+        const unsigned long long* hq_src =
+            A.a.hq + ((size_t)a.n_shared * a.nkb_s + (size_t)slot * a.nkb_r) * 16 + (size_t)it.g0 * 64;
+        uint4 raw[kB1MaxTiles];
+        uint32_t sc[kB1MaxTiles / TR];
+        // with a hint the W2 slice of the hinted expert is requested before the gate is known
+        int e_cur = -1, ng = 0;
+        if (a.hint != nullptr && it.ng > 0) {
+            e_cur = a.hint[slot];
+            if (e_cur < 0 || e_cur >= E) e_cur = -1;
+            if (e_cur >= 0) {
+                const fate_qexpert exh = a.experts[e_cur];
+                ng = b1_down_request<BR, TR>(exh, H, rb, it.g0, it.ng, raw, sc);
+            }
+        }
+        if (!b1_selection(A, tag, tab, zl, ids, wv, src_e, src_w)) {
+            failed = true;
+        } else {
+            const int e_true = src_e[slot];
+            wsrc = src_w[slot];
+            if (it.ng > 0 && e_true != e_cur) {
+                const fate_qexpert ex = reinterpret_cast<const fate_qexpert*>(tab)[e_true];
+                ng = b1_down_request<BR, TR>(ex, H, rb, it.g0, it.ng, raw, sc);
+            }
+            B1_TS(2);
+            if (ng > 0) out = b1_down_product<BR, TR>(raw, sc, ng, hq_src, tag, hl, zrow, &failed);
+        }
     }
-    if (is_shared) FATE_B1_DOWN(BS, TS)
-    else FATE_B1_DOWN(BR, TR)
-#undef FATE_B1_DOWN
     B1_TS(4);
     if (failed && lane == 0) atomicOr(a.status, 2);
     if (lane < 32) red[wave * 32 + lane] = wsrc * out;
@@ -519,7 +618,7 @@ static int b1_add_items(B1Item* items, int n, int src, int G, int maxg) {
 }
 
 bool b1_plan(const fate_ffn_desc& d, const LayerArgs& a, B1Args* b, int* nblocks) {
-    if (d.N != 1) return false;
+    if (d.N != 1 || d.k > kTokPass) return false;
     const int bits_s = d.n_shared ? d.shared_bits : d.bits, group_s = d.n_shared ? d.shared_group : d.group;
     if (!b1_format(d.bits, d.group) || !b1_format(bits_s, group_s)) return false;
     // the straight-line up projection: a whole number of register rings per wave

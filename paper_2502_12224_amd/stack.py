@@ -69,15 +69,17 @@ class LayerBuffers:
         return int(self.layer_ws[self.status_offset:self.status_offset + 4].view(torch.int32)[0])
 
 
-def layer_forward(cfg: MoEShape, lw: LayerWeights, lw_next, x, buf: LayerBuffers, fused=None, one_launch=None):
-    """One MoE layer: route, predict the next layer's experts, permute, FFN."""
+def layer_forward(cfg: MoEShape, lw: LayerWeights, lw_next, x, buf: LayerBuffers, fused=None, one_launch=None,
+                  hint_ids=None):
+    """One MoE layer: route, predict the next layer's experts, permute, FFN.
+    hint_ids: the previous layer's prediction for this layer (device int32, k ids), or None."""
     one_launch = (buf.one_launch_ok and fused is None) if one_launch is None else one_launch
     if one_launch:
         B.fate_moe_layer_decode(buf.desc, x, lw.Wg, lw.bias, None if lw_next is None else lw_next.Wg,
                                 None if lw_next is None else lw_next.bias, cfg.m, cfg.renorm, buf.ids, buf.w,
                                 buf.pred_ids, buf.pred_w, buf.pred_pop, buf.counts, buf.offsets, buf.perm,
                                 buf.inv_perm, buf.order, lw.table, lw.shared_table, lw.shared_gate, buf.y,
-                                buf.layer_ws)
+                                buf.layer_ws, hint_ids=hint_ids)
         return buf.y
     fused = buf.fused_ok if fused is None else fused
     if fused:

@@ -188,3 +188,57 @@ def test_one_launch_layer_replayed_from_a_graph(name, N):
         # eager work of the program between the replays
         layer_forward(cfg, lw, ln, xs[(s + 1) % 4], eager, one_launch=True)
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name", ["qwen", "deepseek"])
+def test_one_token_layer_with_prefetch_hints(name):
+    """The previous layer's prediction handed in as a hint (section 4.3): the routed work groups start on
+    the hinted experts before the gate is known.  Whatever the hint - exact, permuted, partly or wholly
+    wrong, repeated, out of range, pointing at an expert that is not resident - the routing outputs are
+    those of the call without a hint, bit for bit, and y differs at most in the order of its fp32 sums."""
+    cfg = SHAPES[name]
+    E, k = cfg.E, cfg.k
+    x = gen_hidden(cfg, 1, step=11, device=DEV)
+    lw = LayerWeights(cfg, 0, DEV)
+    ln = LayerWeights(cfg, 1, DEV, experts=[])
+    ref = LayerBuffers(cfg, 1, DEV)
+    layer_forward(cfg, lw, ln, x, ref, one_launch=True)
+    torch.cuda.synchronize()
+    assert ref.status() == 0
+    true = ref.ids.cpu().numpy()[0].tolist()
+    others = [e for e in range(E) if e not in true]
+    # an expert that is not selected and not resident: a hint may name it without consequences
+    gone = others[0]
+    lw.table[gone * 64:(gone + 1) * 64].zero_()
+    hints = {
+        "exact": true,
+        "reversed": true[::-1],
+        "one wrong": true[:1] + [others[1]] + true[2:],
+        "all wrong": others[1:1 + k],
+        "repeated": [true[0]] * k,
+        "out of range": [-1, E + 5] + true[:k - 2],
+        "not resident": [gone] + true[1:],
+    }
+    y_ref = f32(ref.y).astype(np.float64)
+    fields = ROUTE_FIELDS + PRED_FIELDS
+    got = LayerBuffers(cfg, 1, DEV)
+    for what, h in hints.items():
+        print(f"case {name} hint {what}: {h}", flush=True)
+        hint = torch.tensor(h, dtype=torch.int32, device=DEV)
+        got.y.fill_(float("nan"))
+        layer_forward(cfg, lw, ln, x, got, one_launch=True, hint_ids=hint)
+        torch.cuda.synchronize()
+        assert got.status() == 0, what
+        for f in fields:
+            assert torch.equal(getattr(got, f), getattr(ref, f)), (what, f)
+        assert ffn_rel_err(f32(got.y), y_ref).max() <= 1e-5, what
+    # against the oracle once more, with the exact hint
+    hint = torch.tensor(true, dtype=torch.int32, device=DEV)
+    layer_forward(cfg, lw, ln, x, got, one_launch=True, hint_ids=hint)
+    torch.cuda.synchronize()
+    from workloads import gen_expert
+    experts = {int(e): oracle_expert(gen_expert(cfg, 0, int(e), device=DEV)) for e in true}
+    shared = [oracle_expert(gen_expert(cfg, 0, s, shared=True, device=DEV)) for s in range(cfg.n_shared)]
+    sg = None if lw.shared_gate is None else f32(lw.shared_gate)
+    y_orc = O.moe_ffn(f32(x), ref.ids.cpu().numpy(), ref.w.cpu().numpy().astype(np.float64), experts, shared, sg)
+    assert ffn_rel_err(f32(got.y), y_orc).max() <= 2e-3
