@@ -34,16 +34,47 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def kernel_sources_id():
+    """sha256 (first 16 hex digits) over the library's sources: names the build a stored counter figure belongs to."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2502_12224_amd", "csrc")
+    for f in sorted(os.listdir(csrc)):
+        if f.endswith((".hip", ".h", ".cpp")):
+            h.update(f.encode())
+            h.update(open(os.path.join(csrc, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(name):
-    """HBM bytes per launch from the counter runs summarised under profiles/ (None if not measured)."""
+    """HBM bytes per launch from the counter runs summarised under profiles/.  The summary names the
+    sources it was taken on (kernel_sources_id); a figure of another build is not reported (None)."""
     path = os.path.join(ROOT, "profiles", name)
+    val = src = None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split("=")[1])
+                val = float(line.split("=")[1])
+            if line.startswith("kernel_sources_id"):
+                src = line.split("=")[1].strip()
     except OSError:
+        return None
+    if val is None or src != kernel_sources_id():
+        log(f"[bench] {name}: counters were taken on sources {src}, this build is {kernel_sources_id()} -> traffic null")
+        return None
+    return val
+
+
+def blas_threads():
+    """Threads the numpy oracle's matrix products really use (the BLAS pool), not the affinity mask."""
+    try:
+        from threadpoolctl import threadpool_info
+        n = [p["num_threads"] for p in threadpool_info() if p.get("user_api") == "blas"]
+        if n:
+            return max(n)
+    except Exception:
         pass
-    return None
+    return len(os.sched_getaffinity(0))
 
 
 def expert_bytes(H, I, bits, group):
@@ -153,6 +184,13 @@ def bench_decode(args):
     acc = [O.prediction_accuracy(p_ids[s, l], t_ids[s, l + 1], cfg.k) for s in range(S) for l in range(L - 1)]
     acc_k = float(np.mean([v[0] for v in acc]))
     rec_m = float(np.mean([v[1] for v in acc]))
+    # rows whose fp64 logits have a top-k gap below 1e-5 (their selection may legitimately differ from fp64)
+    near_ties = 0
+    for l in range(L):
+        lw = stack.layers[l]
+        z = O.gate_logits(xs[:, l].reshape(S * N, H).float().cpu().numpy(), lw.Wg.float().cpu().numpy(),
+                          None if lw.bias is None else lw.bias.cpu().numpy())
+        near_ties += len(O.near_tie_rows(z, cfg.k))
 
     # per-layer buffers whose counts / predicted popularity sit in one arena
     bufs = [LayerBuffers(cfg, N, dev) for _ in range(L)]
@@ -220,6 +258,10 @@ def bench_decode(args):
     ms_per_step = elapsed * 1e3 / args.steps
     tok_s = args.steps * N / elapsed
     log(f"[bench] {args.steps} tokens in {elapsed * 1e3:.1f} ms -> {tok_s:.1f} tok/s")
+    # a wait that ran out or an expert without weights inside the timed region voids the figure
+    bad = [(l, b.status()) for l, b in enumerate(bufs) if b.status() != 0]
+    if bad:
+        raise SystemExit(f"bench.py: layer kernels reported a non-zero status word {bad}: the timing is not valid")
 
     # results of the graph path equal the eager chain (same inputs)
     x_in.copy_(xs[3]); graph.replay(); torch.cuda.synchronize()
@@ -261,7 +303,7 @@ def bench_decode(args):
         ncores = len(os.sched_getaffinity(0))
         per, n_units, t_cpu = cpu_baseline_decode(cfg, xs, layers_sample=[0, 1, 6, 12, 18, 22],
                                                   tokens_sample=list(range(12 if qwen else 2)))
-        cpu = {"value": 1.0 / (per * L), "unit": "tokens/s", "cores": min(ncores, torch.get_num_threads()),
+        cpu = {"value": 1.0 / (per * L), "unit": "tokens/s", "cores": min(ncores, blas_threads()),
                "kind": "oracle",
                "sample": f"{n_units} (token, layer) units of the same stack (layers 0, 1, 6, 12, 18, 22; decode steps 0-11), "
                          f"{t_cpu:.1f} s of oracle time, scaled to {L} layers per token"}
@@ -279,6 +321,7 @@ def bench_decode(args):
                    "layer_us": ms_per_step * 1e3 / L, "layer_algorithmic_MB": layer_bytes / 1e6,
                    "layer_hbm_frac": layer_bytes / (ms_per_step * 1e-3 / L) / 1e9 / HBM_PEAK_GBS,
                    "prediction_accuracy_topk": acc_k, "prediction_recall_topm": rec_m, "m": cfg.m,
+                   "near_tie_rows": near_ties, "routed_rows": S * N * L,
                    "cache_hit_rate": tot["hits"] / max(1, tot["hits"] + tot["misses"])},
         "roofline": {"bound": "hbm", "kernel": "moe_layer_decode_kernel + layer_reduce_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
@@ -347,6 +390,12 @@ def bench_prefill(args, emit=True):
     tok_acc = float(np.mean([O.prediction_accuracy(p_ids[l], t_ids[l + 1], cfg.k)[0]
                              for l in range(L - 1)])) if L > 1 else None
     active = float(np.mean([len(set(t_ids[l].ravel())) for l in range(L)]))
+    near_ties = 0
+    for l in range(L):
+        lw = stack.layers[l]
+        z = O.gate_logits(xs[0, l].float().cpu().numpy(), lw.Wg.float().cpu().numpy(),
+                          None if lw.bias is None else lw.bias.cpu().numpy())
+        near_ties += len(O.near_tie_rows(z, cfg.k))
 
     bufs = [LayerBuffers(cfg, N, dev, mode=2) for _ in range(L)]
     counts_all = torch.zeros(L, E, dtype=torch.int32, device=dev)
@@ -397,6 +446,10 @@ def bench_prefill(args, emit=True):
     ms_per_step = elapsed * 1e3 / args.steps
     tok_s = args.steps * N / elapsed
     log(f"[bench] {args.steps} passes of {N} tokens x {L} layers in {elapsed * 1e3:.1f} ms -> {tok_s:.0f} tok/s")
+    bad = [(l, int(b.ffn_ws[:4].view(torch.int32)[0])) for l, b in enumerate(bufs)
+           if int(b.ffn_ws[:4].view(torch.int32)[0]) != 0]
+    if bad:
+        raise SystemExit(f"bench.py: the FFN reported a non-zero status word {bad}: the timing is not valid")
 
     # roofline of the dominant kernel: the up/gate grouped GEMM (2/3 of the FLOPs)
     up_flops = 4.0 * H * (N * cfg.k * cfg.I + N * cfg.n_shared * (cfg.I_shared or 0))
@@ -430,7 +483,7 @@ def bench_prefill(args, emit=True):
         t_route, t_ffn = cpu_baseline_prefill(cfg, x_in[0], 0, rows)
         per_token = t_route / N + t_ffn / len(rows)
         cpu = {"value": 1.0 / (per_token * L), "unit": "tokens/s",
-               "cores": min(len(os.sched_getaffinity(0)), torch.get_num_threads()), "kind": "oracle",
+               "cores": min(len(os.sched_getaffinity(0)), blas_threads()), "kind": "oracle",
                "sample": f"layer 0: routing, prediction and permutation of all {N} tokens ({t_route:.2f} s) and the "
                          f"FFN of {len(rows)} token rows ({t_ffn:.1f} s, includes dequantising their experts), "
                          f"scaled per token to {L} layers"}
@@ -446,7 +499,7 @@ def bench_prefill(args, emit=True):
                    "layer_useful_GFLOP": layer_flops / 1e9, "ffn_call_us": ffn_us,
                    "ffn_mfma_frac": layer_flops / (ffn_us * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS,
                    "experts_active_per_layer": active, "prefill_set_accuracy": set_acc,
-                   "prediction_accuracy_topk_per_token": tok_acc,
+                   "prediction_accuracy_topk_per_token": tok_acc, "near_tie_rows": near_ties, "routed_rows": N * L,
                    "cache_hit_rate": hits / max(1, hits + misses)},
         "roofline": {"bound": "mfma", "kernel": "prefill_prep_kernel + grouped_gemm_kernel<2>", "achieved": achieved,
                      "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_PEAK_TFLOPS,
@@ -492,22 +545,27 @@ def bench_offload(args):
     from paper_2502_12224_amd.stack import LayerBuffers, OffloadedStack
     from workloads import SHAPES, chain_next_hidden, gen_hidden, unit_rmsnorm_bf16
 
+    import dataclasses
     shape, Np, Nd, S, desc = OFFLOAD_WORKLOADS[args.workload]
     cfg = SHAPES[shape]
+    if args.routed_bits:
+        cfg = dataclasses.replace(cfg, bits=args.routed_bits)       # ablation: experts moved and cached at 8 bits
     dev = "cuda"
     L = args.layers or cfg.layers
     E, H = cfg.E, cfg.H
     steps = args.steps
-    cache_total = int(cfg.cache_frac * L * E)
+    mode = args.mode
+    cache_frac = cfg.cache_frac if args.cache_frac is None else args.cache_frac
+    cache_total = 0 if mode == "lod" else int(cache_frac * L * E)
     lib = B.lib()
     ebytes = expert_bytes(H, cfg.I, cfg.bits, cfg.group)
     peak = h2d_peak_gbs(dev)
     t_expert = ebytes / (peak * 1e9)
-    n_max = args.n_max if args.n_max is not None else min(E, Nd * cfg.m)
     t0 = time.time()
     log(f"[bench] {args.workload}: {L} layers x {E} experts of {ebytes / 1e6:.2f} MB -> pinned host pool "
-        f"{L * E * ebytes / 1e9:.1f} GB; cache_total {cache_total}, n_max {n_max}, H2D peak {peak:.1f} GB/s")
-    st = OffloadedStack(cfg, cache_total, n_max, staging_slots=2 * E + n_max, device=dev, layers=L,
+        f"{L * E * ebytes / 1e9:.1f} GB; cache_total {cache_total}, H2D peak {peak:.1f} GB/s")
+    st = OffloadedStack(cfg, cache_total, 0, staging_slots=3 * E, device=dev, layers=L,
+                        predictor={"fate": "gate", "eap": "eap", "lod": "none"}[mode],
                         progress=lambda l: log(f"[bench]   layer {l} in the host pool ({time.time() - t0:.0f}s)"))
     log(f"[bench] per-layer capacities {st.caps}")
 
@@ -543,7 +601,32 @@ def bench_offload(args):
     pbuf = LayerBuffers(cfg, Np, dev)
     dbuf = LayerBuffers(cfg, Nd, dev)
     run(Nd, 1, 10_000, dbuf)                 # warm the kernels and the copy path
-    B._check(lib.fate_cache_set_n_max(st.cache, E))      # prefill: every predicted expert, most popular first
+    # Calibration of the decode prefetch cap (section 4.3): T is the compute time of a layer whose experts
+    # are all on the device - layer 0 is fully cached, so its calls issue no copy - and n = floor(T / t_expert).
+    t_layer_resident, n_cal = None, None
+    if st.caps[0] == E:
+        xcal = unit_rmsnorm_bf16(gen_hidden(cfg, Nd, step=30_000, device=dev).to(torch.float32))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(3):
+            st.layer(0, xcal, dbuf)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(20):
+            st.layer(0, xcal, dbuf)
+        e1.record()
+        torch.cuda.synchronize()
+        t_layer_resident = e0.elapsed_time(e1) * 1e-3 / 20
+        n_cal = lib.fate_n_max_from_times(t_layer_resident, 0.0, 0.0, t_expert)
+        log(f"[bench] resident layer {t_layer_resident * 1e6:.1f} us, one expert over the link "
+            f"{t_expert * 1e6:.1f} us -> n = {n_cal}")
+    n_max = 0 if mode == "lod" else (args.n_max if args.n_max is not None else (n_cal or 0))
+    log(f"[bench] mode {mode}, decode prefetch cap {n_max}")
+    if mode == "eap":
+        # the baseline's statistics: co-activation counts over calibration decode steps (untimed, no prefetch)
+        st.eap_learning = True
+        run(Nd, args.eap_calibration_steps, 40_000, dbuf)
+        st.eap_learning = False
+    B._check(lib.fate_cache_set_n_max(st.cache, 0 if mode == "lod" else E))   # prefill: every predicted expert, most popular first
     pre = phase(Np, 1, 20_000, pbuf)
     B._check(lib.fate_cache_set_n_max(st.cache, n_max))
     log(f"[bench] prefill {Np} tokens: {pre['seconds'] * 1e3:.1f} ms, {pre['tokens_per_s']:.0f} tok/s, "
@@ -552,8 +635,6 @@ def bench_offload(args):
     dec = phase(Nd, steps, args.warmup, dbuf)
     log(f"[bench] decode batch {Nd} x {steps} steps: {dec['tokens_per_s']:.1f} tok/s, hit rate {dec['hit_rate']:.3f} "
         f"(cache only {dec['hit_rate_cache_only']:.3f}), H2D {dec['h2d_GB']:.2f} GB at {dec['h2d_GBs']:.1f} GB/s")
-    layer_s = dec["seconds"] / (steps * L)
-    n_cal = lib.fate_n_max_from_times(layer_s, 0.0, 0.0, t_expert)
     out = {
         "metric": "MoE-layer tokens/s (decode b=1, prefill 512) + % HBM / MFMA roofline",
         "value": dec["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
@@ -561,8 +642,11 @@ def bench_offload(args):
         "vs_baseline": None, "dtype": "int4/int8 weights, bf16/fp16 activations, fp32 accumulate",
         "data": "synthetic",
         "config": {"workload": desc, "step": f"one decode step of batch {Nd} through {L} MoE layers, experts offloaded",
-                   "layers": L, "batch": Nd, "cache_total": cache_total, "layer_capacities": st.caps,
-                   "n_max": n_max, "n_max_from_measured_times": n_cal, "t_expert_us": t_expert * 1e6,
+                   "layers": L, "batch": Nd, "mode": mode, "routed_bits": cfg.bits, "cache_frac": cache_frac,
+                   "cache_total": cache_total, "layer_capacities": st.caps,
+                   "n_max": n_max, "n_from_resident_layer_time": n_cal,
+                   "t_layer_resident_us": None if t_layer_resident is None else t_layer_resident * 1e6,
+                   "t_expert_us": t_expert * 1e6,
                    "decode": dec, "prefill": dict(tokens=Np, **pre)},
         "roofline": {"bound": "pcie", "kernel": "side-stream H2D copies of missed / prefetched experts",
                      "achieved": dec["h2d_GBs"], "peak": peak, "unit": "GB/s", "frac": dec["h2d_GBs"] / peak,
@@ -588,8 +672,17 @@ def main():
                          "at this prediction accuracy: a wrong hint costs a second pass)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="decode: also run five 1 GiB device copies (reference for hardware-counter runs)")
+    ap.add_argument("--mode", default="fate", choices=["fate", "eap", "lod"],
+                    help="offload workloads: fate = cross-layer gate prediction + shallow-favoring cache (the method); "
+                         "eap = same cache, activation-path prediction; lod = no cache, no prefetch (load on demand)")
+    ap.add_argument("--cache-frac", type=float, default=None,
+                    help="offload workloads: fraction of the routed experts cached on the device (default: the configuration's)")
+    ap.add_argument("--routed-bits", type=int, default=0, choices=[0, 4, 8],
+                    help="offload workloads: code width of the routed experts (ablation of the quantisation step)")
+    ap.add_argument("--eap-calibration-steps", type=int, default=32)
     ap.add_argument("--n-max", type=int, default=None,
-                    help="offload workloads: cap on prefetched experts per layer (default: batch * m, at most E)")
+                    help="offload workloads: cap on prefetched experts per layer in decode (default: n = floor(T / "
+                         "t_expert) from the measured resident layer time and link rate)")
     args = ap.parse_args()
     decode = args.workload in DECODE_WORKLOADS
     if args.steps is None:

@@ -342,6 +342,25 @@ fate_status fate_expert_cache_step_dense(fate_cache*, int layer, const int32_t* 
 fate_status fate_expert_cache_step_layers(fate_cache*, int layer_begin, int layer_end, const int32_t* counts,
                                           const int32_t* pred_pop, fate_cache_stats* stats_sum);
 
+/* ------------------------------------------------------------------------
+ * Activation-path predictor: the prefetch policy of the paper's EAP baseline
+ * (section 5.1: the experts of the next block are predicted from the token's
+ * expert choices in the previous block and statistics collected beforehand),
+ * kept as a comparison mode; its output feeds the same cache step.  Host
+ * integer logic.
+ *   fate_eap_update: adds one calibration batch: ids_l / ids_next [N,k] host,
+ *     the choices of the same tokens in blocks `layer` and `layer`+1.
+ *   fate_eap_predict: pred_pop [E] host out = number of tokens of ids_l [N,k]
+ *     whose m highest positive co-activation scores include the expert (ties to
+ *     the lower id); all zero for the last block.
+ * ---------------------------------------------------------------------- */
+typedef struct fate_eap fate_eap;
+fate_eap* fate_eap_create(int num_layers, int E);
+void fate_eap_destroy(fate_eap*);
+fate_status fate_eap_update(fate_eap*, int layer, const int32_t* ids_l, const int32_t* ids_next, int N, int k);
+fate_status fate_eap_predict(const fate_eap*, int layer, const int32_t* ids_l, int N, int k, int m,
+                             int32_t* pred_pop);
+
 /* Built-in HIP copy engine.  slot_pool_dev: total_slots * slot_bytes of device
  * memory; host_pool_pinned: num_layers*E experts of slot_bytes each (pinned),
  * expert (l,e) at ((l*E)+e)*slot_bytes, already in device-native layout with

@@ -258,3 +258,45 @@ class CacheOracle:
                 r.loads.append((t, e, s, False))
                 issued += 1
         return r
+
+
+class EAPPredictor:
+    """Activation-path predictor of the paper's EAP baseline (section 5.1): the experts of the
+    next block are predicted from the token's expert choices in the previous block and
+    statistics collected beforehand - here the co-activation counts
+    freq[l][e][e'] = number of calibration tokens that chose e in block l and e' in block l+1.
+
+    Reading (the paper gives one sentence): a token's score for a next-block expert is the sum of
+    freq over the experts it chose; its prediction is the m experts with the highest positive
+    scores, ties to the lower id; over a batch the predicted popularity of an expert is the
+    number of tokens that predict it (the same aggregate the cross-layer prediction produces)."""
+
+    def __init__(self, num_layers, E):
+        self.num_layers, self.E = num_layers, E
+        self.freq = [[[0] * E for _ in range(E)] for _ in range(max(0, num_layers - 1))]
+
+    def update(self, layer, ids_l, ids_next):
+        """ids_l, ids_next: [N][k] expert choices of the same tokens in blocks layer and layer+1."""
+        f = self.freq[layer]
+        for row, nxt in zip(ids_l, ids_next):
+            for e in row:
+                for e2 in nxt:
+                    f[int(e)][int(e2)] += 1
+
+    def predict(self, layer, ids_l, m):
+        """Predicted popularity [E] of block layer+1 from the choices ids_l [N][k] in block layer."""
+        pop = [0] * self.E
+        if layer + 1 >= self.num_layers:
+            return pop
+        f = self.freq[layer]
+        for row in ids_l:
+            score = [0] * self.E
+            for e in row:
+                fe = f[int(e)]
+                for e2 in range(self.E):
+                    score[e2] += fe[e2]
+            order = sorted(range(self.E), key=lambda e2: (-score[e2], e2))
+            for e2 in order[:m]:
+                if score[e2] > 0:
+                    pop[e2] += 1
+        return pop

@@ -27,6 +27,7 @@ EXPORTS = [
     "fate_expert_cache_step_layers", "fate_hip_engine_create", "fate_hip_engine_destroy",
     "fate_hip_engine_copy", "fate_hip_engine_begin_step", "fate_hip_engine_wait_ready",
     "fate_hip_engine_preload", "fate_hip_engine_bytes_copied",
+    "fate_eap_create", "fate_eap_destroy", "fate_eap_update", "fate_eap_predict",
 ]
 
 
@@ -108,6 +109,12 @@ def lib():
         L.fate_hip_engine_preload.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int]
         L.fate_hip_engine_bytes_copied.restype = C.c_uint64
         L.fate_hip_engine_bytes_copied.argtypes = [C.c_void_p]
+        L.fate_eap_create.restype = C.c_void_p
+        L.fate_eap_create.argtypes = [C.c_int, C.c_int]
+        L.fate_eap_destroy.restype = None
+        L.fate_eap_destroy.argtypes = [C.c_void_p]
+        L.fate_eap_update.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int]
+        L.fate_eap_predict.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         _lib = L
     return _lib
 

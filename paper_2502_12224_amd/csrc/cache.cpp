@@ -432,3 +432,74 @@ extern "C" fate_status fate_expert_cache_step_layers(fate_cache* c, int layer_be
     *stats_sum = sum;
     return FATE_OK;
 }
+
+// ---- activation-path predictor (the EAP baseline of section 5.1) ------------------------------
+// Co-activation counts freq[l][e][e'] of calibration tokens between consecutive blocks; a token's
+// prediction for block l+1 is the m experts with the highest positive summed counts over the
+// experts it chose in block l (ties to the lower id); the predicted popularity of an expert is
+// the number of tokens that predict it.  Host integer logic, a comparison mode for the cache step.
+struct fate_eap {
+    int num_layers, E;
+    std::vector<int64_t> freq;      // [num_layers - 1][E][E]
+};
+
+extern "C" fate_eap* fate_eap_create(int num_layers, int E) {
+    if (num_layers < 1 || E < 1 || E > 256) {
+        fate::set_error("fate_eap_create: bad argument");
+        return nullptr;
+    }
+    fate_eap* p = new fate_eap();
+    p->num_layers = num_layers;
+    p->E = E;
+    p->freq.assign((size_t)std::max(0, num_layers - 1) * E * E, 0);
+    return p;
+}
+
+extern "C" void fate_eap_destroy(fate_eap* p) { delete p; }
+
+static bool eap_ids_ok(const fate_eap* p, const int32_t* ids, int n) {
+    for (int i = 0; i < n; ++i)
+        if (ids[i] < 0 || ids[i] >= p->E) return false;
+    return true;
+}
+
+extern "C" fate_status fate_eap_update(fate_eap* p, int layer, const int32_t* ids_l, const int32_t* ids_next, int N,
+                                       int k) {
+    if (!p || layer < 0 || layer + 1 >= p->num_layers || N < 0 || k < 1 || (N && (!ids_l || !ids_next)) ||
+        !eap_ids_ok(p, ids_l, N * k) || !eap_ids_ok(p, ids_next, N * k)) {
+        fate::set_error("fate_eap_update: bad argument");
+        return FATE_EINVAL;
+    }
+    int64_t* f = p->freq.data() + (size_t)layer * p->E * p->E;
+    for (int t = 0; t < N; ++t)
+        for (int i = 0; i < k; ++i)
+            for (int j = 0; j < k; ++j) ++f[(size_t)ids_l[t * k + i] * p->E + ids_next[t * k + j]];
+    return FATE_OK;
+}
+
+extern "C" fate_status fate_eap_predict(const fate_eap* p, int layer, const int32_t* ids_l, int N, int k, int m,
+                                        int32_t* pred_pop) {
+    if (!p || layer < 0 || layer >= p->num_layers || N < 0 || k < 1 || m < 1 || !pred_pop || (N && !ids_l) ||
+        !eap_ids_ok(p, ids_l, N * k)) {
+        fate::set_error("fate_eap_predict: bad argument");
+        return FATE_EINVAL;
+    }
+    const int E = p->E;
+    for (int e = 0; e < E; ++e) pred_pop[e] = 0;
+    if (layer + 1 >= p->num_layers) return FATE_OK;
+    const int64_t* f = p->freq.data() + (size_t)layer * E * E;
+    std::vector<int64_t> score(E);
+    std::vector<int> order(E);
+    for (int t = 0; t < N; ++t) {
+        std::fill(score.begin(), score.end(), 0);
+        for (int i = 0; i < k; ++i) {
+            const int64_t* fe = f + (size_t)ids_l[t * k + i] * E;
+            for (int e = 0; e < E; ++e) score[e] += fe[e];
+        }
+        for (int e = 0; e < E; ++e) order[e] = e;
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return score[a] > score[b]; });
+        for (int i = 0; i < m && i < E; ++i)
+            if (score[order[i]] > 0) ++pred_pop[order[i]];
+    }
+    return FATE_OK;
+}

@@ -147,8 +147,11 @@ class OffloadedStack:
     the built-in HIP copy engine (side stream) around the per-layer calls."""
 
     def __init__(self, cfg: MoEShape, cache_total, n_max, staging_slots, device="cuda", layers=None,
-                 L_shallow=None, progress=None):
+                 L_shallow=None, progress=None, predictor="gate"):
+        """predictor: "gate" = the cross-layer gate prediction (the method), "eap" = the activation-path
+        baseline (co-activation statistics, fed through eap_observe), "none" = no prediction."""
         self.cfg, self.device = cfg, device
+        self.predictor = predictor
         self.nl = cfg.layers if layers is None else layers
         L, E = self.nl, cfg.E
         lib = B.lib()
@@ -215,6 +218,10 @@ class OffloadedStack:
         self.trace = []          # per step: (layer, compute_order, loads) for checks against the oracle
         self.keep_trace = False
         self._h_counts = torch.zeros(2, E, dtype=torch.int32).pin_memory()
+        self._h_ids = torch.zeros(4096 * cfg.k, dtype=torch.int32).pin_memory()
+        self.eap = lib.fate_eap_create(L, E) if predictor == "eap" else None
+        self._eap_prev = None          # (layer, host ids) of the previous layer call, for the statistics
+        self.eap_learning = False
         self._order = (C.c_int32 * E)()
         self._slots = (C.c_int32 * E)()
         self._loads = (B.fate_cache_load * 512)()
@@ -241,14 +248,28 @@ class OffloadedStack:
             B.fate_permute(buf.ids, cfg.E, buf.counts, buf.offsets, buf.perm, buf.inv_perm, buf.order)
         # the host needs the routing result to check residency (the one device -> host hop per layer)
         self._h_counts[0].copy_(buf.counts, non_blocking=True)
-        if nxt:
+        if nxt and self.predictor == "gate":
             self._h_counts[1].copy_(buf.pred_pop, non_blocking=True)
+        nk = buf.ids.numel()
+        if self.eap is not None:
+            self._h_ids[:nk].copy_(buf.ids.reshape(-1), non_blocking=True)
         torch.cuda.current_stream().synchronize()
+        if self.eap is not None:
+            N = nk // cfg.k
+            if self.eap_learning and self._eap_prev is not None and self._eap_prev[0] == l - 1 and \
+                    self._eap_prev[1].numel() == nk:
+                B._check(lib.fate_eap_update(self.eap, l - 1, C.c_void_p(self._eap_prev[1].data_ptr()),
+                                             C.c_void_p(self._h_ids.data_ptr()), N, cfg.k))
+            self._eap_prev = (l, self._h_ids[:nk].clone())
+            if nxt:
+                B._check(lib.fate_eap_predict(self.eap, l, C.c_void_p(self._h_ids.data_ptr()), N, cfg.k, cfg.m,
+                                              C.c_void_p(self._h_counts[1].data_ptr())))
+        have_pred = nxt and self.predictor in ("gate", "eap")
         B._check(lib.fate_hip_engine_begin_step(self.engine, C.c_void_p(self.done_event.cuda_event)
                                                 if self.have_done else None))
         st = self._st
         B._check(lib.fate_expert_cache_step_dense(self.cache, l, C.c_void_p(self._h_counts[0].data_ptr()),
-                                                  C.c_void_p(self._h_counts[1].data_ptr()) if nxt else None,
+                                                  C.c_void_p(self._h_counts[1].data_ptr()) if have_pred else None,
                                                   self._order, self._slots, C.byref(self._nact), self._loads, 512,
                                                   C.byref(st)))
         n = self._nact.value
@@ -273,3 +294,5 @@ class OffloadedStack:
         torch.cuda.synchronize()
         self.lib.fate_cache_destroy(self.cache)
         self.lib.fate_hip_engine_destroy(self.engine)
+        if self.eap is not None:
+            self.lib.fate_eap_destroy(self.eap)

@@ -226,3 +226,28 @@ def test_bench_refuses_more_than_one_gpu():
     assert p.returncode != 0
     assert "one GPU" in p.stderr + p.stdout
     assert not any(l.startswith("{") for l in p.stdout.splitlines())
+
+
+def test_eap_predictor_follows_the_oracle():
+    """The C++ activation-path predictor against the Python one on random calibration data."""
+    L = B.lib()
+    nl, E, k, m = 4, 16, 3, 5
+    rnd = random.Random(5)
+    ref = OC.EAPPredictor(nl, E)
+    h = L.fate_eap_create(nl, E)
+    assert h
+    arr = lambda rows: (C.c_int32 * (len(rows) * k))(*[e for r in rows for e in r])
+    pick = lambda n: [rnd.sample(range(E), k) for _ in range(n)]
+    for _ in range(20):
+        for l in range(nl - 1):
+            a, b = pick(7), pick(7)
+            ref.update(l, a, b)
+            assert L.fate_eap_update(h, l, arr(a), arr(b), 7, k) == 0
+    out = (C.c_int32 * E)()
+    for l in range(nl):
+        q = pick(9)
+        assert L.fate_eap_predict(h, l, arr(q), 9, k, m, out) == 0
+        assert list(out) == ref.predict(l, q, m), l
+    assert L.fate_eap_update(h, nl - 1, arr(pick(1)), arr(pick(1)), 1, k) == 1       # no block after the last
+    assert L.fate_eap_predict(h, 0, arr([[0, 1, E]]), 1, k, m, out) == 1             # id out of range
+    L.fate_eap_destroy(h)

@@ -127,3 +127,48 @@ def test_offloaded_mixtral_shape_against_both_oracles():
     experts cached in each deep layer (25 %), batch 1."""
     cfg = SHAPES["mixtral"]
     _offload_case(cfg, L=3, cache_total=8 + 2 + 2, L_shallow=1, n_max=1, N=1, steps=6, check_steps=2)
+
+
+@pytest.mark.parametrize("predictor", ["eap", "none"])
+def test_offloaded_stack_comparison_modes(predictor):
+    """The baseline modes of section 5.1 on the device: the activation-path predictor (statistics learned
+    on the first steps, then used) and no prediction at all feed the same cache step; decisions equal the
+    cache oracle fed by the Python predictor, outputs equal the all-resident path."""
+    cfg = dataclasses.replace(SHAPES["tiny"], name="tiny4", layers=4)
+    L, E, N, n_max, cache_total = cfg.layers, cfg.E, 3, 2, 10
+    staging = 2 * E + n_max
+    ref = MoEStack(cfg, DEV)
+    off = OffloadedStack(cfg, cache_total, n_max, staging, DEV, L_shallow=1, predictor=predictor)
+    off.keep_trace = True
+    sim = OC.CacheOracle(L, E, cache_total, 1, n_max, staging)
+    eap = OC.EAPPredictor(L, E)
+    b_ref, b_off = LayerBuffers(cfg, N, DEV), LayerBuffers(cfg, N, DEV)
+    prefetched = 0
+    for step in range(10):
+        learning = step < 5
+        off.eap_learning = learning
+        h = gen_hidden(cfg, N, step=step, device=DEV).float()
+        prev_ids = None
+        for l in range(L):
+            x = unit_rmsnorm_bf16(h)
+            y_ref = layer_forward(cfg, ref.layers[l], ref.layers[l + 1] if l + 1 < L else None, x, b_ref).clone()
+            ntr = len(off.trace)
+            y_off = off.layer(l, x, b_off)
+            torch.cuda.synchronize()
+            assert int(b_off.ffn_ws[:4].view(torch.int32)[0]) == 0
+            assert (y_off - y_ref).abs().max().item() / y_ref.abs().max().item() < 1e-5
+            ids = b_off.ids.cpu().numpy().tolist()
+            if predictor == "eap" and learning and prev_ids is not None:
+                eap.update(l - 1, prev_ids, ids)
+            prev_ids = ids
+            counts = b_off.counts.cpu().numpy()
+            aids = [e for e in range(E) if counts[e] > 0]
+            pop = eap.predict(l, ids, cfg.m) if predictor == "eap" else [0] * E
+            pids = [e for e in range(E) if pop[e] > 0] if l + 1 < L else []
+            r = sim.step(l, aids, [int(counts[e]) for e in aids], pids, [int(pop[e]) for e in pids])
+            tl, order, loads = off.trace[ntr]
+            assert tl == l and order == r.compute_order and loads == r.loads, (step, l)
+            prefetched += sum(1 for ld in loads if not ld[3])
+            h = chain_next_hidden(h, y_off)
+    assert (prefetched > 0) == (predictor == "eap")
+    off.close()

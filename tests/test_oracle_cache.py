@@ -179,3 +179,23 @@ def test_simulator_zero_capacity_and_zero_nmax():
     r = sim.step(0, [1], [1])
     assert r.miss == [1]                      # nothing was kept
     assert sorted(sim.free + sim.pending) == list(range(8))
+
+
+def test_eap_predictor_hand_case():
+    """Activation-path baseline (section 5.1): prediction from co-activation counts, worked by hand."""
+    p = C.EAPPredictor(3, 4)
+    # calibration: two tokens.  token A: block 0 {0,1} -> block 1 {2,3}; token B: block 0 {1,2} -> block 1 {3,0}
+    p.update(0, [[0, 1], [1, 2]], [[2, 3], [3, 0]])
+    assert p.freq[0][0] == [0, 0, 1, 1]
+    assert p.freq[0][1] == [1, 0, 1, 2]       # expert 1 was chosen by both tokens
+    assert p.freq[0][2] == [1, 0, 0, 1]
+    assert p.freq[0][3] == [0, 0, 0, 0]
+    # a token that chose {1, 2}: scores [2, 0, 1, 3] -> top-2 = experts 3, 0
+    assert p.predict(0, [[1, 2]], 2) == [1, 0, 0, 1]
+    # a token that chose {0}: scores [0, 0, 1, 1] -> tie between 2 and 3 goes to the lower id with m = 1
+    assert p.predict(0, [[0]], 1) == [0, 0, 1, 0]
+    # zero scores are never predicted; popularity adds up over tokens
+    assert p.predict(0, [[3]], 2) == [0, 0, 0, 0]
+    assert p.predict(0, [[1, 2], [0], [0]], 2) == [1, 0, 2, 3]
+    # block 1 has no statistics yet, the last block predicts nothing
+    assert p.predict(1, [[0, 1]], 2) == [0, 0, 0, 0] and p.predict(2, [[0, 1]], 2) == [0, 0, 0, 0]
