@@ -278,9 +278,10 @@ fate_status fate_moe_layer_decode_noalloc(void* stream, const fate_ffn_desc* d, 
  * ---------------------------------------------------------------------- */
 typedef struct fate_cache fate_cache;
 
-/* copy callback: bring expert `e` of `layer` into `slot`.  demand != 0 for a
- * load the current layer waits on.  Return 0 on success. */
-typedef int (*fate_copy_fn)(void* user, int layer, int expert, int slot, int demand);
+/* copy callback: bring the `bits`-wide copy of expert `e` of `layer` into
+ * `slot`.  demand != 0 for a load the current layer waits on.  Return 0 on
+ * success. */
+typedef int (*fate_copy_fn)(void* user, int layer, int expert, int slot, int demand, int bits);
 
 /* closed forms of section 4.3 / 4.4 */
 int64_t fate_cache_total_from_budget(int64_t memory_budget, int64_t others, int64_t expert_bytes);
@@ -296,6 +297,15 @@ int32_t fate_cache_total_slots(const fate_cache*);
  * ratio differs between prefill and decode, so a caller re-calibrates between the phases.
  * n_max < 0 -> FATE_EINVAL. */
 fate_status fate_cache_set_n_max(fate_cache*, int n_max);
+/* Popularity-aware hybrid width of the transfers (section 4.5, "Quantization for I/O": in prefill the
+ * least popular experts are moved at a lower width; the prefetch list carries the width, section 4.1
+ * step 2).  Of the experts predicted for the next layer (popularity > 0), ranked by predicted
+ * popularity, the last floor(percent * n / 100) are transferred as `low_bits` copies if they need a
+ * transfer at all; everything else, and every demand load, moves at `bits`.  A low-width copy serves
+ * its layer's computation and is then dropped: it never enters the layer's cache, which holds
+ * `bits` copies only.  percent = 0 (the default) switches the rule off; a caller sets it for the
+ * prefill pass and clears it for decoding, where every selected expert counts the same. */
+fate_status fate_cache_set_low_precision(fate_cache*, int percent, int bits, int low_bits);
 /* slot of (layer, expert) or -1; resident: 2 = in the layer's cache, 1 = staged, 0 = absent */
 int32_t fate_cache_slot_of(const fate_cache*, int layer, int expert);
 int32_t fate_cache_resident(const fate_cache*, int layer, int expert);
@@ -307,7 +317,7 @@ typedef struct {
     int32_t n_loads;                               /* entries written to loads[] */
 } fate_cache_stats;
 
-typedef struct { int32_t layer, expert, slot, demand; } fate_cache_load;
+typedef struct { int32_t layer, expert, slot, demand, bits; } fate_cache_load;
 
 /* One cache step for `layer` (host arrays):
  *   actual_ids/actual_counts [n_actual]: unique experts the true gate chose,
@@ -384,7 +394,13 @@ fate_hip_engine* fate_hip_engine_create(int num_layers, int E, int total_slots, 
                                         fate_qexpert* table_dev, void* copy_stream, void* compute_stream);
 void fate_hip_engine_destroy(fate_hip_engine*);
 /* the fate_copy_fn to pass to fate_cache_create together with the engine as `user` */
-int fate_hip_engine_copy(void* engine, int layer, int expert, int slot, int demand);
+int fate_hip_engine_copy(void* engine, int layer, int expert, int slot, int demand, int bits);
+/* Second host pool with the low-width copies (section 4.5: both widths of every expert are kept in
+ * host memory): num_layers*E experts of layout->slot_bytes each, pinned, expert (l,e) at
+ * ((l*E)+e)*slot_bytes.  A copy whose `bits` equals layout->bits comes from this pool and writes a
+ * table entry of that width; slot_bytes must not exceed the main layout's. */
+fate_status fate_hip_engine_set_low_pool(fate_hip_engine*, const fate_slot_layout* layout,
+                                         const void* host_pool_low_pinned);
 /* call before each fate_expert_cache_step: orders later copies after `compute_done_event` (may be NULL) */
 fate_status fate_hip_engine_begin_step(fate_hip_engine*, void* compute_done_event);
 /* call after the step: compute_stream waits for the copies of `layer`'s activated experts */

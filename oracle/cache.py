@@ -134,6 +134,7 @@ class StepResult:
         self.miss = []           # experts loaded on demand, in load order
         self.compute_order = []  # cached, then prefetched, then misses in load order
         self.loads = []          # (layer, expert, slot, is_demand) in issue order
+        self.load_bits = []      # code width of each load (same order): the cache's width, or the low one
         self.slot_of = {}        # expert -> slot for every activated expert
         self.wasted = []         # staged-but-unused experts evicted at step start
         self.evicted = []        # experts evicted by ARC in this step
@@ -145,10 +146,17 @@ class StepResult:
 class CacheOracle:
     """Reference simulator of the per-layer cache step."""
 
-    def __init__(self, num_layers, E, cache_total, L_shallow, n_max, staging_slots):
+    def __init__(self, num_layers, E, cache_total, L_shallow, n_max, staging_slots, low_percent=0, bits=4,
+                 low_bits=2):
+        """low_percent: popularity-aware hybrid width of section 4.5 - of the experts predicted for
+        the next layer, ranked by predicted popularity, the least popular low_percent % (floored) are
+        transferred as low_bits copies when they need a transfer at all.  Such a copy serves the
+        layer's computation and is then dropped: the cache holds `bits` copies only."""
         self.num_layers = num_layers
         self.E = E
         self.n_max = n_max
+        self.low_percent, self.bits, self.low_bits = low_percent, bits, low_bits
+        self.staged_low = [set() for _ in range(num_layers)]
         self.caps = layer_capacities(num_layers, E, cache_total, L_shallow)
         self.total_slots = sum(self.caps) + staging_slots
         self.full = [c >= E for c in self.caps]
@@ -196,6 +204,7 @@ class CacheOracle:
         for e in list(self.staged[l]):
             if e not in cnt:
                 self.staged[l].remove(e)
+                self.staged_low[l].discard(e)
                 self._release(l, e)
                 r.wasted.append(e)
         # (i) residency check, demand loads
@@ -215,6 +224,7 @@ class CacheOracle:
                 r.miss.append(a)
                 r.pair_misses += cnt[a]
                 r.loads.append((l, a, s, True))
+                r.load_bits.append(self.bits)
         # (ii) compute order
         r.compute_order = r.hit_cache + r.hit_prefetch + r.miss
         for a in A:
@@ -225,8 +235,10 @@ class CacheOracle:
         if not self.full[l]:
             arc = self.arc[l]
             for a in r.compute_order:
-                if arc is None:
+                if arc is None or a in self.staged_low[l]:
+                    # no cache in this layer, or a low-width copy: used once, then dropped
                     self.staged[l].remove(a)
+                    self.staged_low[l].discard(a)
                     self._release(l, a)
                     r.evicted.append(a)
                     continue
@@ -240,6 +252,9 @@ class CacheOracle:
         t = l + 1
         if t < self.num_layers and len(pred_ids) and self.n_max > 0:
             porder = sorted(range(len(pred_ids)), key=lambda i: (-int(pred_pop[i]), i))
+            npos = sum(1 for i in porder if int(pred_pop[i]) > 0)
+            nlow = npos * self.low_percent // 100
+            rank = 0                      # position among the predicted experts with popularity > 0
             issued = 0
             for i in porder:
                 if issued >= self.n_max:
@@ -247,6 +262,8 @@ class CacheOracle:
                 e = int(pred_ids[i])
                 if int(pred_pop[i]) <= 0:
                     continue
+                low = rank >= npos - nlow
+                rank += 1
                 if self.resident(t, e) or e in self.staged[t]:
                     continue
                 s = self._alloc()
@@ -255,7 +272,10 @@ class CacheOracle:
                     continue
                 self.slot[t][e] = s
                 self.staged[t].append(e)
+                if low:
+                    self.staged_low[t].add(e)
                 r.loads.append((t, e, s, False))
+                r.load_bits.append(self.low_bits if low else self.bits)
                 issued += 1
         return r
 

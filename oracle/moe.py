@@ -143,10 +143,18 @@ def permute(ids, E):
 
 def unpack_codes(codes_u8, bits):
     """Canonical stored codes -> signed integer codes [rows, K] (int32).
-    int8: two's complement bytes.  int4: nibble u = q + 8, low nibble first."""
+    int8: two's complement bytes.  int4: nibble u = q + 8, low nibble first.
+    int2: field u in 0..3, four per byte, column 4b+i in bits 2i..2i+1 of byte b; the signed code
+    is the odd integer q = 2u - 3 (levels -3, -1, 1, 3 times the group's scale)."""
     c = np.asarray(codes_u8, dtype=np.uint8)
     if bits == 8:
         return c.view(np.int8).astype(np.int32)
+    if bits == 2:
+        rows, quarter = c.shape
+        q = np.empty((rows, quarter * 4), dtype=np.int32)
+        for i in range(4):
+            q[:, i::4] = 2 * ((c >> (2 * i)) & 0x3).astype(np.int32) - 3
+        return q
     assert bits == 4
     rows, half = c.shape
     q = np.empty((rows, half * 2), dtype=np.int32)
@@ -156,7 +164,8 @@ def unpack_codes(codes_u8, bits):
 
 
 def dequant(codes_u8, scales_f16, bits, group):
-    """w[r, c] = q[r, c] * s[r, c // group] in fp64 (symmetric: zero-point 0)."""
+    """w[r, c] = q[r, c] * s[r, c // group] in fp64 (symmetric: zero-point 0; for the 2-bit
+    format q runs over the odd integers -3 .. 3)."""
     q = unpack_codes(codes_u8, bits).astype(np.float64)
     s = np.asarray(scales_f16, dtype=np.float16).astype(np.float64)
     rows, K = q.shape
@@ -167,9 +176,22 @@ def dequant(codes_u8, scales_f16, bits, group):
 def quantize_sym(w, bits, group):
     """Reference symmetric group quantiser: s = fp16(max|w|/qmax) per group
     (1 for an all-zero group), q = round-half-even(w/s) clamped to +-qmax with
-    the rounded s.  Returns (signed codes int32 [rows,K], scales fp16)."""
+    the rounded s.  Returns (signed codes int32 [rows,K], scales fp16).
+
+    bits = 2 (the low-precision copy of section 4.5): a symmetric code with a zero level would
+    use three of the four codes, so the four levels are the odd multiples -3, -1, 1, 3 of the
+    scale s = fp16(max|w|/3) (s = 0 for an all-zero group, which then dequantises to zero);
+    q is the nearest level, computed with the rounded s, ties to the field value that is even."""
     w = np.asarray(w, dtype=np.float64)
     rows, K = w.shape
+    if bits == 2:
+        wg = w.reshape(rows, K // group, group)
+        s = (np.abs(wg).max(axis=-1) / 3).astype(np.float16)
+        sd = s.astype(np.float64)[..., None]
+        with np.errstate(divide="ignore", invalid="ignore"):
+            u = np.where(sd > 0, np.rint((wg / sd + 3) / 2), 0)
+        u = np.clip(u, 0, 3).astype(np.int32)
+        return (2 * u - 3).reshape(rows, K), s
     qmax = 127 if bits == 8 else 7
     wg = w.reshape(rows, K // group, group)
     s = (np.abs(wg).max(axis=-1) / qmax).astype(np.float16)
@@ -183,6 +205,9 @@ def pack_codes(q, bits):
     q = np.asarray(q, dtype=np.int32)
     if bits == 8:
         return q.astype(np.int8).view(np.uint8)
+    if bits == 2:
+        u = ((q + 3) // 2).astype(np.uint8)
+        return (u[:, 0::4] | (u[:, 1::4] << 2) | (u[:, 2::4] << 4) | (u[:, 3::4] << 6)).astype(np.uint8)
     u = (q + 8).astype(np.uint8)
     return (u[:, 0::2] | (u[:, 1::2] << 4)).astype(np.uint8)
 

@@ -22,7 +22,8 @@ EXPORTS = [
     "fate_route_fused_workspace", "fate_route_fused", "fate_pack_weight", "fate_pack_scales", "fate_moe_ffn_q_workspace",
     "fate_moe_ffn_q", "fate_profile_ffn_mfma_phase", "fate_moe_layer_decode_workspace", "fate_moe_layer_decode",
     "fate_moe_layer_decode_noalloc", "fate_cache_total_from_budget", "fate_n_max_from_times", "fate_cache_layer_capacities",
-    "fate_cache_create", "fate_cache_destroy", "fate_cache_total_slots", "fate_cache_set_n_max", "fate_cache_slot_of",
+    "fate_cache_create", "fate_cache_destroy", "fate_cache_total_slots", "fate_cache_set_n_max",
+    "fate_cache_set_low_precision", "fate_hip_engine_set_low_pool", "fate_cache_slot_of",
     "fate_cache_resident", "fate_expert_cache_step", "fate_expert_cache_step_dense",
     "fate_expert_cache_step_layers", "fate_hip_engine_create", "fate_hip_engine_destroy",
     "fate_hip_engine_copy", "fate_hip_engine_begin_step", "fate_hip_engine_wait_ready",
@@ -56,7 +57,7 @@ class fate_cache_stats(C.Structure):
 
 
 class fate_cache_load(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("layer", "expert", "slot", "demand")]
+    _fields_ = [(n, C.c_int32) for n in ("layer", "expert", "slot", "demand", "bits")]
 
 
 class fate_slot_layout(C.Structure):
@@ -65,7 +66,7 @@ class fate_slot_layout(C.Structure):
                 ("bits", C.c_int32), ("group", C.c_int32), ("I", C.c_int32)]
 
 
-COPY_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int)
+COPY_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int)
 
 _lib = None
 
@@ -87,6 +88,8 @@ def lib():
         L.fate_cache_destroy.restype = None
         L.fate_cache_total_slots.argtypes = [C.c_void_p]
         L.fate_cache_set_n_max.argtypes = [C.c_void_p, C.c_int]
+        L.fate_cache_set_low_precision.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int]
+        L.fate_hip_engine_set_low_pool.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.fate_cache_slot_of.argtypes = [C.c_void_p, C.c_int, C.c_int]
         L.fate_cache_resident.argtypes = [C.c_void_p, C.c_int, C.c_int]
         L.fate_cache_total_from_budget.restype = C.c_int64

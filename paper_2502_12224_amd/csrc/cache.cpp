@@ -134,6 +134,8 @@ struct fate_cache {
     std::vector<Arc> arc;                    // used when 0 < cap < E
     std::vector<std::vector<int>> slot;      // [layer][expert] -> slot or -1
     std::vector<std::vector<int>> staged;    // [layer] experts staged, in arrival order
+    std::vector<std::vector<uint8_t>> staged_low;   // [layer][expert] 1 = the staged copy is the low-width one
+    int bits = 4, low_bits = 2, low_percent = 0;
     std::set<int> free_slots;
     std::vector<int> pending;                // freed in the current step
     fate_copy_fn copy;
@@ -198,6 +200,7 @@ extern "C" fate_cache* fate_cache_create(int num_layers, int E, int cache_total,
     c->arc.resize(num_layers);
     c->slot.assign(num_layers, std::vector<int>(E, -1));
     c->staged.resize(num_layers);
+    c->staged_low.assign(num_layers, std::vector<uint8_t>(E, 0));
     int next = 0;
     for (int l = 0; l < num_layers; ++l) {
         c->full[l] = c->caps[l] >= E;
@@ -218,6 +221,17 @@ extern "C" fate_status fate_cache_set_n_max(fate_cache* c, int n_max) {
         return FATE_EINVAL;
     }
     c->n_max = n_max;
+    return FATE_OK;
+}
+extern "C" fate_status fate_cache_set_low_precision(fate_cache* c, int percent, int bits, int low_bits) {
+    if (!c || percent < 0 || percent > 100 || bits < 1 || low_bits < 1) {
+        fate::set_error("fate_cache_set_low_precision: cache %p, percent %d, bits %d / %d", (void*)c, percent, bits,
+                        low_bits);
+        return FATE_EINVAL;
+    }
+    c->low_percent = percent;
+    c->bits = bits;
+    c->low_bits = low_bits;
     return FATE_OK;
 }
 extern "C" int32_t fate_cache_slot_of(const fate_cache* c, int layer, int expert) {
@@ -258,8 +272,8 @@ extern "C" fate_status fate_expert_cache_step(fate_cache* c, int layer, const in
             return FATE_EINVAL;
         }
     fate_cache_stats st{};
-    auto record = [&](int ly, int e, int s, int demand) {
-        if (st.n_loads < max_loads) loads[st.n_loads] = fate_cache_load{ly, e, s, demand};
+    auto record = [&](int ly, int e, int s, int demand, int bits) {
+        if (st.n_loads < max_loads) loads[st.n_loads] = fate_cache_load{ly, e, s, demand, bits};
         ++st.n_loads;
     };
     // slots released during the previous step are reusable from here on
@@ -277,6 +291,7 @@ extern "C" fate_status fate_expert_cache_step(fate_cache* c, int layer, const in
         for (int e : c->staged[l]) {
             if (cnt[e] == 0) {
                 c->release(l, e);
+                c->staged_low[l][e] = 0;
                 ++st.n_wasted;
             } else {
                 keep.push_back(e);
@@ -301,7 +316,7 @@ extern "C" fate_status fate_expert_cache_step(fate_cache* c, int layer, const in
                 fate::set_error("layer %d: no free slot for the demand load of expert %d", l, e);
                 return FATE_ECAPACITY;
             }
-            if (c->copy && c->copy(c->user, l, e, s, 1) != 0) {
+            if (c->copy && c->copy(c->user, l, e, s, 1, c->bits) != 0) {
                 c->free_slots.insert(s);
                 *stats = st;
                 fate::set_error("layer %d: copy of expert %d into slot %d failed", l, e, s);
@@ -311,7 +326,7 @@ extern "C" fate_status fate_expert_cache_step(fate_cache* c, int layer, const in
             c->staged[l].push_back(e);
             miss.push_back(e);
             st.pair_misses += cnt[e];
-            record(l, e, s, 1);
+            record(l, e, s, 1, c->bits);
         }
     }
     st.n_hit_cache = (int)hit_cache.size();
@@ -329,8 +344,10 @@ extern "C" fate_status fate_expert_cache_step(fate_cache* c, int layer, const in
     if (!c->full[l]) {
         for (int i = 0; i < n_actual; ++i) {
             const int e = compute_order[i];
-            if (c->caps[l] == 0) {
+            if (c->caps[l] == 0 || c->staged_low[l][e]) {
+                // no cache in this layer, or a low-width copy: used once, then dropped
                 c->unstage(l, e);
+                c->staged_low[l][e] = 0;
                 c->release(l, e);
                 ++st.n_evicted;
                 continue;
@@ -349,18 +366,26 @@ extern "C" fate_status fate_expert_cache_step(fate_cache* c, int layer, const in
         std::vector<int> po(n_pred);
         for (int i = 0; i < n_pred; ++i) po[i] = i;
         std::stable_sort(po.begin(), po.end(), [&](int a, int b) { return pred_pop[a] > pred_pop[b]; });
-        int issued = 0;
+        // popularity-aware hybrid width (section 4.5): the least popular low_percent % of the predicted
+        // experts travel as low-width copies when they need a transfer
+        int npos = 0;
+        for (int i : po) npos += pred_pop[i] > 0;
+        const int nlow = (int)((long long)npos * c->low_percent / 100);
+        int rank = 0, issued = 0;
         for (int i : po) {
             if (issued >= c->n_max) break;
             const int e = pred_ids[i];
             if (pred_pop[i] <= 0) continue;
+            const bool low = rank >= npos - nlow;
+            ++rank;
             if (c->resident(t, e) || c->is_staged(t, e)) continue;
             const int s = c->alloc();
             if (s < 0) {
                 ++st.n_prefetch_dropped;
                 continue;
             }
-            if (c->copy && c->copy(c->user, t, e, s, 0) != 0) {
+            const int bits = low ? c->low_bits : c->bits;
+            if (c->copy && c->copy(c->user, t, e, s, 0, bits) != 0) {
                 c->free_slots.insert(s);
                 *stats = st;
                 fate::set_error("layer %d: prefetch copy of expert %d into slot %d failed", t, e, s);
@@ -368,7 +393,8 @@ extern "C" fate_status fate_expert_cache_step(fate_cache* c, int layer, const in
             }
             c->slot[t][e] = s;
             c->staged[t].push_back(e);
-            record(t, e, s, 0);
+            c->staged_low[t][e] = low ? 1 : 0;
+            record(t, e, s, 0, bits);
             ++issued;
         }
         st.n_prefetch_issued = issued;

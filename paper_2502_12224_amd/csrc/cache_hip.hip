@@ -19,8 +19,10 @@
 struct fate_hip_engine {
     int num_layers, E, total_slots;
     fate_slot_layout lay;
+    fate_slot_layout lay_low;      // layout of the low-width copies (slot_bytes 0: none)
     char* pool;
     const char* host;
+    const char* host_low;
     fate_qexpert* table;
     hipStream_t copy_stream, compute_stream;
     hipStream_t copy2;             // the engine's own second copy stream
@@ -36,12 +38,12 @@ __global__ void set_entry_kernel(fate_qexpert* dst, fate_qexpert v) {
     if (threadIdx.x == 0 && blockIdx.x == 0) *dst = v;
 }
 
-static fate_qexpert entry_for(const fate_hip_engine* g, int slot) {
-    const char* b = g->pool + (size_t)slot * g->lay.slot_bytes;
+static fate_qexpert entry_for(const fate_hip_engine* g, int slot, const fate_slot_layout& lay) {
+    const char* b = g->pool + (size_t)slot * g->lay.slot_bytes;      // slots are spaced by the main layout
     fate_qexpert q;
-    q.w1 = b + g->lay.off_w1; q.w3 = b + g->lay.off_w3; q.w2 = b + g->lay.off_w2;
-    q.s1 = b + g->lay.off_s1; q.s3 = b + g->lay.off_s3; q.s2 = b + g->lay.off_s2;
-    q.bits = g->lay.bits; q.group = g->lay.group; q.I = g->lay.I; q.reserved = 0;
+    q.w1 = b + lay.off_w1; q.w3 = b + lay.off_w3; q.w2 = b + lay.off_w2;
+    q.s1 = b + lay.off_s1; q.s3 = b + lay.off_s3; q.s2 = b + lay.off_s2;
+    q.bits = lay.bits; q.group = lay.group; q.I = lay.I; q.reserved = 0;
     return q;
 }
 
@@ -74,6 +76,8 @@ extern "C" fate_hip_engine* fate_hip_engine_create(int num_layers, int E, int to
     g->compute_stream = static_cast<hipStream_t>(compute_stream);
     g->bytes = 0;
     g->flip = 0;
+    g->lay_low = fate_slot_layout{};
+    g->host_low = nullptr;
     if (hipStreamCreateWithFlags(&g->copy2, hipStreamNonBlocking) != hipSuccess) {
         delete g;
         set_error("hipStreamCreateWithFlags failed");
@@ -101,26 +105,44 @@ extern "C" void fate_hip_engine_destroy(fate_hip_engine* g) {
     delete g;
 }
 
-extern "C" int fate_hip_engine_copy(void* engine, int layer, int expert, int slot, int demand) {
+extern "C" fate_status fate_hip_engine_set_low_pool(fate_hip_engine* g, const fate_slot_layout* layout,
+                                                    const void* host_pool_low_pinned) {
+    if (!g || !layout || !host_pool_low_pinned || layout->slot_bytes == 0 || (layout->slot_bytes & 15) ||
+        layout->slot_bytes > g->lay.slot_bytes || layout->bits == g->lay.bits)
+        FATE_FAIL(FATE_EINVAL, "fate_hip_engine_set_low_pool: bad argument");
+    const size_t offs[6] = {layout->off_w1, layout->off_w3, layout->off_w2,
+                            layout->off_s1, layout->off_s3, layout->off_s2};
+    for (size_t o : offs)
+        if ((o & 15) || o >= layout->slot_bytes)
+            FATE_FAIL(FATE_EINVAL, "array offsets must be 16-byte aligned and inside the slot");
+    g->lay_low = *layout;
+    g->host_low = static_cast<const char*>(host_pool_low_pinned);
+    return FATE_OK;
+}
+
+extern "C" int fate_hip_engine_copy(void* engine, int layer, int expert, int slot, int demand, int bits) {
     (void)demand;
     fate_hip_engine* g = static_cast<fate_hip_engine*>(engine);
     if (!g || layer < 0 || layer >= g->num_layers || expert < 0 || expert >= g->E || slot < 0 ||
         slot >= g->total_slots)
         return 1;
-    const size_t nb = g->lay.slot_bytes;
+    const bool low = g->host_low != nullptr && bits == g->lay_low.bits;
+    if (!low && bits != g->lay.bits) return 6;       // no pool holds copies of that width
+    const fate_slot_layout& lay = low ? g->lay_low : g->lay;
+    const char* src = (low ? g->host_low : g->host) + ((size_t)layer * g->E + expert) * lay.slot_bytes;
+    const size_t nb = lay.slot_bytes;
     hipStream_t cs = g->flip ? g->copy2 : g->copy_stream;
     g->flip ^= 1;
     // An earlier copy into this slot that nobody waited for (a prefetch that went unused) may
     // still be in flight on the other stream: order this copy after it.
     if (g->ev_live[slot] && hipStreamWaitEvent(cs, g->ev[slot], 0) != hipSuccess) return 5;
-    if (hipMemcpyAsync(g->pool + (size_t)slot * nb, g->host + ((size_t)layer * g->E + expert) * nb, nb,
-                       hipMemcpyHostToDevice, cs) != hipSuccess)
+    if (hipMemcpyAsync(g->pool + (size_t)slot * g->lay.slot_bytes, src, nb, hipMemcpyHostToDevice, cs) != hipSuccess)
         return 2;
     if (hipEventRecord(g->ev[slot], cs) != hipSuccess) return 3;
     g->ev_live[slot] = 1;
     g->bytes += nb;
     set_entry_kernel<<<1, 64, 0, g->compute_stream>>>(g->table + (size_t)layer * g->E + expert,
-                                                     entry_for(g, slot));
+                                                     entry_for(g, slot, lay));
     return hipGetLastError() == hipSuccess ? 0 : 4;
 }
 
@@ -153,7 +175,7 @@ extern "C" fate_status fate_hip_engine_preload(fate_hip_engine* g, int layer, in
     const size_t nb = g->lay.slot_bytes;
     FATE_HIP(hipMemcpy(g->pool + (size_t)slot * nb, g->host + ((size_t)layer * g->E + expert) * nb, nb,
                        hipMemcpyHostToDevice));
-    fate_qexpert q = entry_for(g, slot);
+    fate_qexpert q = entry_for(g, slot, g->lay);
     FATE_HIP(hipMemcpy(g->table + (size_t)layer * g->E + expert, &q, sizeof(q), hipMemcpyHostToDevice));
     return FATE_OK;
 }

@@ -98,12 +98,14 @@ class _Cache:
 
     def __init__(self, nl, E, total, Ls, n_max, staging, fail_at=None):
         self.copies = []
+        self.copy_bits = []
         self.fail_at = fail_at
 
-        def cb(user, layer, expert, slot, demand):
+        def cb(user, layer, expert, slot, demand, bits):
             if self.fail_at is not None and len(self.copies) == self.fail_at:
                 return 1
             self.copies.append((layer, expert, slot, bool(demand)))
+            self.copy_bits.append(bits)
             return 0
         self._cb = B.COPY_FN(cb)
         self.h = B.lib().fate_cache_create(nl, E, total, Ls, n_max, staging, self._cb, None)
@@ -122,6 +124,7 @@ class _Cache:
         rc = B.lib().fate_expert_cache_step(self.h, layer, a, c, n, pi, pp, npred, order, slots, loads, 512,
                                             C.byref(st))
         ld = [(loads[i].layer, loads[i].expert, loads[i].slot, bool(loads[i].demand)) for i in range(min(st.n_loads, 512))]
+        self.last_bits = [loads[i].bits for i in range(min(st.n_loads, 512))]
         return rc, list(order)[:n], list(slots)[:n], ld, st
 
     def close(self):
@@ -251,3 +254,34 @@ def test_eap_predictor_follows_the_oracle():
     assert L.fate_eap_update(h, nl - 1, arr(pick(1)), arr(pick(1)), 1, k) == 1       # no block after the last
     assert L.fate_eap_predict(h, 0, arr([[0, 1, E]]), 1, k, m, out) == 1             # id out of range
     L.fate_eap_destroy(h)
+
+
+def test_hybrid_width_of_the_prefetch_list_follows_the_oracle():
+    """Popularity-aware hybrid width (section 4.5): the C++ cache against the oracle on random traces with
+    the least popular quarter of the predicted experts moved as 2-bit copies, then with the rule off."""
+    nl, E = 4, 16
+    rnd = random.Random(17)
+    for percent in (25, 50, 0):
+        ref = OC.CacheOracle(nl, E, 14, 1, 6, 2 * E, low_percent=percent)
+        cc = _Cache(nl, E, 14, 1, 6, 2 * E)
+        assert B.lib().fate_cache_set_low_precision(cc.h, percent, 4, 2) == 0
+        seen_low = 0
+        for step in range(40):
+            for l in range(nl):
+                ids = sorted(rnd.sample(range(E), rnd.randint(1, 5)))
+                counts = [rnd.randint(1, 9) for _ in ids]
+                pids = sorted(rnd.sample(range(E), rnd.randint(0, 10)))
+                ppop = [rnd.randint(0, 6) for _ in pids]
+                r = ref.step(l, ids, counts, pids, ppop)
+                rc, order, slots, loads, st = cc.step(l, ids, counts, pids, ppop)
+                assert rc == 0 and order == r.compute_order and loads == r.loads
+                assert cc.last_bits == r.load_bits
+                assert st.n_evicted == len(r.evicted) and st.n_wasted == len(r.wasted)
+                seen_low += sum(1 for b in r.load_bits if b == 2)
+                for e in range(E):
+                    want = 2 if ref.resident(l, e) else (1 if e in ref.staged[l] else 0)
+                    assert B.lib().fate_cache_resident(cc.h, l, e) == want
+        assert (seen_low > 0) == (percent > 0)
+        assert cc.copy_bits.count(2) == seen_low
+        cc.close()
+    assert B.lib().fate_cache_set_low_precision(None, 25, 4, 2) == 1

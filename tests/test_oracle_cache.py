@@ -199,3 +199,30 @@ def test_eap_predictor_hand_case():
     assert p.predict(0, [[1, 2], [0], [0]], 2) == [1, 0, 2, 3]
     # block 1 has no statistics yet, the last block predicts nothing
     assert p.predict(1, [[0, 1]], 2) == [0, 0, 0, 0] and p.predict(2, [[0, 1]], 2) == [0, 0, 0, 0]
+
+
+def test_hybrid_width_hand_trace():
+    """Section 4.5: of the experts predicted for the next layer, the least popular quarter moves as a
+    low-width copy; such a copy is used by its layer and dropped, it never enters the 4-bit cache."""
+    c = C.CacheOracle(num_layers=2, E=8, cache_total=2, L_shallow=0, n_max=8, staging_slots=12, low_percent=25)
+    assert c.caps == [1, 1]                           # expert 0 preloaded in each layer
+    r = c.step(0, [0], [4], pred_ids=list(range(8)), pred_pop=[8, 7, 6, 5, 4, 3, 2, 1])
+    # 8 predicted experts -> the 2 least popular (6, 7) are low-width; expert 0 is resident in layer 1
+    assert [(e, d) for (_, e, _, d) in r.loads] == [(e, False) for e in range(1, 8)]
+    assert r.load_bits == [4, 4, 4, 4, 4, 2, 2]
+    assert c.staged_low[1] == {6, 7}
+    # layer 1 activates 0 (cached), 2 (staged at 4 bits) and 6 (staged at 2 bits)
+    r = c.step(1, [0, 2, 6], [3, 2, 1])
+    assert r.hit_cache == [0] and r.hit_prefetch == [2, 6] and r.miss == []
+    assert sorted(r.wasted) == [1, 3, 4, 5, 7]
+    # 2 went through ARC (capacity 1: it replaces 0), 6 was dropped without touching ARC
+    assert c.resident(1, 2) and not c.resident(1, 6) and not c.resident(1, 0)
+    assert 6 in r.evicted and 6 not in c.staged[1] and c.staged_low[1] == set()
+    # popularity zero does not count as predicted: 3 positive -> floor(0.75) = 0 low-width copies
+    c2 = C.CacheOracle(2, 8, 0, 0, 8, 12, low_percent=25)
+    r = c2.step(0, [1], [1], pred_ids=[0, 1, 2, 3], pred_pop=[5, 0, 3, 1])
+    assert r.load_bits == [4, 4, 4, 4]               # the demand load of expert 1, then 0, 2, 3
+    # demand loads always move at the cache's width
+    c3 = C.CacheOracle(2, 8, 0, 0, 8, 12, low_percent=100)
+    r = c3.step(0, [1], [1], pred_ids=[2, 3], pred_pop=[2, 1])
+    assert r.load_bits == [4, 2, 2]

@@ -185,3 +185,51 @@ def test_grouped_ffn_repeated_expert_and_empty_cases():
     assert np.allclose(O.moe_ffn_grouped(x, ids, w, experts), O.moe_ffn(x, ids, w, experts), rtol=1e-12, atol=1e-16)
     empty = O.moe_ffn_grouped(x[:0], ids[:0], w[:0], experts)
     assert empty.shape == (0, cfg.H)
+
+
+def test_int2_format_hand_worked_group():
+    """The low-precision copy of section 4.5, one row, two groups of 4.  Group 0: max|w| = 0.6 ->
+    s = fp16(0.2); levels -0.6, -0.2, 0.2, 0.6 (times the rounded s).  Group 1 is all zero -> s = 0."""
+    w = np.array([[0.6, -0.35, 0.05, -0.6, 0.0, 0.0, 0.0, 0.0]])
+    q, s = O.quantize_sym(w, 2, 4)
+    s0 = np.float16(0.6 / 3)
+    assert s.dtype == np.float16 and s[0, 0] == s0 and s[0, 1] == np.float16(0.0)
+    # 0.6 -> +3 ; -0.35 / 0.2 = -1.75 -> nearest odd level -1 (field (-1.75 + 3) / 2 = 0.625 -> 1);
+    # 0.05 -> +1 ; -0.6 -> -3 ; the zero group takes field 0 = level -3 times a zero scale
+    assert q.tolist() == [[3, -1, 1, -3, -3, -3, -3, -3]]
+    packed = O.pack_codes(q, 2)
+    # fields u = (q + 3) / 2 = 3, 1, 2, 0 -> byte 3 | 1 << 2 | 2 << 4 | 0 << 6 = 0x27 ; second byte 0
+    assert packed.tolist() == [[0x27, 0x00]]
+    assert np.array_equal(O.unpack_codes(packed, 2), q)
+    d = O.dequant(packed, s, 2, 4)
+    assert d[0, 0] == 3 * float(s0) and d[0, 1] == -float(s0) and d[0, 3] == -3 * float(s0)
+    assert (d[0, 4:] == 0).all()
+
+
+def test_int2_round_trip_and_error_bound():
+    rng = np.random.default_rng(2)
+    group = 128
+    w = rng.normal(size=(40, 4 * group)) * 0.02
+    w[5, group:2 * group] = 0.0
+    q, s = O.quantize_sym(w, 2, group)
+    assert set(np.unique(q).tolist()) <= {-3, -1, 1, 3}
+    packed = O.pack_codes(q, 2)
+    assert packed.shape == (40, 4 * group // 4) and np.array_equal(O.unpack_codes(packed, 2), q)
+    d = O.dequant(packed, s, 2, group)
+    sfull = np.repeat(s.astype(np.float64), group, axis=1)
+    # nearest of the levels -3s .. 3s: off by at most s, plus what rounding s to fp16 moves the outermost level
+    assert (np.abs(w - d) <= sfull * (1 + 3 * 2.0 ** -11) + 1e-18).all()
+    # q*s is exact in fp32; re-quantising the dequantised weights with the same scales gives the same codes
+    d32 = (q.astype(np.float32) * np.repeat(s.astype(np.float32), group, axis=1)).astype(np.float64)
+    assert np.array_equal(d, d32)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        u2 = np.where(sfull > 0, np.rint((d / sfull + 3) / 2), 0)
+    assert np.array_equal(2 * np.clip(u2, 0, 3).astype(np.int32) - 3, q)
+    # every non-zero group reaches an outermost level; the all-zero group dequantises to zero
+    gmax = np.abs(q).reshape(40, 4, group).max(axis=-1)
+    assert (gmax[np.abs(w).reshape(40, 4, group).max(-1) > 0] == 3).all()
+    assert s[5, 1] == 0 and (d[5, group:2 * group] == 0).all()
+    # coarser than the 4-bit format on the same weights, finer than nothing: error ordering
+    q4, s4 = O.quantize_sym(w, 4, group)
+    d4 = O.dequant(O.pack_codes(q4, 4), s4, 4, group)
+    assert np.abs(w - d4).mean() < np.abs(w - d).mean() < np.abs(w).mean()
