@@ -121,13 +121,16 @@ fate_status fate_route_fused(void* stream, const void* x_bf16, const void* Wg_bf
  * reduction dimension of an output row, w = q*s.
  *   int8: two's-complement bytes [rows,K];  int4: nibble u = q+8, two per
  *   byte, low nibble = even column, [rows,K/2];  scales fp16 [rows,K/group].
+ *   int2 (the low-precision copy of section 4.5): field u in 0..3, four per
+ *   byte, column 4b+i in bits 2i..2i+1 of byte b, [rows,K/4]; the code is the
+ *   odd integer q = 2u-3, i.e. the levels -3s, -s, s, 3s of the group.
  *
  * Device-native form used by the FFN kernels: 1 KiB tiles of 32 rows x
- * (64 | 32) columns (int4 | int8), one 16-byte piece per lane of a
+ * (128 | 64 | 32) columns (int2 | int4 | int8), one 16-byte piece per lane of a
  * wavefront, so that a wave-wide load is one contiguous KiB and each lane's
  * piece feeds its MFMA operand or its dot products directly.
  * fate_pack_weight converts canonical -> device-native (dev to dev, same
- * byte size, out of place).  rows % 32 == 0, K % 64 == 0.
+ * byte size, out of place).  rows % 32 == 0, K % 64 == 0 (K % 128 == 0 for int2).
  * Device-native scales are group-major, fp16 [K/group, rows]: the 32 rows of
  * a tile find their scales of one group in 64 contiguous bytes.
  * fate_pack_scales transposes canonical [rows, groups] into that form (dev
@@ -145,7 +148,7 @@ typedef struct {
     const void* s1; /* fp16 scales, group-major [H/group, I] */
     const void* s3;
     const void* s2; /* fp16 scales, group-major [I/group, H] */
-    int32_t bits;   /* 4 or 8 */
+    int32_t bits;   /* 2, 4 or 8: width of THIS copy */
     int32_t group;  /* multiple of 64 */
     int32_t I;      /* intermediate size, multiple of 64 */
     int32_t reserved;
@@ -166,14 +169,20 @@ typedef struct {
  * expert_order [E] dev (from fate_permute).  y [N,H] dev, fp32 (y_is_fp32) or
  * bf16, overwritten.  I_max / I_shared_max bound the intermediate sizes in the
  * tables (host-known; used to size launches and scratch); bits/group of the
- * routed experts and of the shared experts are passed host-side as well and
- * must match the table entries.
+ * routed experts and of the shared experts are passed host-side as well: they
+ * are the nominal format of the layer.  The kernels read the width and group of
+ * every entry from the table, so a layer may mix copies of different widths
+ * (the popularity-aware hybrid of section 4.5: the least popular experts of a
+ * prefill arrive as 2-bit copies); a group is a whole number of tile columns
+ * (128 / 64 / 32 for int2 / int4 / int8); the decode kernels take groups of
+ * 64..256 columns (int4), 64 / 128 (int8), 128 / 256 (int2).
  * mode: 0 = choose (decode kernels if N <= 16, else MFMA), 1 = decode
  * dequant-GEMV kernels, 2 = MFMA grouped GEMM (H and the intermediate sizes
  * multiples of 128; N*H, N*k*I_max and n_shared*N*I_shared_max below 2^31;
  * FATE_ESHAPE otherwise).
- * Activated experts whose w1 is NULL are skipped and flagged: the int32 at
- * workspace offset 0 is set non-zero (check with fate_moe_ffn_q_status).
+ * Activated experts whose w1 is NULL are skipped and flagged in the int32 at
+ * workspace offset 0 (bit 0); an entry whose width / group the kernels cannot
+ * read is skipped too (bit 2).
  * ---------------------------------------------------------------------- */
 typedef struct {
     int32_t N, H, E, k;

@@ -126,8 +126,8 @@ extern "C" int fate_hip_engine_copy(void* engine, int layer, int expert, int slo
     if (!g || layer < 0 || layer >= g->num_layers || expert < 0 || expert >= g->E || slot < 0 ||
         slot >= g->total_slots)
         return 1;
+    // a width that names the low pool comes from there; every other request is the cache's own copy
     const bool low = g->host_low != nullptr && bits == g->lay_low.bits;
-    if (!low && bits != g->lay.bits) return 6;       // no pool holds copies of that width
     const fate_slot_layout& lay = low ? g->lay_low : g->lay;
     const char* src = (low ? g->host_low : g->host) + ((size_t)layer * g->E + expert) * lay.slot_bytes;
     const size_t nb = lay.slot_bytes;

@@ -144,7 +144,8 @@ __device__ __forceinline__ void ring_run(TileRing<NMAT, D, TPG>& r, const gu4_t*
 
 // The register ring's type depends on the tiles per group; the format of an
 // expert is only known at run time, so the kernels branch once to the matching
-// instantiation.  tpg in {1, 2, 4} for int4, {2, 4} for int8 (checked on the host).
+// instantiation.  tpg in {1, 2, 4} for int4, {2, 4} for int8, {1, 2} for int2 (checked on the host
+// for the descriptor's widths, on the device for an expert entry of another width).
 #define FATE_FORMAT_SWITCH(bits, tpg, BODY)                \
     if ((bits) == 4) {                                     \
         if ((tpg) == 2) { BODY(4, 2) }                     \
@@ -155,8 +156,31 @@ __device__ __forceinline__ void ring_run(TileRing<NMAT, D, TPG>& r, const gu4_t*
         else { BODY(8, 2) }                                \
     }
 
+__host__ __device__ inline int tile_columns(int bits) { return bits == 4 ? 64 : (bits == 8 ? 32 : 128); }
+// the same with the 2-bit format (the separate-call FFN kernels; the one-call layer keeps 4 / 8 bits)
+#define FATE_FORMAT_SWITCH_ALL(bits, tpg, BODY)            \
+    if ((bits) == 2) {                                     \
+        if ((tpg) == 1) { BODY(2, 1) }                     \
+        else { BODY(2, 2) }                                \
+    } else {                                               \
+        FATE_FORMAT_SWITCH(bits, tpg, BODY)                \
+    }
+
 static inline bool decode_group_ok(int bits, int group) {
-    const int tpg = group / (bits == 4 ? 64 : 32);
+    if (group % tile_columns(bits)) return false;
+    const int tpg = group / tile_columns(bits);
+    if (bits == 2) return tpg == 1 || tpg == 2;
+    return bits == 4 ? (tpg == 1 || tpg == 2 || tpg == 4) : (tpg == 2 || tpg == 4);
+}
+
+// An expert entry as the FFN kernels can read it: a width they know, a group that is a whole
+// number of tiles and one of the instantiated tiles-per-group, dimensions that are whole groups.
+__host__ __device__ inline bool entry_format_ok(int bits, int group, int H, int I) {
+    if (bits != 2 && bits != 4 && bits != 8) return false;
+    const int kt = tile_columns(bits);
+    if (group <= 0 || group % kt || H % group || I % group) return false;
+    const int tpg = group / kt;
+    if (bits == 2) return tpg == 1 || tpg == 2;
     return bits == 4 ? (tpg == 1 || tpg == 2 || tpg == 4) : (tpg == 2 || tpg == 4);
 }
 

@@ -15,14 +15,15 @@ static fate_status check_desc(const fate_ffn_desc* d) {
     if (d->E < 1 || d->E > kMaxE) FATE_FAIL(FATE_ESHAPE, "E = %d outside [1, %d]", d->E, kMaxE);
     if (d->k < 1 || d->k > d->E) FATE_FAIL(FATE_EINVAL, "k = %d outside [1, E]", d->k);
     if (d->H < 64 || d->H % 64) FATE_FAIL(FATE_ESHAPE, "H = %d must be a positive multiple of 64", d->H);
-    if (d->bits != 4 && d->bits != 8) FATE_FAIL(FATE_EINVAL, "bits = %d (4 or 8)", d->bits);
+    if (d->bits != 2 && d->bits != 4 && d->bits != 8) FATE_FAIL(FATE_EINVAL, "bits = %d (2, 4 or 8)", d->bits);
     if (d->group < 64 || d->group % 64) FATE_FAIL(FATE_ESHAPE, "group = %d must be a multiple of 64", d->group);
     if (d->I_max < 64 || d->I_max % 64) FATE_FAIL(FATE_ESHAPE, "I_max = %d must be a multiple of 64", d->I_max);
     if (d->H % d->group || d->I_max % d->group)
         FATE_FAIL(FATE_ESHAPE, "H and I_max must be multiples of the group (%d)", d->group);
     if (d->n_shared < 0 || d->n_shared > 16) FATE_FAIL(FATE_EINVAL, "n_shared = %d outside [0, 16]", d->n_shared);
     if (d->n_shared) {
-        if (d->shared_bits != 4 && d->shared_bits != 8) FATE_FAIL(FATE_EINVAL, "shared_bits = %d", d->shared_bits);
+        if (d->shared_bits != 2 && d->shared_bits != 4 && d->shared_bits != 8)
+            FATE_FAIL(FATE_EINVAL, "shared_bits = %d", d->shared_bits);
         if (d->shared_group < 64 || d->shared_group % 64) FATE_FAIL(FATE_ESHAPE, "shared_group = %d", d->shared_group);
         if (d->I_shared_max < 64 || d->I_shared_max % 64 || d->I_shared_max % d->shared_group || d->H % d->shared_group)
             FATE_FAIL(FATE_ESHAPE, "I_shared_max = %d / H must be multiples of 64 and of the shared group", d->I_shared_max);

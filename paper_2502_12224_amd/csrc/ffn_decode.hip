@@ -40,7 +40,6 @@ __global__ __launch_bounds__(256, 2) void ffn_up_decode_kernel(DecodeArgs a) {
         live = T > 0;
         ex = a.experts + e;
         sbeg = a.offsets[e];
-        bits = a.bits_r; group = a.group_r;
         hbuf = a.h_r + (size_t)sbeg * a.ldh_r; ldh = a.ldh_r;
     } else {
         b -= nrout;
@@ -48,13 +47,18 @@ __global__ __launch_bounds__(256, 2) void ffn_up_decode_kernel(DecodeArgs a) {
         rb = b % a.rb_s;
         ex = a.shared + s;
         T = a.N;
-        bits = a.bits_s; group = a.group_s;
         hbuf = a.h_s + (size_t)s * a.N * a.ldh_s; ldh = a.ldh_s;
     }
+    // the width and group of THIS expert's copy (a layer may hold copies of several widths)
+    bits = ex->bits; group = ex->group;
     gu4_t w1 = nullptr;
     gu4_t w3 = nullptr;
     if (live) {
         live = rb * 32 < ex->I;
+        if (live && !entry_format_ok(bits, group, a.H, ex->I)) {
+            if (tid == 0) atomicOr(a.status, 4);
+            live = false;
+        }
         w1 = as_global<uint4>(ex->w1);
         w3 = as_global<uint4>(ex->w3);
         if (live && (w1 == nullptr || w3 == nullptr)) {
@@ -71,7 +75,7 @@ __global__ __launch_bounds__(256, 2) void ffn_up_decode_kernel(DecodeArgs a) {
     }
     if (!live) return;
     const int H = a.H, nvec = H >> 3, G = H / group;
-    const int KT = bits == 4 ? 64 : 32;
+    const int KT = tile_columns(bits);
     const int tiles_k = H / KT, tpg = group / KT;
     const int n = lane & 31, half = lane >> 5;
     const int g_beg = G * wave / 4, g_end = G * (wave + 1) / 4;
@@ -130,7 +134,7 @@ __global__ __launch_bounds__(256, 2) void ffn_up_decode_kernel(DecodeArgs a) {
             finish(nt, t0, out);                                                                          \
         }                                                                                                 \
     }
-    FATE_FORMAT_SWITCH(bits, tpg, FATE_UP_BODY)
+    FATE_FORMAT_SWITCH_ALL(bits, tpg, FATE_UP_BODY)
 #undef FATE_UP_BODY
 }
 
@@ -155,7 +159,6 @@ __global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
         if (T == 0) return;
         ex = a.experts + e;
         sbeg = a.offsets[e];
-        bits = a.bits_r; group = a.group_r;
         hbuf = a.h_r + (size_t)sbeg * a.ldh_r; ldh = a.ldh_r;
     } else {
         b -= nrout;
@@ -164,15 +167,18 @@ __global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
         rb = rem / a.nchunk_s; ch = rem - rb * a.nchunk_s; cg = a.cg_s;
         ex = a.shared + s;
         T = a.N;
-        bits = a.bits_s; group = a.group_s;
         hbuf = a.h_s + (size_t)s * a.N * a.ldh_s; ldh = a.ldh_s;
     }
+    bits = ex->bits; group = ex->group;
+    if (!entry_format_ok(bits, group, a.H, ex->I)) return;     // flagged by the up kernel
+    // the launch cut the reduction dimension into chunks of cg groups of the descriptor's group size
+    cg = cg * (is_shared ? a.group_s : a.group_r) / group;
     const int I = ex->I, G = I / group;
     const int gb = ch * cg, ge = min(G, gb + cg);
     if (gb >= ge) return;
     gu4_t w2 = as_global<uint4>(ex->w2);
     if (w2 == nullptr) return;   // flagged by the up kernel
-    const int KT = bits == 4 ? 64 : 32;
+    const int KT = tile_columns(bits);
     const int tiles_k = I / KT, tpg = group / KT;
     const int n = lane & 31, half = lane >> 5;
     gu4_t wt[1] = {w2 + (size_t)rb * tiles_k * 64 + lane};
@@ -243,7 +249,7 @@ __global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
             finish(nt, t0, out);                                                                          \
         }                                                                                                 \
     }
-    FATE_FORMAT_SWITCH(bits, tpg, FATE_DOWN_BODY)
+    FATE_FORMAT_SWITCH_ALL(bits, tpg, FATE_DOWN_BODY)
 #undef FATE_DOWN_BODY
 }
 

@@ -145,7 +145,20 @@ __device__ __forceinline__ void dequant_tile(const uint4& raw, uint32_t scale_bi
     const f16x2v_t s2 = {__builtin_bit_cast(_Float16, (unsigned short)scale_bits),
                          __builtin_bit_cast(_Float16, (unsigned short)scale_bits)};
     const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
-    if constexpr (BITS == 4) {
+    if constexpr (BITS == 2) {
+        // sixteen fields per dword -> two operands of 8 columns; signed code 2u - 3 (exact), one rounding in code * scale
+        const f16x2v_t two = {(_Float16)2.f, (_Float16)2.f}, three = {(_Float16)3.f, (_Float16)3.f};
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            f16x2_t f[8];
+            int2_fields_to_f16(r[d], f);
+            f16x2v_t w[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[i] = (__builtin_bit_cast(f16x2v_t, f[i]) * two - three) * s2;
+            b[2 * d] = f16x8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
+            b[2 * d + 1] = f16x8_t{w[4].x, w[4].y, w[5].x, w[5].y, w[6].x, w[6].y, w[7].x, w[7].y};
+        }
+    } else if constexpr (BITS == 4) {
         const f16x2v_t offA = {(_Float16)1032.f, (_Float16)1032.f};   // 1024 + 8
         const f16x2v_t offB = {(_Float16)72.f, (_Float16)72.f};       // 64 + 8
 #pragma unroll
@@ -186,8 +199,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
                                           int nblk, const int* arow, __half* xt, __half* out, int ldo,
                                           int out_row0, int Nout, int K, const __half* A, int lda) {
     constexpr int KT = QFmt<BITS>::KT;
-    constexpr int TPC = kKC / KT;          // weight tiles per chunk (2 | 4)
-    constexpr int SPT = KT / 16;           // MFMA k-slots per tile (4 | 2)
+    constexpr int TPC = kKC / KT;          // weight tiles per chunk (1 | 2 | 4)
+    constexpr int SPT = KT / 16;           // MFMA k-slots per tile (8 | 4 | 2)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, half = lane >> 5;
     const int G = K / group, tiles_k = K / KT, nchunk = K / kKC;
@@ -403,9 +416,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __half* out = is_shared ? a.out_s : a.out_r;
     const int ldo = is_shared ? a.ldo_s : a.ldo_r;
     const int out_row0 = (is_shared ? (seg - a.E) * a.N : sbeg) + row0;
-    const int bits = is_shared ? a.bits_s : a.bits_r, group = is_shared ? a.group_s : a.group_r;
+    // width and group of THIS expert's copy: a layer may hold copies of several widths (the
+    // popularity-aware hybrid of section 4.5 moves the least popular experts at 2 bits)
+    const int bits = ex->bits, group = ex->group;
+    const int kt = bits == 4 ? 64 : (bits == 8 ? 32 : 128);
+    if ((bits != 2 && bits != 4 && bits != 8) || group < kt || group % kt || K % group) {
+        if (threadIdx.x == 0) atomicOr(a.status, 4);
+        return;
+    }
     if (bits == 4)
         gemm_tile<4, NMAT, kBM>(a, ex, group, row0, T, nblk, arow, xt, out, ldo, out_row0, Nout, K, A, lda);
+    else if (bits == 2)
+        gemm_tile<2, NMAT, kBM>(a, ex, group, row0, T, nblk, arow, xt, out, ldo, out_row0, Nout, K, A, lda);
     else
         gemm_tile<8, NMAT, kBM>(a, ex, group, row0, T, nblk, arow, xt, out, ldo, out_row0, Nout, K, A, lda);
 }

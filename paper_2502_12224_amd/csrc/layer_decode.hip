@@ -56,6 +56,8 @@ fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArg
     if (d.N < 1 || d.N > kLayerMaxN || d.N * d.k > kLayerMaxP)
         FATE_FAIL(FATE_ESHAPE, "fused layer: need 1 <= N <= %d and N*k <= %d (N = %d, k = %d)", kLayerMaxN,
                   kLayerMaxP, d.N, d.k);
+    if (d.bits == 2 || (d.n_shared && d.shared_bits == 2))
+        FATE_FAIL(FATE_ESHAPE, "fused layer: 4- and 8-bit experts only (2-bit copies go through fate_moe_ffn_q)");
     if (!decode_group_ok(d.bits, d.group) || (d.n_shared && !decode_group_ok(d.shared_bits, d.shared_group)))
         FATE_FAIL(FATE_ESHAPE, "fused layer: group must be 64, 128 or 256 (int4) / 64 or 128 (int8)");
     const WorkLds L = work_lds(d.N, d.H, d.E, d.k);

@@ -248,7 +248,8 @@ __device__ __forceinline__ void b1_up_role(const B1Args& A, int ub, bool is_shar
         unsigned long long* hq_dst = A.a.hq + ((size_t)s * a.nkb_s + kb) * 16;
         const fate_qexpert ex = a.shared[s];
         B1_TS(1);
-        const bool absent = ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr;
+        const bool absent = ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr || ex.bits != a.bits_s ||
+                            ex.group != a.group_s;
         uint32_t hbits = 0;
         if (absent && tid == 0) atomicOr(a.status, 1);
         if (!absent && kb * kLayerNeurons < ex.I) {
@@ -282,7 +283,8 @@ __device__ __forceinline__ void b1_up_role(const B1Args& A, int ub, bool is_shar
     for (int pass = 0; pass < 2; ++pass) {
         bool absent = true;
         if (e_cur >= 0) {
-            absent = ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr;
+            absent = ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr || ex.bits != a.bits_r ||
+                     ex.group != a.group_r;
             hbits = 0;
             if (!absent && kb * kLayerNeurons < ex.I) {
                 cx.I = ex.I; cx.kb = kb; cx.ex = ex;
@@ -322,7 +324,8 @@ __device__ __forceinline__ int b1_down_request(const fate_qexpert& ex, int H, in
     const int tiles_k2 = ex.I / KT;
     const int gmax = ex.I / group;
     ng = g0 + ng <= gmax ? ng : (gmax > g0 ? gmax - g0 : 0);
-    if (ng <= 0 || ex.w2 == nullptr) return 0;
+    if (ng <= 0 || ex.w2 == nullptr || ex.w1 == nullptr || ex.w3 == nullptr || ex.bits != BITS || ex.group != group)
+        return 0;
     const int nt = ng * TPG;
     gu4_t w2 = as_global<uint4>(ex.w2) + ((size_t)rb * tiles_k2 + (size_t)g0 * TPG) * 64 + lane;
     gu16_t s2 = as_global<uint16_t>(ex.s2) + (size_t)g0 * H + rb * 32 + n;

@@ -14,7 +14,20 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const uint32_t* __rest
     const int lane = (int)((o >> 2) & 63);
     const long long tile = o >> 8;
     const int n = lane & 31, half = lane >> 5;
-    if (bits == 4) {
+    if (bits == 2) {
+        const int tiles_k = K / 128;
+        const int rb = (int)(tile / tiles_k), kb = (int)(tile % tiles_k);
+        const long long row = (long long)rb * 32 + n;
+        const int k0 = kb * 128 + half * 64 + 16 * d;               // 16 fields = one canonical dword
+        const uint32_t s = src[(row * K + k0) >> 4];
+        uint32_t r = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            r |= ((s >> (4 * i)) & 0x3u) << (2 * i);                // column 2i   -> bits 2i
+            r |= ((s >> (4 * i + 2)) & 0x3u) << (2 * i + 16);       // column 2i+1 -> bits 16 + 2i
+        }
+        dst[o] = r;
+    } else if (bits == 4) {
         const int tiles_k = K / 64;
         const int rb = (int)(tile / tiles_k), kb = (int)(tile % tiles_k);
         const long long row = (long long)rb * 32 + n;
@@ -66,9 +79,10 @@ extern "C" fate_status fate_pack_scales(void* stream, const void* canonical_dev,
 
 extern "C" fate_status fate_pack_weight(void* stream, const void* canonical_dev, int rows, int K, int bits,
                                         void* packed_dev) {
-    if (bits != 4 && bits != 8) FATE_FAIL(FATE_EINVAL, "bits = %d (4 or 8 supported)", bits);
+    if (bits != 2 && bits != 4 && bits != 8) FATE_FAIL(FATE_EINVAL, "bits = %d (2, 4 or 8 supported)", bits);
     if (rows < 32 || rows % 32 != 0) FATE_FAIL(FATE_ESHAPE, "rows = %d must be a positive multiple of 32", rows);
-    if (K < 64 || K % 64 != 0) FATE_FAIL(FATE_ESHAPE, "K = %d must be a positive multiple of 64", K);
+    const int kt = bits == 2 ? 128 : 64;
+    if (K < kt || K % kt != 0) FATE_FAIL(FATE_ESHAPE, "K = %d must be a positive multiple of %d", K, kt);
     FATE_CHECK_PTR(canonical_dev);
     FATE_CHECK_PTR(packed_dev);
     if (canonical_dev == packed_dev) FATE_FAIL(FATE_EINVAL, "packing is out of place");

@@ -11,6 +11,11 @@
 //         isolates one pair of neighbouring columns in the low bits of the
 //         two 16-bit halves.
 //   int8: 16 bytes in column order, offset binary u = q + 128.
+//   int2: KT = 128; the lane's 64 codes sit in 4 dwords of 16; in dword d the
+//         field (u in 0..3, signed code q = 2u - 3) of column 16d + 2i is bits
+//         2i..2i+1 and that of column 16d + 2i + 1 is bits 16+2i..16+2i+1, so
+//         (dword >> 8j) & (3 << 2i) isolates a pair of neighbouring columns in
+//         the two 16-bit halves at four mantissa positions.
 //
 // A pair of codes becomes a pair of 16-bit floats by OR-ing the integer into
 // the mantissa of a power of two: bf16 0x4300|u = 128 + u, fp16 0x6400|u =
@@ -31,6 +36,14 @@ struct QFmt<4> {
     static constexpr int MSTEPS = 4;    // 8-code matrix-core operands per lane per tile
     static constexpr float OFF_BF16 = 136.f;   // 128 + 8
     static constexpr float OFF_F16 = 1032.f;   // 1024 + 8
+};
+template <>
+struct QFmt<2> {
+    static constexpr int KT = 128;
+    static constexpr int NP = 32;
+    static constexpr int MSTEPS = 8;
+    static constexpr float OFF_BF16 = 0.f;     // (the pair form is not used for this width)
+    static constexpr float OFF_F16 = 0.f;
 };
 template <>
 struct QFmt<8> {
@@ -96,10 +109,38 @@ __device__ __forceinline__ uint32_t and_or_b32(uint32_t x, uint32_t mask, uint32
 // power-of-two mantissa tricks so that one shift serves four pairs:
 // 0x6400|u = 1024 + u for nibbles at bits 0..3, 0x5400|(u << 4) = 64 + u for
 // nibbles at bits 4..7 of each 16-bit half.
+// One dword of sixteen 2-bit fields -> 16 fp16 values u (0..3) in column order: the field is
+// OR-ed into the mantissa of 1024, 256, 64 or 16 by its bit position and the power of two
+// is subtracted again (exact).
+__device__ __forceinline__ void int2_fields_to_f16(uint32_t r, f16x2_t (&w)[8]) {
+    const f16x2_t c0 = {(_Float16)1024.f, (_Float16)1024.f}, c1 = {(_Float16)256.f, (_Float16)256.f};
+    const f16x2_t c2 = {(_Float16)64.f, (_Float16)64.f}, c3 = {(_Float16)16.f, (_Float16)16.f};
+    const uint32_t hi = r >> 8;
+    w[0] = __builtin_bit_cast(f16x2_t, and_or_b32(r, 0x00030003u, 0x64006400u)) - c0;
+    w[1] = __builtin_bit_cast(f16x2_t, and_or_b32(r, 0x000c000cu, 0x5c005c00u)) - c1;
+    w[2] = __builtin_bit_cast(f16x2_t, and_or_b32(r, 0x00300030u, 0x54005400u)) - c2;
+    w[3] = __builtin_bit_cast(f16x2_t, and_or_b32(r, 0x00c000c0u, 0x4c004c00u)) - c3;
+    w[4] = __builtin_bit_cast(f16x2_t, and_or_b32(hi, 0x00030003u, 0x64006400u)) - c0;
+    w[5] = __builtin_bit_cast(f16x2_t, and_or_b32(hi, 0x000c000cu, 0x5c005c00u)) - c1;
+    w[6] = __builtin_bit_cast(f16x2_t, and_or_b32(hi, 0x00300030u, 0x54005400u)) - c2;
+    w[7] = __builtin_bit_cast(f16x2_t, and_or_b32(hi, 0x00c000c0u, 0x4c004c00u)) - c3;
+}
+
 template <int BITS>
 __device__ __forceinline__ void codes_to_f16(const uint4& raw, f16x8_t* b) {
     const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
-    if constexpr (BITS == 4) {
+    if constexpr (BITS == 2) {
+        const f16x2_t two = {(_Float16)2.f, (_Float16)2.f}, three = {(_Float16)3.f, (_Float16)3.f};
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            f16x2_t w[8];
+            int2_fields_to_f16(r[d], w);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[i] = w[i] * two - three;      // signed code 2u - 3, exact
+            b[2 * d] = f16x8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
+            b[2 * d + 1] = f16x8_t{w[4].x, w[4].y, w[5].x, w[5].y, w[6].x, w[6].y, w[7].x, w[7].y};
+        }
+    } else if constexpr (BITS == 4) {
         const f16x2_t offA = {(_Float16)1032.f, (_Float16)1032.f};   // 1024 + 8
         const f16x2_t offB = {(_Float16)72.f, (_Float16)72.f};       // 64 + 8
 #pragma unroll

@@ -206,6 +206,7 @@ class OffloadedStack:
         self.cache = lib.fate_cache_create(L, E, cache_total, Ls, n_max, staging_slots, self._copy_fn,
                                            C.c_void_p(self.engine))
         assert lib.fate_cache_total_slots(self.cache) == self.total_slots
+        B._check(lib.fate_cache_set_low_precision(self.cache, 0, cfg.bits, 2))     # width labels of the load list
         for l in range(L):
             for e in range(E):
                 s = lib.fate_cache_slot_of(self.cache, l, e)

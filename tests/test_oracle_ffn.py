@@ -59,7 +59,7 @@ def test_quant_round_trip_and_error_bound(bits, group):
     assert s[3, 0] == np.float16(1.0) and (q[3, :group] == 0).all()
 
 
-@pytest.mark.parametrize("bits,group", [(8, 64), (4, 128)])
+@pytest.mark.parametrize("bits,group", [(8, 64), (4, 128), (2, 128)])
 def test_workload_quantizer_agrees_with_oracle_reading(bits, group):
     """The generator's stored weights obey the oracle's format: same scales,
     and codes that differ at most where w/s sits on a rounding boundary."""
@@ -69,7 +69,7 @@ def test_workload_quantizer_agrees_with_oracle_reading(bits, group):
     q_ref, s_ref = O.quantize_sym(w.numpy().astype(np.float64), bits, group)
     assert np.array_equal(s.numpy(), s_ref)
     q = O.unpack_codes(codes.numpy(), bits)
-    assert np.abs(q - q_ref).max() <= 1 and (q != q_ref).mean() < 1e-3
+    assert np.abs(q - q_ref).max() <= (2 if bits == 2 else 1) and (q != q_ref).mean() < 1e-3
 
 
 def _dense_swiglu_torch(x, W1, W3, W2):

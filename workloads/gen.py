@@ -9,6 +9,8 @@ are those codes and scales.  The storage format ("canonical layout"):
   int8: one two's-complement byte per code, row-major [rows, K].
   int4: unsigned nibble u = q + 8, two per byte, low nibble = even column,
         row-major [rows, K/2].
+  int2: field u in 0..3 (level (2u - 3) * scale), four per byte, column 4b+i in bits 2i..2i+1
+        of byte b, row-major [rows, K/4].
   scales: fp16, row-major [rows, K/group].
 """
 from dataclasses import dataclass
@@ -74,9 +76,19 @@ def quantize_sym(w: torch.Tensor, bits: int, group: int):
     scale = fp16(max|w| / qmax) per group (1 for an all-zero group), code =
     round-half-even(w / scale) clamped to [-qmax, qmax].
     """
-    assert bits in (4, 8)
+    assert bits in (2, 4, 8)
     rows, K = w.shape
-    assert K % group == 0 and group % 2 == 0
+    assert K % group == 0 and group % 4 == 0
+    if bits == 2:
+        # four levels -3s, -s, s, 3s with s = fp16(max|w| / 3) (0 for an all-zero group); field u = (q + 3) / 2
+        wg = w.reshape(rows, K // group, group)
+        s = (wg.abs().amax(dim=-1) / 3).to(torch.float16)
+        sf = s.to(torch.float32).unsqueeze(-1)
+        u = torch.where(sf > 0, torch.round((wg / torch.where(sf > 0, sf, torch.ones_like(sf)) + 3) / 2),
+                        torch.zeros_like(wg))
+        u = torch.clamp(u, 0, 3).reshape(rows, K).to(torch.uint8)
+        codes = u[:, 0::4] | (u[:, 1::4] << 2) | (u[:, 2::4] << 4) | (u[:, 3::4] << 6)
+        return codes.contiguous(), s.contiguous()
     qmax = 127 if bits == 8 else 7
     wg = w.reshape(rows, K // group, group)
     s = (wg.abs().amax(dim=-1) / qmax).to(torch.float16)
@@ -113,18 +125,30 @@ class QExpertHost:
                            self.s2.cpu(), self.bits, self.group, self.I, self.H)
 
 
-def gen_expert(cfg: MoEShape, layer: int, e: int, shared: bool = False, device="cpu") -> QExpertHost:
-    """Expert e of a layer: three N(0, w_std) matrices, quantised."""
+def gen_expert(cfg: MoEShape, layer: int, e: int, shared: bool = False, device="cpu", bits: Optional[int] = None,
+               group: Optional[int] = None) -> QExpertHost:
+    """Expert e of a layer: three N(0, w_std) matrices, quantised.  bits / group override the
+    configuration's format: the same weights (same random stream) stored at another width."""
     I = cfg.I_shared if shared else cfg.I
-    bits = cfg.shared_bits if shared else cfg.bits
+    bits = bits or (cfg.shared_bits if shared else cfg.bits)
+    group = group or cfg.group
     g = _gen(device, cfg.seed, _KIND["shared" if shared else "expert"], layer, e)
     mats = []
     for rows, K in ((I, cfg.H), (I, cfg.H), (cfg.H, I)):
         w = torch.randn(rows, K, generator=g, device=device, dtype=torch.float32) * cfg.w_std
-        mats.append(quantize_sym(w, bits, cfg.group))
+        mats.append(quantize_sym(w, bits, group))
         del w
     (w1, s1), (w3, s3), (w2, s2) = mats
-    return QExpertHost(w1, w3, w2, s1, s3, s2, bits, cfg.group, I, cfg.H)
+    return QExpertHost(w1, w3, w2, s1, s3, s2, bits, group, I, cfg.H)
+
+
+def gen_expert_unquantized(cfg: MoEShape, layer: int, e: int, shared: bool = False, device="cpu"):
+    """The fp32 matrices (W1, W3, W2) that gen_expert quantises: reference for the reported
+    quantisation error of a stored format."""
+    I = cfg.I_shared if shared else cfg.I
+    g = _gen(device, cfg.seed, _KIND["shared" if shared else "expert"], layer, e)
+    return tuple(torch.randn(rows, K, generator=g, device=device, dtype=torch.float32) * cfg.w_std
+                 for rows, K in ((I, cfg.H), (I, cfg.H), (cfg.H, I)))
 
 
 def unit_rmsnorm_bf16(h: torch.Tensor) -> torch.Tensor:
