@@ -566,6 +566,7 @@ def bench_offload(args):
         f"{L * E * ebytes / 1e9:.1f} GB; cache_total {cache_total}, H2D peak {peak:.1f} GB/s")
     st = OffloadedStack(cfg, cache_total, 0, staging_slots=3 * E, device=dev, layers=L,
                         predictor={"fate": "gate", "eap": "eap", "lod": "none"}[mode],
+                        low_bits=2 if args.low_percent > 0 else 0,
                         progress=lambda l: log(f"[bench]   layer {l} in the host pool ({time.time() - t0:.0f}s)"))
     log(f"[bench] per-layer capacities {st.caps}")
 
@@ -627,7 +628,11 @@ def bench_offload(args):
         run(Nd, args.eap_calibration_steps, 40_000, dbuf)
         st.eap_learning = False
     B._check(lib.fate_cache_set_n_max(st.cache, 0 if mode == "lod" else E))   # prefill: every predicted expert, most popular first
+    if args.low_percent > 0:
+        st.set_low_percent(args.low_percent)     # prefill only: the least popular predicted experts move as 2-bit copies
     pre = phase(Np, 1, 20_000, pbuf)
+    if args.low_percent > 0:
+        st.set_low_percent(0)
     B._check(lib.fate_cache_set_n_max(st.cache, n_max))
     log(f"[bench] prefill {Np} tokens: {pre['seconds'] * 1e3:.1f} ms, {pre['tokens_per_s']:.0f} tok/s, "
         f"hit rate {pre['hit_rate']:.3f}, H2D {pre['h2d_GB']:.2f} GB at {pre['h2d_GBs']:.1f} GB/s")
@@ -643,6 +648,7 @@ def bench_offload(args):
         "data": "synthetic",
         "config": {"workload": desc, "step": f"one decode step of batch {Nd} through {L} MoE layers, experts offloaded",
                    "layers": L, "batch": Nd, "mode": mode, "routed_bits": cfg.bits, "cache_frac": cache_frac,
+                   "prefill_low_width_percent": args.low_percent,
                    "cache_total": cache_total, "layer_capacities": st.caps,
                    "n_max": n_max, "n_from_resident_layer_time": n_cal,
                    "t_layer_resident_us": None if t_layer_resident is None else t_layer_resident * 1e6,
@@ -680,6 +686,9 @@ def main():
     ap.add_argument("--routed-bits", type=int, default=0, choices=[0, 4, 8],
                     help="offload workloads: code width of the routed experts (ablation of the quantisation step)")
     ap.add_argument("--eap-calibration-steps", type=int, default=32)
+    ap.add_argument("--low-percent", type=int, default=0,
+                    help="offload workloads: share of the predicted experts, least popular first, that the prefill pass "
+                         "moves as 2-bit copies (popularity-aware hybrid width; the paper uses 25 for Qwen1.5-MoE)")
     ap.add_argument("--n-max", type=int, default=None,
                     help="offload workloads: cap on prefetched experts per layer in decode (default: n = floor(T / "
                          "t_expert) from the measured resident layer time and link rate)")

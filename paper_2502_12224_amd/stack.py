@@ -147,9 +147,11 @@ class OffloadedStack:
     the built-in HIP copy engine (side stream) around the per-layer calls."""
 
     def __init__(self, cfg: MoEShape, cache_total, n_max, staging_slots, device="cuda", layers=None,
-                 L_shallow=None, progress=None, predictor="gate"):
+                 L_shallow=None, progress=None, predictor="gate", low_bits=0):
         """predictor: "gate" = the cross-layer gate prediction (the method), "eap" = the activation-path
-        baseline (co-activation statistics, fed through eap_observe), "none" = no prediction."""
+        baseline (co-activation statistics, fed through eap_observe), "none" = no prediction.
+        low_bits: 2 = also keep a 2-bit copy of every routed expert in a second pinned pool (section 4.5:
+        both widths live in host memory); set_low_percent() then switches the hybrid transfer width on."""
         self.cfg, self.device = cfg, device
         self.predictor = predictor
         self.nl = cfg.layers if layers is None else layers
@@ -170,6 +172,19 @@ class OffloadedStack:
         self.gates, self.shared, self.shared_tables, self.shared_gates = [], [], [], []
         self.host_pool = torch.empty(L * E, self.slot_bytes, dtype=torch.uint8, pin_memory=True)
         stage = torch.zeros(self.slot_bytes, dtype=torch.uint8, device=device)
+        self.low_bits = low_bits
+        if low_bits:
+            assert low_bits == 2 and cfg.group % 128 == 0 and cfg.H % 128 == 0 and cfg.I % 128 == 0
+            wl = cfg.I * cfg.H * low_bits // 8
+            offl, o = {}, 0
+            for name, nb in (("w1", wl), ("w3", wl), ("w2", wl), ("s1", sb), ("s3", sb), ("s2", sb)):
+                offl[name] = o
+                o = _align(o + nb)
+            self.low_slot_bytes = o
+            self.low_layout = B.fate_slot_layout(o, offl["w1"], offl["w3"], offl["w2"], offl["s1"], offl["s3"],
+                                                 offl["s2"], low_bits, cfg.group, cfg.I)
+            self.host_pool_low = torch.empty(L * E, o, dtype=torch.uint8, pin_memory=True)
+            stage_low = torch.zeros(o, dtype=torch.uint8, device=device)
         for l in range(L):
             self.gates.append(gen_gate(cfg, l, device))
             self.shared_gates.append(gen_shared_gate(cfg, l, device))
@@ -182,6 +197,12 @@ class OffloadedStack:
                     t = pe.t[name].reshape(-1).view(torch.uint8)
                     stage[offs[name]:offs[name] + t.numel()] = t
                 self.host_pool[l * E + e].copy_(stage)
+                if low_bits:
+                    pl = B.PackedExpert(gen_expert(cfg, l, e, device=device, bits=low_bits), device)
+                    for name in offl:
+                        t = pl.t[name].reshape(-1).view(torch.uint8)
+                        stage_low[offl[name]:offl[name] + t.numel()] = t
+                    self.host_pool_low[l * E + e].copy_(stage_low)
             if progress:
                 progress(l)
         torch.cuda.synchronize()
@@ -207,6 +228,9 @@ class OffloadedStack:
                                            C.c_void_p(self.engine))
         assert lib.fate_cache_total_slots(self.cache) == self.total_slots
         B._check(lib.fate_cache_set_low_precision(self.cache, 0, cfg.bits, 2))     # width labels of the load list
+        if low_bits:
+            B._check(lib.fate_hip_engine_set_low_pool(self.engine, C.byref(self.low_layout),
+                                                      C.c_void_p(self.host_pool_low.data_ptr())))
         for l in range(L):
             for e in range(E):
                 s = lib.fate_cache_slot_of(self.cache, l, e)
@@ -217,6 +241,7 @@ class OffloadedStack:
         self.stats = dict(hit_cache=0, hit_prefetch=0, miss=0, pair_hits=0, pair_misses=0, prefetch=0, wasted=0,
                           evicted=0)
         self.trace = []          # per step: (layer, compute_order, loads) for checks against the oracle
+        self.trace_bits = []     # per step: the width of every load
         self.keep_trace = False
         self._h_counts = torch.zeros(2, E, dtype=torch.int32).pin_memory()
         self._h_ids = torch.zeros(4096 * cfg.k, dtype=torch.int32).pin_memory()
@@ -228,6 +253,12 @@ class OffloadedStack:
         self._loads = (B.fate_cache_load * 512)()
         self._st = B.fate_cache_stats()
         self._nact = C.c_int32(0)
+
+    def set_low_percent(self, percent):
+        """Popularity-aware hybrid transfer width (section 4.5): the least popular `percent` % of the experts
+        predicted for the next layer travel as low-width copies.  A caller sets it for prefill, 0 for decode."""
+        assert percent == 0 or self.low_bits
+        B._check(self.lib.fate_cache_set_low_precision(self.cache, percent, self.cfg.bits, self.low_bits or 2))
 
     def table_for(self, l):
         return self.table[l * self.cfg.E * C.sizeof(B.fate_qexpert):]
@@ -282,6 +313,7 @@ class OffloadedStack:
         if self.keep_trace:
             self.trace.append((l, list(self._order[:n]), [(ld.layer, ld.expert, ld.slot, bool(ld.demand))
                                                           for ld in self._loads[:min(st.n_loads, 512)]]))
+            self.trace_bits.append([ld.bits for ld in self._loads[:min(st.n_loads, 512)]])
         B.fate_moe_ffn_q(buf.desc, x, self.table_for(l), buf.counts, buf.offsets, buf.perm, buf.inv_perm, buf.order,
                          buf.w, self.shared_tables[l], self.shared_gates[l], buf.y, buf.ffn_ws)
         self.done_event.record()

@@ -172,3 +172,57 @@ def test_offloaded_stack_comparison_modes(predictor):
             h = chain_next_hidden(h, y_off)
     assert (prefetched > 0) == (predictor == "eap")
     off.close()
+
+
+def test_offloaded_prefill_with_hybrid_transfer_width():
+    """Section 4.5 end to end on the device: in a prefill pass the least popular quarter of the predicted
+    experts arrives as 2-bit copies.  The load list (experts, slots, widths) equals the cache oracle's, the
+    bytes moved are the sum of the copies' sizes, and y equals the FFN oracle evaluated on the copy of every
+    expert that the layer really used."""
+    from oracle import moe as O
+    from workloads import gen_expert
+    from helpers import bias_np, f32, ffn_rel_err, oracle_expert
+    cfg = dataclasses.replace(SHAPES["qwen_prefill"], layers=3)
+    L, E, N = 3, cfg.E, 192
+    cache_total, n_max, staging = 60 + 12 + 12, E, 2 * E + E          # layer 0 full, 12 slots in each deep layer
+    off = OffloadedStack(cfg, cache_total, n_max, staging, DEV, layers=L, L_shallow=1, low_bits=2)
+    off.set_low_percent(25)
+    off.keep_trace = True
+    sim = OC.CacheOracle(L, E, cache_total, 1, n_max, staging, low_percent=25, bits=4, low_bits=2)
+    assert off.caps == sim.caps == [60, 12, 12]
+    buf = LayerBuffers(cfg, N, DEV, mode=2)
+    width = {}                     # (layer, expert) -> width of the copy staged for it
+    n_low = bytes_expected = 0
+    h = gen_hidden(cfg, N, step=0, device=DEV).float()
+    for l in range(L):
+        x = unit_rmsnorm_bf16(h)
+        y = off.layer(l, x, buf)
+        torch.cuda.synchronize()
+        assert int(buf.ffn_ws[:4].view(torch.int32)[0]) == 0
+        counts, pop = buf.counts.cpu().numpy(), buf.pred_pop.cpu().numpy()
+        aids = [e for e in range(E) if counts[e] > 0]
+        pids = [e for e in range(E) if pop[e] > 0] if l + 1 < L else []
+        r = sim.step(l, aids, [int(counts[e]) for e in aids], pids, [int(pop[e]) for e in pids])
+        tl, order, loads = off.trace[-1]
+        assert tl == l and order == r.compute_order and loads == r.loads and off.trace_bits[-1] == r.load_bits
+        for (ll, e, _, _), b in zip(r.loads, r.load_bits):
+            width[(ll, e)] = b
+            n_low += b == 2
+            bytes_expected += off.low_slot_bytes if b == 2 else off.slot_bytes
+        Wg, bias = off.gates[l]
+        rid, rw, _, rz = O.gate_route(f32(x), f32(Wg), bias_np(bias), cfg.k, cfg.renorm)
+        ties = set(O.near_tie_rows(rz, cfg.k).tolist())
+        rows = [t for t in range(N) if t not in ties]
+        assert np.array_equal(buf.ids.cpu().numpy()[rows], rid[rows])
+        used = sorted(set(rid.ravel().tolist()))
+        experts = {e: oracle_expert(gen_expert(cfg, l, e, device=DEV, bits=width.get((l, e), 4))) for e in used}
+        shared = [oracle_expert(gen_expert(cfg, l, s, shared=True, device=DEV)) for s in range(cfg.n_shared)]
+        y_ref = O.moe_ffn_grouped(f32(x), rid, rw, experts, shared, f32(off.shared_gates[l]))
+        err = ffn_rel_err(f32(y)[rows], y_ref[rows]).max()
+        low_used = sorted(e for e in used if width.get((l, e), 4) == 2)
+        print(f"layer {l}: {len(used)} experts activated, {len(low_used)} of them from 2-bit copies, max row error "
+              f"{err:.2e}", flush=True)
+        assert err <= 2e-3
+        h = chain_next_hidden(h, y)
+    assert n_low > 0 and off.bytes_copied() == bytes_expected
+    off.close()
