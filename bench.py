@@ -474,8 +474,12 @@ def bench_prefill(args, emit=True):
         times.append(e0.elapsed_time(e1) * 1e3 / (reps * L))
     up_us, ffn_us = times
     achieved = up_flops / (up_us * 1e-6) / 1e12
+    # the other roof: the stored bytes of the experts the layer activates (codes + scales), once per layer
+    layer_bytes = active * expert_bytes(H, cfg.I, cfg.bits, cfg.group) + \
+        cfg.n_shared * expert_bytes(H, cfg.I_shared or 0, cfg.shared_bits, cfg.group)
+    hbm_gbs = layer_bytes / (ffn_us * 1e-6) / 1e9
     log(f"[bench] prep+up GEMM {up_us:.1f} us/layer ({achieved:.0f} TFLOP/s), whole FFN {ffn_us:.1f} us/layer "
-        f"({layer_flops / (ffn_us * 1e-6) / 1e12:.0f} TFLOP/s)")
+        f"({layer_flops / (ffn_us * 1e-6) / 1e12:.0f} TFLOP/s; {layer_bytes / 1e6:.1f} MB of weights -> {hbm_gbs:.0f} GB/s)")
 
     cpu = None
     if not args.no_cpu_baseline and L > 1:
@@ -503,7 +507,12 @@ def bench_prefill(args, emit=True):
                    "cache_hit_rate": hits / max(1, hits + misses)},
         "roofline": {"bound": "mfma", "kernel": "prefill_prep_kernel + grouped_gemm_kernel<2>", "achieved": achieved,
                      "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_PEAK_TFLOPS,
-                     "traffic": None, "flops_per_launch": up_flops, "us_per_launch": up_us},
+                     "traffic": measured_traffic(f"prefill_{args.workload}_traffic.txt"),
+                     "flops_per_launch": up_flops, "us_per_launch": up_us,
+                     "hbm_roof": {"bound": "hbm", "kernel": "whole FFN call (four launches)",
+                                  "achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                  "frac": hbm_gbs / HBM_PEAK_GBS, "bytes_per_layer": layer_bytes,
+                                  "us_per_layer": ffn_us}},
         "cpu_baseline": cpu,
     }
     if not emit:
