@@ -637,6 +637,7 @@ def bench_offload(args):
         run(Nd, args.eap_calibration_steps, 40_000, dbuf)
         st.eap_learning = False
     B._check(lib.fate_cache_set_n_max(st.cache, 0 if mode == "lod" else E))   # prefill: every predicted expert, most popular first
+    st.overlap_piece = args.overlap_piece        # prefill FFN in pieces that follow the transfers (0 = one call per layer)
     if args.low_percent > 0:
         st.set_low_percent(args.low_percent)     # prefill only: the least popular predicted experts move as 2-bit copies
     pre = phase(Np, 1, 20_000, pbuf)
@@ -657,7 +658,7 @@ def bench_offload(args):
         "data": "synthetic",
         "config": {"workload": desc, "step": f"one decode step of batch {Nd} through {L} MoE layers, experts offloaded",
                    "layers": L, "batch": Nd, "mode": mode, "routed_bits": cfg.bits, "cache_frac": cache_frac,
-                   "prefill_low_width_percent": args.low_percent,
+                   "prefill_low_width_percent": args.low_percent, "prefill_overlap_piece": args.overlap_piece,
                    "cache_total": cache_total, "layer_capacities": st.caps,
                    "n_max": n_max, "n_from_resident_layer_time": n_cal,
                    "t_layer_resident_us": None if t_layer_resident is None else t_layer_resident * 1e6,
@@ -695,6 +696,9 @@ def main():
     ap.add_argument("--routed-bits", type=int, default=0, choices=[0, 4, 8],
                     help="offload workloads: code width of the routed experts (ablation of the quantisation step)")
     ap.add_argument("--eap-calibration-steps", type=int, default=32)
+    ap.add_argument("--overlap-piece", type=int, default=0,
+                    help="offload workloads: prefill FFN in pieces of this many experts that follow the order of the "
+                         "transfers (experts in the cache first), each piece waiting only for its own copies; 0 = one call")
     ap.add_argument("--low-percent", type=int, default=0,
                     help="offload workloads: share of the predicted experts, least popular first, that the prefill pass "
                          "moves as 2-bit copies (popularity-aware hybrid width; the paper uses 25 for Qwen1.5-MoE)")

@@ -202,6 +202,29 @@ fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, const void* x_b
                            void* y, void* workspace, size_t workspace_bytes);
 
 /* ------------------------------------------------------------------------
+ * The same FFN taken in pieces, for a prefill layer whose experts are still
+ * arriving (paper section 4.3, figure "rearranging the order of expert
+ * computations": experts already on the device are computed first, the others
+ * in the order of their transfers, so that computation and transfers overlap).
+ * Matrix-core mode only.  Each call processes the routed experts listed in
+ * part_experts (host array of n_part ids in [0,E), read during the call); a
+ * caller walks through the cache step's compute_order and makes the stream wait
+ * for a piece's transfers before the piece's call.
+ *   flags bit 0: first piece - prepares x, and processes the shared experts;
+ *   flags bit 1: last piece - adds up y (y is undefined before it).
+ * Every activated expert must belong to exactly one piece; the pieces of a
+ * layer share workspace and arguments and are ordered on one stream.  The
+ * result equals fate_moe_ffn_q's bit for bit.
+ * ---------------------------------------------------------------------- */
+fate_status fate_moe_ffn_q_part(void* stream, const fate_ffn_desc* d, const void* x_bf16,
+                                const fate_qexpert* experts_dev, const int32_t* counts, const int32_t* offsets,
+                                const int32_t* perm, const int32_t* inv_perm, const int32_t* expert_order,
+                                const float* topk_w,
+                                const fate_qexpert* shared_dev, const void* shared_gate_bf16,
+                                void* y, void* workspace, size_t workspace_bytes,
+                                const int32_t* part_experts, int n_part, int flags);
+
+/* ------------------------------------------------------------------------
  * Whole decode-side MoE layer in one call (1 <= N <= 8, N*k <= 64; two
  * launches: the layer kernel and a small reduction): fate_gate_route +
  * fate_cross_layer_predict + fate_permute + fate_moe_ffn_q (section 4.1

@@ -20,7 +20,7 @@ STATUS_NAMES = {0: "FATE_OK", 1: "FATE_EINVAL", 2: "FATE_ESHAPE", 3: "FATE_EALIG
 EXPORTS = [
     "fate_last_error", "fate_version", "fate_gate_route", "fate_cross_layer_predict", "fate_permute",
     "fate_route_fused_workspace", "fate_route_fused", "fate_pack_weight", "fate_pack_scales", "fate_moe_ffn_q_workspace",
-    "fate_moe_ffn_q", "fate_profile_ffn_mfma_phase", "fate_moe_layer_decode_workspace", "fate_moe_layer_decode",
+    "fate_moe_ffn_q", "fate_moe_ffn_q_part", "fate_profile_ffn_mfma_phase", "fate_moe_layer_decode_workspace", "fate_moe_layer_decode",
     "fate_moe_layer_decode_noalloc", "fate_cache_total_from_budget", "fate_n_max_from_times", "fate_cache_layer_capacities",
     "fate_cache_create", "fate_cache_destroy", "fate_cache_total_slots", "fate_cache_set_n_max",
     "fate_cache_set_low_precision", "fate_hip_engine_set_low_pool", "fate_cache_slot_of",
@@ -239,6 +239,16 @@ def fate_moe_ffn_q(desc, x, experts_dev, counts, offsets, perm, inv_perm, expert
     _check(lib().fate_moe_ffn_q(_stream(stream), C.byref(desc), _p(x), _p(experts_dev), _p(counts), _p(offsets),
                                 _p(perm), _p(inv_perm), _p(expert_order), _p(topk_w), _p(shared_dev), _p(shared_gate), _p(y),
                                 _p(workspace), C.c_size_t(workspace.numel() * workspace.element_size())))
+
+
+def fate_moe_ffn_q_part(desc, x, experts_dev, counts, offsets, perm, inv_perm, expert_order, topk_w, shared_dev,
+                        shared_gate, y, workspace, part_experts, first, last, stream=None):
+    arr = (C.c_int32 * max(1, len(part_experts)))(*part_experts)
+    _check(lib().fate_moe_ffn_q_part(_stream(stream), C.byref(desc), _p(x), _p(experts_dev), _p(counts), _p(offsets),
+                                     _p(perm), _p(inv_perm), _p(expert_order), _p(topk_w), _p(shared_dev),
+                                     _p(shared_gate), _p(y), _p(workspace),
+                                     C.c_size_t(workspace.numel() * workspace.element_size()), arr,
+                                     len(part_experts), (1 if first else 0) | (2 if last else 0)))
 
 
 # ---------------------------------------------------------------------------

@@ -71,7 +71,7 @@ extern "C" fate_status fate_moe_ffn_q_workspace(const fate_ffn_desc* d, size_t* 
     return FATE_OK;
 }
 
-static fate_status ffn_q_phase(int phase, void* stream, const fate_ffn_desc* d, const void* x_bf16,
+static fate_status ffn_q_phase(int phase, const PartSel& sel, void* stream, const fate_ffn_desc* d, const void* x_bf16,
                                       const fate_qexpert* experts_dev, const int32_t* counts,
                                       const int32_t* offsets, const int32_t* perm, const int32_t* inv_perm,
                                       const int32_t* expert_order, const float* topk_w, const fate_qexpert* shared_dev,
@@ -107,10 +107,11 @@ static fate_status ffn_q_phase(int phase, void* stream, const fate_ffn_desc* d, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int mode = d->mode ? d->mode : (d->N <= 16 ? 1 : 2);
     if (mode == 1) {
-        if (phase != 0) FATE_FAIL(FATE_EINVAL, "the decode kernels run the whole FFN only (phase = %d)", phase);
+        if (phase != 0 || !sel.first || !sel.last || ~sel.mask[0] || ~sel.mask[1] || ~sel.mask[2] || ~sel.mask[3])
+            FATE_FAIL(FATE_EINVAL, "the decode kernels run the whole FFN only (no phases, no pieces)");
         return launch_ffn_decode(st, *d, a, y);
     }
-    return launch_ffn_mfma(st, *d, a, w.ms, y, phase);
+    return launch_ffn_mfma(st, *d, a, w.ms, y, phase, sel);
 }
 
 extern "C" fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, const void* x_bf16,
@@ -119,7 +120,26 @@ extern "C" fate_status fate_moe_ffn_q(void* stream, const fate_ffn_desc* d, cons
                                       const int32_t* expert_order, const float* topk_w, const fate_qexpert* shared_dev,
                                       const void* shared_gate_bf16, void* y, void* workspace,
                                       size_t workspace_bytes) {
-    return ffn_q_phase(0, stream, d, x_bf16, experts_dev, counts, offsets, perm, inv_perm, expert_order, topk_w,
+    return ffn_q_phase(0, part_all(), stream, d, x_bf16, experts_dev, counts, offsets, perm, inv_perm, expert_order,
+                       topk_w, shared_dev, shared_gate_bf16, y, workspace, workspace_bytes);
+}
+
+extern "C" fate_status fate_moe_ffn_q_part(void* stream, const fate_ffn_desc* d, const void* x_bf16,
+                                           const fate_qexpert* experts_dev, const int32_t* counts,
+                                           const int32_t* offsets, const int32_t* perm, const int32_t* inv_perm,
+                                           const int32_t* expert_order, const float* topk_w,
+                                           const fate_qexpert* shared_dev, const void* shared_gate_bf16, void* y,
+                                           void* workspace, size_t workspace_bytes, const int32_t* part_experts,
+                                           int n_part, int flags) {
+    if (n_part < 0 || (n_part > 0 && part_experts == nullptr) || (flags & ~3))
+        FATE_FAIL(FATE_EINVAL, "fate_moe_ffn_q_part: n_part = %d, flags = %d", n_part, flags);
+    PartSel sel{{0, 0, 0, 0}, (flags & 1) != 0, (flags & 2) != 0};
+    for (int i = 0; i < n_part; ++i) {
+        const int e = part_experts[i];
+        if (d == nullptr || e < 0 || e >= d->E) FATE_FAIL(FATE_EINVAL, "part_experts[%d] = %d out of range", i, e);
+        sel.mask[e >> 6] |= 1ull << (e & 63);
+    }
+    return ffn_q_phase(0, sel, stream, d, x_bf16, experts_dev, counts, offsets, perm, inv_perm, expert_order, topk_w,
                        shared_dev, shared_gate_bf16, y, workspace, workspace_bytes);
 }
 
@@ -131,7 +151,7 @@ extern "C" fate_status fate_profile_ffn_mfma_phase(void* stream, const fate_ffn_
                                                    const fate_qexpert* shared_dev, const void* shared_gate_bf16,
                                                    void* y, void* workspace, size_t workspace_bytes) {
     if (phase != 1 && phase != 2) FATE_FAIL(FATE_EINVAL, "phase = %d (1 = up half, 2 = down half)", phase);
-    return ffn_q_phase(phase, stream, d, x_bf16, experts_dev, counts, offsets, perm, inv_perm, expert_order, topk_w,
+    return ffn_q_phase(phase, part_all(), stream, d, x_bf16, experts_dev, counts, offsets, perm, inv_perm, expert_order, topk_w,
                        shared_dev, shared_gate_bf16, y, workspace, workspace_bytes);
 }
 

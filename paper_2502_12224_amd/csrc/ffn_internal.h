@@ -48,8 +48,16 @@ struct FfnWorkspace {
 };
 
 fate_status launch_ffn_decode(hipStream_t st, const fate_ffn_desc& d, DecodeArgs a, void* y_out);
+// Piece of a layer (matrix-core path): the routed experts of `mask` (bit e), the shared experts and
+// the preparation of x with the first piece, the per-token combination with the last one.
+struct PartSel {
+    unsigned long long mask[4];
+    int first, last;
+};
+inline PartSel part_all() { return PartSel{{~0ull, ~0ull, ~0ull, ~0ull}, 1, 1}; }
+
 // phase: 0 = whole FFN, 1 = prep + up/gate GEMM only, 2 = down GEMM + combine only (timing aid)
 fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs a, const MfmaScratch& ms,
-                            void* y_out, int phase);
+                            void* y_out, int phase, const PartSel& sel);
 
 }  // namespace fate

@@ -73,10 +73,12 @@ __global__ __launch_bounds__(256) void prefill_prep_kernel(const uint16_t* __res
                                                            __half* __restrict__ xh, float* __restrict__ sgate,
                                                            int32_t* __restrict__ tab_up,
                                                            int32_t* __restrict__ tab_down, int nb_r_up,
-                                                           int nb_s_up, int nb_r_down, int nb_s_down) {
+                                                           int nb_s_up, int nb_r_down, int nb_s_down, PartSel sel) {
     __shared__ float red[4];
     const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nvec = H >> 3;
+    // (a later piece of a layer processed in pieces finds x and the gate values in place: only the tables change)
+    if (sel.first) {
     const uint4* xr = reinterpret_cast<const uint4*>(x) + (size_t)t * nvec;
     uint4* xo = reinterpret_cast<uint4*>(xh) + (size_t)t * nvec;
     const uint4* gv = reinterpret_cast<const uint4*>(shared_gate);
@@ -107,6 +109,7 @@ __global__ __launch_bounds__(256) void prefill_prep_kernel(const uint16_t* __res
         __syncthreads();
         if (tid == 0) sgate[t] = 1.0f / (1.0f + expf(-((red[0] + red[1]) + (red[2] + red[3]))));
     }
+    }
     if (t == 0 && wave == 0) {
         // tile tables: exclusive prefix sums over the segments, 64 segments per step of one wave
         const int nseg = E + n_shared;
@@ -115,7 +118,9 @@ __global__ __launch_bounds__(256) void prefill_prep_kernel(const uint16_t* __res
             const int s = s0 + lane;
             int cu = 0, cd = 0;
             if (s < nseg) {
-                const int T = s < E ? offsets[s + 1] - offsets[s] : N;
+                // a piece holds the routed experts of its mask; the shared experts go with the first piece
+                const bool mine = s < E ? ((sel.mask[s >> 6] >> (s & 63)) & 1ull) != 0 : sel.first != 0;
+                const int T = !mine ? 0 : (s < E ? offsets[s + 1] - offsets[s] : N);
                 cu = ((T + kBMUp - 1) / kBMUp) * (s < E ? nb_r_up : nb_s_up);
                 cd = ((T + kBMDown - 1) / kBMDown) * (s < E ? nb_r_down : nb_s_down);
             }
@@ -478,7 +483,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const __half* __restrict__
 }
 
 fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs da, const MfmaScratch& ms,
-                            void* y_out, int phase) {
+                            void* y_out, int phase, const PartSel& sel) {
     if (d.H % kKC || d.I_max % kKC || (d.n_shared && d.I_shared_max % kKC))
         FATE_FAIL(FATE_ESHAPE, "the MFMA path needs H and I to be multiples of %d", kKC);
     const int P = d.N * d.k;
@@ -493,9 +498,9 @@ fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs d
     const bool do_up = phase != 2, do_down = phase != 1;
     (void)nseg;
     if (do_up) {
-        prefill_prep_kernel<<<d.N, 256, 0, st>>>(da.x, d.N, d.H, d.E, d.n_shared, da.offsets, da.shared_gate,
-                                                  ms.xh, ms.sgate, ms.tab_up, ms.tab_down, nb_r_up, nb_s_up,
-                                                  nb_down, nb_down);
+        prefill_prep_kernel<<<sel.first ? d.N : 1, 256, 0, st>>>(da.x, d.N, d.H, d.E, d.n_shared, da.offsets,
+                                                                 da.shared_gate, ms.xh, ms.sgate, ms.tab_up, ms.tab_down,
+                                                                 nb_r_up, nb_s_up, nb_down, nb_down, sel);
         FATE_HIP(hipGetLastError());
     }
     // upper bounds of the routed row blocks, and the shared experts' row blocks, per GEMM
@@ -524,7 +529,8 @@ fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs d
         if (grid > 0x7fffffffLL) FATE_FAIL(FATE_ESHAPE, "too many tiles");
         grouped_gemm_kernel<1><<<(unsigned)grid, 256, 0, st>>>(g);
         FATE_HIP(hipGetLastError());
-        combine_kernel<<<d.N, 256, 0, st>>>(ms.yp_r, ms.yp_s, da.inv_perm, da.topk_w,
+        if (sel.last)
+            combine_kernel<<<d.N, 256, 0, st>>>(ms.yp_r, ms.yp_s, da.inv_perm, da.topk_w,
                                             da.shared_gate ? ms.sgate : nullptr, d.N, d.H, d.k, d.n_shared,
                                             d.y_is_fp32 ? static_cast<float*>(y_out) : nullptr,
                                             d.y_is_fp32 ? nullptr : static_cast<uint16_t*>(y_out));

@@ -154,6 +154,10 @@ class OffloadedStack:
         both widths live in host memory); set_low_percent() then switches the hybrid transfer width on."""
         self.cfg, self.device = cfg, device
         self.predictor = predictor
+        # >0: a prefill layer's FFN runs in pieces that follow the cache step's compute order - experts
+        # found in the cache first (with the shared experts), then the prefetched and the demand-loaded
+        # ones `overlap_piece` at a time, each piece waiting only for its own transfers
+        self.overlap_piece = 0
         self.nl = cfg.layers if layers is None else layers
         L, E = self.nl, cfg.E
         lib = B.lib()
@@ -242,6 +246,7 @@ class OffloadedStack:
                           evicted=0)
         self.trace = []          # per step: (layer, compute_order, loads) for checks against the oracle
         self.trace_bits = []     # per step: the width of every load
+        self.piece_log = []      # overlapped prefill: (layer, [experts of each piece])
         self.keep_trace = False
         self._h_counts = torch.zeros(2, E, dtype=torch.int32).pin_memory()
         self._h_ids = torch.zeros(4096 * cfg.k, dtype=torch.int32).pin_memory()
@@ -305,7 +310,12 @@ class OffloadedStack:
                                                   self._order, self._slots, C.byref(self._nact), self._loads, 512,
                                                   C.byref(st)))
         n = self._nact.value
-        B._check(lib.fate_hip_engine_wait_ready(self.engine, self._slots, n))
+        pieces = None
+        if self.overlap_piece > 0 and buf.desc.mode == 2 or (self.overlap_piece > 0 and buf.desc.mode == 0 and x.shape[0] > 16):
+            nc = st.n_hit_cache
+            pieces = [(0, nc)] + [(i, min(n, i + self.overlap_piece)) for i in range(nc, n, self.overlap_piece)]
+        else:
+            B._check(lib.fate_hip_engine_wait_ready(self.engine, self._slots, n))
         s = self.stats
         s["hit_cache"] += st.n_hit_cache; s["hit_prefetch"] += st.n_hit_prefetch; s["miss"] += st.n_miss
         s["pair_hits"] += st.pair_hits; s["pair_misses"] += st.pair_misses; s["prefetch"] += st.n_prefetch_issued
@@ -314,8 +324,18 @@ class OffloadedStack:
             self.trace.append((l, list(self._order[:n]), [(ld.layer, ld.expert, ld.slot, bool(ld.demand))
                                                           for ld in self._loads[:min(st.n_loads, 512)]]))
             self.trace_bits.append([ld.bits for ld in self._loads[:min(st.n_loads, 512)]])
-        B.fate_moe_ffn_q(buf.desc, x, self.table_for(l), buf.counts, buf.offsets, buf.perm, buf.inv_perm, buf.order,
-                         buf.w, self.shared_tables[l], self.shared_gates[l], buf.y, buf.ffn_ws)
+        if pieces is None:
+            B.fate_moe_ffn_q(buf.desc, x, self.table_for(l), buf.counts, buf.offsets, buf.perm, buf.inv_perm, buf.order,
+                             buf.w, self.shared_tables[l], self.shared_gates[l], buf.y, buf.ffn_ws)
+        else:
+            self.piece_log.append((l, [list(self._order[a:b]) for a, b in pieces]))
+            for i, (a, b) in enumerate(pieces):
+                if b > a:
+                    sl = (C.c_int32 * (b - a))(*self._slots[a:b])
+                    B._check(lib.fate_hip_engine_wait_ready(self.engine, sl, b - a))
+                B.fate_moe_ffn_q_part(buf.desc, x, self.table_for(l), buf.counts, buf.offsets, buf.perm, buf.inv_perm,
+                                      buf.order, buf.w, self.shared_tables[l], self.shared_gates[l], buf.y, buf.ffn_ws,
+                                      list(self._order[a:b]), first=i == 0, last=i == len(pieces) - 1)
         self.done_event.record()
         self.have_done = True
         return buf.y

@@ -226,3 +226,57 @@ def test_offloaded_prefill_with_hybrid_transfer_width():
         h = chain_next_hidden(h, y)
     assert n_low > 0 and off.bytes_copied() == bytes_expected
     off.close()
+
+
+def test_prefill_compute_follows_the_order_of_the_transfers():
+    """Section 4.3, figure "rearranging the order of expert computations": experts 2 and 4 are already on
+    the device, 3, 1 and 5 are being loaded in that order; the computation runs 2, 4 first and then 3, 1, 5
+    as they arrive.  Here on the device path: a layer whose cache holds {2, 4}, tokens routed so that the
+    demand loads come out in the order 3, 1, 5, the FFN taken in pieces of one expert."""
+    from oracle import moe as O
+    from helpers import f32, ffn_rel_err, oracle_expert, gpu_permute
+    from workloads import gen_expert
+    cfg = dataclasses.replace(SHAPES["tiny"], name="tiny1", layers=1, E=8, k=1, bits=4, group=128)
+    E, N = cfg.E, 40
+    # the cache preloads experts 0 .. c-1, so the figure's expert ids are renamed: cached {0, 1} play {2, 4},
+    # and the loads 5, 3, 7 (by decreasing token count) play 3, 1, 5
+    off = OffloadedStack(cfg, cache_total=2, n_max=0, staging_slots=2 * E, device=DEV, layers=1, L_shallow=0)
+    off.overlap_piece = 1
+    off.keep_trace = True
+    assert off.caps == [2]
+    x = gen_hidden(cfg, N, device=DEV)
+    ids = torch.tensor([[0]] * 6 + [[1]] * 5 + [[5]] * 12 + [[3]] * 9 + [[7]] * 8, dtype=torch.int32, device=DEV)
+    w = torch.rand(N, 1, device=DEV) + 0.5
+    # drive the stack's layer call with a fixed routing: the routing entry points are replaced by copies
+    buf = LayerBuffers(cfg, N, DEV, mode=2)
+    import paper_2502_12224_amd.binding as B
+    assert not buf.fused_ok              # 40 tokens: the stack calls fate_gate_route and fate_permute
+    real = B.fate_gate_route
+
+    def fixed(xx, Wg, bias, k, renorm, oid, ow, probs, stream=None):
+        oid.copy_(ids)
+        ow.copy_(w)
+    B.fate_gate_route = fixed
+    try:
+        y = off.layer(0, x, buf).clone()
+    finally:
+        B.fate_gate_route = real
+    torch.cuda.synchronize()
+    assert int(buf.ffn_ws[:4].view(torch.int32)[0]) == 0
+    tl, order, loads = off.trace[-1]
+    assert order == [0, 1, 5, 3, 7]                                   # on the device first, then in load order
+    assert [(e, d) for (_, e, _, d) in loads] == [(5, True), (3, True), (7, True)]
+    assert off.piece_log[-1] == (0, [[0, 1], [5], [3], [7]])
+    sim = OC.CacheOracle(1, E, 2, 0, 0, 2 * E)
+    r = sim.step(0, [0, 1, 3, 5, 7], [6, 5, 9, 12, 8])
+    assert r.compute_order == order and r.loads == loads
+    experts = {e: oracle_expert(gen_expert(cfg, 0, e, device=DEV)) for e in (0, 1, 3, 5, 7)}
+    y_ref = O.moe_ffn_grouped(f32(x), ids.cpu().numpy(), w.cpu().numpy().astype(np.float64), experts)
+    assert ffn_rel_err(f32(y), y_ref).max() <= 2e-3
+    # the pieces add up to exactly what one call gives
+    g = gpu_permute(ids, E)
+    y_one = torch.empty_like(y)
+    B.fate_moe_ffn_q(buf.desc, x, off.table_for(0), *g, w, None, None, y_one, buf.ffn_ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y_one, y)
+    off.close()
