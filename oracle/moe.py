@@ -212,10 +212,100 @@ def pack_codes(q, bits):
     return (u[:, 0::2] | (u[:, 1::2] << 4)).astype(np.uint8)
 
 
-class OracleExpert:
-    """Dequantised fp64 matrices of one SwiGLU expert."""
+# -- asymmetric (zero-point) group format: what HQQ, the quantiser the paper uses (section 4.5), produces --
 
-    def __init__(self, w1, s1, w3, s3, w2, s2, bits, group):
+
+def unpack_fields(codes_u8, bits):
+    """Canonical stored bytes -> the unsigned fields u in [0, 2^bits) [rows, K] (int32): the nibble
+    (int4), the 2-bit field (int2) or the byte (int8) as stored by the asymmetric quantiser."""
+    c = np.asarray(codes_u8, dtype=np.uint8)
+    if bits == 8:
+        return c.astype(np.int32)
+    per = 8 // bits
+    rows, nb = c.shape
+    u = np.empty((rows, nb * per), dtype=np.int32)
+    for i in range(per):
+        u[:, i::per] = (c >> (bits * i)) & ((1 << bits) - 1)
+    return u
+
+
+def pack_fields(u, bits):
+    """Inverse of unpack_fields."""
+    u = np.asarray(u, dtype=np.int32)
+    if bits == 8:
+        return u.astype(np.uint8)
+    per = 8 // bits
+    out = np.zeros((u.shape[0], u.shape[1] // per), dtype=np.uint8)
+    for i in range(per):
+        out |= (u[:, i::per] << (bits * i)).astype(np.uint8)
+    return out
+
+
+def dequant_zp(codes_u8, scales_f16, zeros_f16, bits, group):
+    """w[r, c] = (u[r, c] - z[r, c // group]) * s[r, c // group] in fp64, u the stored unsigned field,
+    s and z one fp16 value per group."""
+    u = unpack_fields(codes_u8, bits).astype(np.float64)
+    s = np.repeat(np.asarray(scales_f16, dtype=np.float16).astype(np.float64), group, axis=1)
+    z = np.repeat(np.asarray(zeros_f16, dtype=np.float16).astype(np.float64), group, axis=1)
+    assert s.shape == u.shape == z.shape
+    return (u - z) * s
+
+
+def _shrink_lp(x, beta, p):
+    """Generalised soft threshold of the half-quadratic solver: sign(x) * max(|x| - |x|^(p-1) / beta, 0)."""
+    ax = np.abs(x)
+    with np.errstate(divide="ignore"):
+        t = np.where(ax > 0, ax ** (p - 1.0) / beta, 0.0)
+    return np.sign(x) * np.maximum(ax - t, 0.0)
+
+
+def quantize_asym(w, bits, group, hqq_iters=0, p=0.7, beta=10.0, kappa=1.01):
+    """Asymmetric group quantiser: per group s = fp16((max - min) / (2^bits - 1)) (1 for a constant
+    group) and zero-point z = fp16(-min / s), u = clamp(round-half-even(w / s + z), 0, 2^bits - 1).
+    hqq_iters > 0 refines the zero-point the way Half-Quadratic Quantization (Badri & Shaji, 2023)
+    does, with the scale kept fixed: alternate the l_p shrinkage of the residual with the closed-form
+    zero-point z = mean(u - (w - e) / s), beta growing by kappa per step; the best zero-point seen (mean
+    |residual|) is kept.  Returns (fields int32 [rows, K], scales fp16, zeros fp16)."""
+    w = np.asarray(w, dtype=np.float64)
+    rows, K = w.shape
+    qmax = (1 << bits) - 1
+    wg = w.reshape(rows, K // group, group)
+    lo, hi = wg.min(axis=-1), wg.max(axis=-1)
+    s = ((hi - lo) / qmax).astype(np.float16)
+    s = np.where(s == 0, np.float16(1.0), s)
+    sd = s.astype(np.float64)[..., None]
+    z = (-lo[..., None] / sd)
+
+    def fields(zz):
+        return np.clip(np.rint(wg / sd + zz), 0, qmax)
+
+    if hqq_iters > 0:
+        best_z, best_err = z.copy(), np.abs(wg - (fields(z) - z) * sd).mean(axis=-1, keepdims=True)
+        b = beta
+        for _ in range(hqq_iters):
+            u = fields(z)
+            e = _shrink_lp(wg - (u - z) * sd, b, p)
+            z = (u - (wg - e) / sd).mean(axis=-1, keepdims=True)
+            b *= kappa
+            err = np.abs(wg - (fields(z) - z) * sd).mean(axis=-1, keepdims=True)
+            better = err < best_err
+            best_z = np.where(better, z, best_z)
+            best_err = np.where(better, err, best_err)
+        z = best_z
+    z16 = z[..., 0].astype(np.float16)
+    u = np.clip(np.rint(wg / sd + z16.astype(np.float64)[..., None]), 0, qmax).astype(np.int32)
+    return u.reshape(rows, K), s, z16
+
+
+class OracleExpert:
+    """Dequantised fp64 matrices of one SwiGLU expert (zero-points z1, z3, z2 given: the asymmetric format)."""
+
+    def __init__(self, w1, s1, w3, s3, w2, s2, bits, group, z1=None, z3=None, z2=None):
+        if z1 is not None:
+            self.W1 = dequant_zp(w1, s1, z1, bits, group)
+            self.W3 = dequant_zp(w3, s3, z3, bits, group)
+            self.W2 = dequant_zp(w2, s2, z2, bits, group)
+            return
         self.W1 = dequant(w1, s1, bits, group)   # [I, H]
         self.W3 = dequant(w3, s3, bits, group)   # [I, H]
         self.W2 = dequant(w2, s2, bits, group)   # [H, I]

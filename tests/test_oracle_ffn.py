@@ -233,3 +233,67 @@ def test_int2_round_trip_and_error_bound():
     q4, s4 = O.quantize_sym(w, 4, group)
     d4 = O.dequant(O.pack_codes(q4, 4), s4, 4, group)
     assert np.abs(w - d4).mean() < np.abs(w - d).mean() < np.abs(w).mean()
+
+
+def test_zero_point_format_hand_worked_group():
+    """The asymmetric format of the paper's quantiser (HQQ, section 4.5): one row, one group of 4, int4.
+    min = -0.1, max = 0.5 -> s = fp16(0.6 / 15) = fp16(0.04), z = fp16(0.1 / s)."""
+    w = np.array([[-0.1, 0.5, 0.0, 0.21]])
+    u, s, z = O.quantize_asym(w, 4, 4)
+    s0 = np.float16(0.6 / 15)
+    z0 = np.float16(0.1 / float(s0))
+    assert s[0, 0] == s0 and z[0, 0] == z0 and 2.4 < float(z0) < 2.6
+    # fields: -0.1 / s + z = 0 ; 0.5 / s + z = 15.0 ; 0 -> z = 2.5 (ties to even: 2) ; 0.21 / 0.04 + 2.5 = 7.75 -> 8
+    assert u.tolist() == [[0, 15, round(float(z0)), 8]]
+    packed = O.pack_fields(u, 4)
+    assert packed.tolist() == [[0xF0, 0x80 | round(float(z0))]]
+    assert np.array_equal(O.unpack_fields(packed, 4), u)
+    d = O.dequant_zp(packed, s, z, 4, 4)
+    assert d[0, 1] == (15 - float(z0)) * float(s0) and d[0, 0] == (0 - float(z0)) * float(s0)
+    # the symmetric formats are the special case z = 8 (int4) / 128 (int8, offset binary) / 1.5 with twice the scale (int2)
+    rng = np.random.default_rng(0)
+    w2 = rng.normal(size=(4, 256)) * 0.02
+    for bits, zsym, smul in ((4, 8.0, 1.0), (8, 128.0, 1.0), (2, 1.5, 2.0)):
+        q, ss = O.quantize_sym(w2, bits, 128)
+        ufield = O.unpack_fields(O.pack_codes(q, bits) if bits != 8 else (q + 128).astype(np.uint8), bits)
+        dz = O.dequant_zp(O.pack_fields(ufield, bits), (ss.astype(np.float64) * smul).astype(np.float16),
+                          np.full(ss.shape, zsym, np.float16), bits, 128)
+        assert np.array_equal(dz, O.dequant(O.pack_codes(q, bits), ss, bits, 128))
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_zero_point_quantiser_error_bounds_and_refinement(bits):
+    rng = np.random.default_rng(bits)
+    group = 128
+    w = rng.normal(size=(24, 3 * group)) * 0.02 + 0.01          # off-centre: where a zero-point pays
+    w[2, :group] = 0.37                                         # a constant group
+    u, s, z = O.quantize_asym(w, bits, group)
+    qmax = (1 << bits) - 1
+    assert u.min() >= 0 and u.max() <= qmax
+    d = O.dequant_zp(O.pack_fields(u, bits), s, z, bits, group)
+    sfull = np.repeat(s.astype(np.float64), group, axis=1)
+    # nearest level of a grid that covers [min, max] up to the fp16 rounding of s and z
+    assert (np.abs(w - d) <= sfull * (0.5 + qmax * 2.0 ** -10) + 1e-12).all()
+    assert s[2, 0] == np.float16(1.0) and np.abs(d[2, :group] - 0.37).max() <= 0.5
+    # asymmetric beats symmetric on off-centre weights at the same width
+    q, ss = O.quantize_sym(w, bits, group)
+    dsym = O.dequant(O.pack_codes(q, bits), ss, bits, group)
+    assert np.abs(w - d)[3:].mean() < np.abs(w - dsym)[3:].mean()
+    # the half-quadratic refinement of the zero-point never loses against its starting point (it keeps the best)
+    u2, s2, z2 = O.quantize_asym(w, bits, group, hqq_iters=20)
+    d2 = O.dequant_zp(O.pack_fields(u2, bits), s2, z2, bits, group)
+    assert np.array_equal(s2, s)
+    e1 = np.abs(w - d).reshape(24, 3, group).mean(-1)
+    e2 = np.abs(w - d2).reshape(24, 3, group).mean(-1)
+    assert (e2 <= e1 * 1.02 + 1e-9).all() and e2.mean() <= e1.mean()
+
+
+def test_shrinkage_operator_of_the_half_quadratic_solver():
+    x = np.array([-2.0, -0.01, 0.0, 0.01, 0.5, 3.0])
+    y = O._shrink_lp(x, beta=10.0, p=0.7)
+    # |x| - |x|^(p-1)/beta, clipped at zero, sign kept: small entries vanish, large ones barely move
+    assert y[2] == 0 and y[1] == 0 and y[3] == 0
+    assert np.isclose(y[5], 3.0 - 3.0 ** (-0.3) / 10) and np.isclose(y[0], -(2.0 - 2.0 ** (-0.3) / 10))
+    assert np.isclose(y[4], 0.5 - 0.5 ** (-0.3) / 10)
+    # p = 1 is the ordinary soft threshold
+    assert np.allclose(O._shrink_lp(x, 4.0, 1.0), np.sign(x) * np.maximum(np.abs(x) - 0.25, 0))
