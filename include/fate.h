@@ -118,7 +118,8 @@ fate_status fate_route_fused(void* stream, const void* x_bf16, const void* Wg_bf
  * Canonical stored form (what a quantiser produces; paper section 4.5 stores
  * experts as low-bit integers and dequantises before compute): symmetric
  * codes q with one fp16 scale per `group` consecutive elements along the
- * reduction dimension of an output row, w = q*s.
+ * reduction dimension of an output row, w = q*s; optionally one fp16
+ * zero-point per group as well (see fate_qexpert), w = (u - z)*s.
  *   int8: two's-complement bytes [rows,K];  int4: nibble u = q+8, two per
  *   byte, low nibble = even column, [rows,K/2];  scales fp16 [rows,K/group].
  *   int2 (the low-precision copy of section 4.5): field u in 0..3, four per
@@ -152,7 +153,18 @@ typedef struct {
     int32_t group;  /* multiple of 64 */
     int32_t I;      /* intermediate size, multiple of 64 */
     int32_t reserved;
-} fate_qexpert;
+    /* fp16 zero-points per group, laid out like the scales (group-major), or NULL for the symmetric
+     * formats.  With zero-points w = (u - z) * s on the stored unsigned field u (the int4 nibble or the
+     * int2 field; z any fp16 value, usually in [0, 2^bits - 1]): the asymmetric format of the quantiser the
+     * paper uses (HQQ, section 4.5).  All three NULL or all three set; bits must be 4 or 2 (an 8-bit entry
+     * with zero-points raises status bit 2 and contributes nothing).  fate_moe_ffn_q and
+     * fate_moe_ffn_q_part read them in both of their modes; the one-call decode layer takes symmetric
+     * entries only (others count as not resident: status bit 0). */
+    const void* z1;
+    const void* z3;
+    const void* z2;
+    int64_t reserved2;
+} fate_qexpert;   /* 96 bytes */
 
 /* ------------------------------------------------------------------------
  * Grouped SwiGLU FFN over quantised experts, dequantised in-kernel (paper

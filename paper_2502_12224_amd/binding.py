@@ -47,7 +47,8 @@ class fate_ffn_desc(C.Structure):
 class fate_qexpert(C.Structure):
     _fields_ = [("w1", C.c_void_p), ("w3", C.c_void_p), ("w2", C.c_void_p), ("s1", C.c_void_p),
                 ("s3", C.c_void_p), ("s2", C.c_void_p), ("bits", C.c_int32), ("group", C.c_int32),
-                ("I", C.c_int32), ("reserved", C.c_int32)]
+                ("I", C.c_int32), ("reserved", C.c_int32), ("z1", C.c_void_p), ("z3", C.c_void_p),
+                ("z2", C.c_void_p), ("reserved2", C.c_int64)]
 
 
 class fate_cache_stats(C.Structure):
@@ -271,7 +272,11 @@ class PackedExpert:
             dst = torch.empty_like(src)
             fate_pack_weight(src, rows, K, ex.bits, dst)
             self.t[name] = dst
-        for name, rows, K in (("s1", ex.I, ex.H), ("s3", ex.I, ex.H), ("s2", ex.H, ex.I)):
+        names = [("s1", ex.I, ex.H), ("s3", ex.I, ex.H), ("s2", ex.H, ex.I)]
+        self.has_zero = getattr(ex, "z1", None) is not None
+        if self.has_zero:                       # zero-points travel like scales (fp16 per group, group-major)
+            names += [("z1", ex.I, ex.H), ("z3", ex.I, ex.H), ("z2", ex.H, ex.I)]
+        for name, rows, K in names:
             src = getattr(ex, name).to(device).contiguous()
             dst = torch.empty_like(src).view(K // ex.group, rows)
             fate_pack_scales(src, rows, K // ex.group, dst)
@@ -280,8 +285,9 @@ class PackedExpert:
 
     def struct(self):
         t = self.t
+        z = [t[n].data_ptr() for n in ("z1", "z3", "z2")] if self.has_zero else [None, None, None]
         return fate_qexpert(t["w1"].data_ptr(), t["w3"].data_ptr(), t["w2"].data_ptr(), t["s1"].data_ptr(),
-                            t["s3"].data_ptr(), t["s2"].data_ptr(), self.bits, self.group, self.I, 0)
+                            t["s3"].data_ptr(), t["s2"].data_ptr(), self.bits, self.group, self.I, 0, *z, 0)
 
     def nbytes(self):
         return sum(v.numel() * v.element_size() for v in self.t.values())

@@ -44,6 +44,7 @@ static fate_qexpert entry_for(const fate_hip_engine* g, int slot, const fate_slo
     q.w1 = b + lay.off_w1; q.w3 = b + lay.off_w3; q.w2 = b + lay.off_w2;
     q.s1 = b + lay.off_s1; q.s3 = b + lay.off_s3; q.s2 = b + lay.off_s2;
     q.bits = lay.bits; q.group = lay.group; q.I = lay.I; q.reserved = 0;
+    q.z1 = q.z3 = q.z2 = nullptr; q.reserved2 = 0;      // the pools hold symmetric copies
     return q;
 }
 

@@ -63,17 +63,53 @@ __device__ __forceinline__ uint4 bf16x8_to_f16x8(const uint4& v) {
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
 
-template <int NMAT, int D, int TPG>
+template <int NMAT, int D, int TPG, bool ZP = false>
 struct TileRing {
     uint4 raw[NMAT][D];
     uint32_t sc[NMAT][D / TPG];   // fp16 bits of the group scale, one full register each
+    uint32_t zr[NMAT][ZP ? D / TPG : 1];   // fp16 bits of the group zero-point (formats that have one)
 };
 
+// Zero-points, w = (u - z) * s: the matrix cores see the same symmetric codes q = a*u - c as
+// without them, and the difference is one term per group,
+//   sum_k (u_k - z) x_k = (sum_k q_k x_k + (c - a z) sum_k x_k) / a,
+// with the group sums of the activations taken once per staged row.
+template <int BITS> struct ZpFmt;
+template <> struct ZpFmt<4> { static constexpr float inv_a = 1.0f, c_over_a = 8.0f; };     // q = u - 8
+template <> struct ZpFmt<2> { static constexpr float inv_a = 0.5f, c_over_a = 1.5f; };     // q = 2u - 3
+template <> struct ZpFmt<8> { static constexpr float inv_a = 1.0f, c_over_a = 128.0f; };   // not instantiated with zero-points
+
+constexpr int kZpMaxGroups = 128;   // groups per staged activation row the zero-point path keeps sums for
+
+// gs[t * G + g] = sum over group g of row t of the activations staged in LDS (fp16, row stride
+// ldx halves); the whole workgroup calls it (256 threads), a quarter group per lane
+__device__ __forceinline__ void stage_group_sums(const _Float16* xs, int ldx, int nt, int G, int group, float* gs) {
+    const int tid = threadIdx.x;
+    const int lim = nt * G * 4, q = group >> 2;
+    for (int base = 0; base < lim; base += 256) {
+        const int idx = base + tid;
+        float s = 0.f;
+        if (idx < lim) {
+            const int tg = idx >> 2, t = tg / G, g = tg - t * G;
+            const _Float16* p = xs + t * ldx + g * group + (idx & 3) * q;
+            for (int c = 0; c < q; c += 8) {
+                const f16x8_t v = *reinterpret_cast<const f16x8_t*>(p + c);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s += (float)v[e];
+            }
+        }
+        s += __shfl_xor(s, 1);
+        s += __shfl_xor(s, 2);
+        if (idx < lim && (idx & 3) == 0) gs[idx >> 2] = s;
+    }
+}
+
 // request the first D tiles of the groups [g_beg, g_end) (TPG tiles per group).
-// sc[i]: this lane's row in the group-major scale array, srows = its row count.
-template <int NMAT, int D, int TPG>
-__device__ __forceinline__ void ring_start(TileRing<NMAT, D, TPG>& r, const gu4_t* wt, const gu16_t* sc,
-                                           int srows, int g_beg, int g_end) {
+// sc[i]: this lane's row in the group-major scale array, srows = its row count;
+// zp[i]: the same for the zero-points (read only if ZP).
+template <int NMAT, int D, int TPG, bool ZP = false>
+__device__ __forceinline__ void ring_start(TileRing<NMAT, D, TPG, ZP>& r, const gu4_t* wt, const gu16_t* sc,
+                                           int srows, int g_beg, int g_end, const gu16_t* zp = nullptr) {
     const int tbeg = g_beg * TPG, tend = g_end * TPG;
 #pragma unroll
     for (int j = 0; j < D; ++j) {
@@ -81,7 +117,10 @@ __device__ __forceinline__ void ring_start(TileRing<NMAT, D, TPG>& r, const gu4_
 #pragma unroll
             for (int i = 0; i < NMAT; ++i) {
                 r.raw[i][j] = wt[i][(size_t)(tbeg + j) * 64];
-                if (j % TPG == 0) r.sc[i][j / TPG] = sc[i][(size_t)(g_beg + j / TPG) * srows];
+                if (j % TPG == 0) {
+                    r.sc[i][j / TPG] = sc[i][(size_t)(g_beg + j / TPG) * srows];
+                    if constexpr (ZP) r.zr[i][j / TPG] = zp[i][(size_t)(g_beg + j / TPG) * srows];
+                }
             }
         }
     }
@@ -92,11 +131,13 @@ __device__ __forceinline__ void ring_start(TileRing<NMAT, D, TPG>& r, const gu4_
 // ring_start must have been called with the same range.  xa: this lane's
 // activation row in LDS (fp16), already offset by its half of a tile; its
 // column 0 is absolute column k_base.  out[i][j]: row n of matrix i, token
-// 4*half + j.
-template <int BITS, int TPG, int NMAT, int D>
-__device__ __forceinline__ void ring_run(TileRing<NMAT, D, TPG>& r, const gu4_t* wt, const gu16_t* sc,
+// 4*half + j.  With ZP: zp as in ring_start, gs = the group sums of this lane's first token
+// (token 4*half), rows gs_ld floats apart, its entry 0 being group g_off.
+template <int BITS, int TPG, int NMAT, int D, bool ZP = false>
+__device__ __forceinline__ void ring_run(TileRing<NMAT, D, TPG, ZP>& r, const gu4_t* wt, const gu16_t* sc,
                                          int srows, int g_beg, int g_end, const _Float16* xa, int k_base,
-                                         float (&out)[NMAT][4]) {
+                                         float (&out)[NMAT][4], const gu16_t* zp = nullptr,
+                                         const float* gs = nullptr, int gs_ld = 0, int g_off = 0) {
     constexpr int KT = QFmt<BITS>::KT, S = QFmt<BITS>::MSTEPS;
     static_assert(D % TPG == 0, "ring depth must hold whole groups");
     const int tbeg = g_beg * TPG, tend = g_end * TPG;
@@ -109,10 +150,19 @@ __device__ __forceinline__ void ring_run(TileRing<NMAT, D, TPG>& r, const gu4_t*
                 float s[NMAT];
 #pragma unroll
                 for (int i = 0; i < NMAT; ++i) s[i] = half_bits_to_float(r.sc[i][jg]);
-                const int gnext = base / TPG + jg + D / TPG;
+                float dz[NMAT];
+                if constexpr (ZP) {
+#pragma unroll
+                    for (int i = 0; i < NMAT; ++i) dz[i] = ZpFmt<BITS>::c_over_a - half_bits_to_float(r.zr[i][jg]);
+                }
+                const int gcur = base / TPG + jg;
+                const int gnext = gcur + D / TPG;
                 if (gnext < g_end) {
 #pragma unroll
-                    for (int i = 0; i < NMAT; ++i) r.sc[i][jg] = sc[i][(size_t)gnext * srows];
+                    for (int i = 0; i < NMAT; ++i) {
+                        r.sc[i][jg] = sc[i][(size_t)gnext * srows];
+                        if constexpr (ZP) r.zr[i][jg] = zp[i][(size_t)gnext * srows];
+                    }
                 }
 #pragma unroll
                 for (int tl = 0; tl < TPG; ++tl) {
@@ -133,10 +183,20 @@ __device__ __forceinline__ void ring_run(TileRing<NMAT, D, TPG>& r, const gu4_t*
                                 av[st], b[st], (tl == 0 && st == 0) ? zero : acc[i], 0, 0, 0);
                     }
                 }
+                if constexpr (ZP) {
 #pragma unroll
-                for (int i = 0; i < NMAT; ++i)
+                    for (int j = 0; j < 4; ++j) {
+                        const float gsum = gs[j * gs_ld + (gcur - g_off)];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) out[i][j] = fmaf(s[i], acc[i][j], out[i][j]);
+                        for (int i = 0; i < NMAT; ++i)
+                            out[i][j] = fmaf(s[i], fmaf(ZpFmt<BITS>::inv_a, acc[i][j], dz[i] * gsum), out[i][j]);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < NMAT; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) out[i][j] = fmaf(s[i], acc[i][j], out[i][j]);
+                }
             }
         }
     }
@@ -164,6 +224,17 @@ __host__ __device__ inline int tile_columns(int bits) { return bits == 4 ? 64 : 
         else { BODY(2, 2) }                                \
     } else {                                               \
         FATE_FORMAT_SWITCH(bits, tpg, BODY)                \
+    }
+
+// formats with zero-points: 4 and 2 bits
+#define FATE_FORMAT_SWITCH_ZP(bits, tpg, BODY)             \
+    if ((bits) == 2) {                                     \
+        if ((tpg) == 1) { BODY(2, 1) }                     \
+        else { BODY(2, 2) }                                \
+    } else {                                               \
+        if ((tpg) == 2) { BODY(4, 2) }                     \
+        else if ((tpg) == 1) { BODY(4, 1) }                \
+        else { BODY(4, 4) }                                \
     }
 
 static inline bool decode_group_ok(int bits, int group) {

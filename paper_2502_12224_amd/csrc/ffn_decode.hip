@@ -20,10 +20,12 @@
 namespace fate {
 
 constexpr int kRing = 8;       // weight tiles in flight per matrix per wave
+constexpr int kZpChunkGroups = 64;   // groups of a down chunk the zero-point path keeps activation sums for
 
 __global__ __launch_bounds__(256, 2) void ffn_up_decode_kernel(DecodeArgs a) {
     extern __shared__ uint4 smem[];
     __shared__ float red[2][4][kTokPass][32];
+    __shared__ float gsum[kTokPass * kZpMaxGroups];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     int b = blockIdx.x;
     const int nrout = a.nact * a.rb_r;
@@ -59,6 +61,12 @@ __global__ __launch_bounds__(256, 2) void ffn_up_decode_kernel(DecodeArgs a) {
             if (tid == 0) atomicOr(a.status, 4);
             live = false;
         }
+        // zero-points: with the 4- and 2-bit formats, on all three matrices
+        if (live && ex->z1 != nullptr &&
+            (bits == 8 || ex->z2 == nullptr || ex->z3 == nullptr || a.H / group > kZpMaxGroups)) {
+            if (tid == 0) atomicOr(a.status, 4);
+            live = false;
+        }
         w1 = as_global<uint4>(ex->w1);
         w3 = as_global<uint4>(ex->w3);
         if (live && (w1 == nullptr || w3 == nullptr)) {
@@ -81,6 +89,9 @@ __global__ __launch_bounds__(256, 2) void ffn_up_decode_kernel(DecodeArgs a) {
     const int g_beg = G * wave / 4, g_end = G * (wave + 1) / 4;
     gu4_t wt[2] = {w1 + (size_t)rb * tiles_k * 64 + lane, w3 + (size_t)rb * tiles_k * 64 + lane};
     gu16_t sc[2] = {as_global<uint16_t>(ex->s1) + rb * 32 + n, as_global<uint16_t>(ex->s3) + rb * 32 + n};
+    const bool has_z = ex->z1 != nullptr;
+    gu16_t zp[2] = {as_global<uint16_t>(has_z ? ex->z1 : ex->s1) + rb * 32 + n,
+                    as_global<uint16_t>(has_z ? ex->z3 : ex->s3) + rb * 32 + n};
     const int srows = ex->I;
     const int ldx = H + kLdsPad;                       // halves per LDS row; the last row is all zero
     const int zrow = a.lds_rows - 1;
@@ -115,33 +126,47 @@ __global__ __launch_bounds__(256, 2) void ffn_up_decode_kernel(DecodeArgs a) {
         }
     };
 
-#define FATE_UP_BODY(BITS, TPG)                                                                          \
+#define FATE_UP_BODY_(BITS, TPG, ZP)                                                                     \
     {                                                                                                     \
-        TileRing<2, kRing, TPG> ring;                                                                     \
-        ring_start<2, kRing, TPG>(ring, wt, sc, srows, g_beg, g_end);                                            \
+        TileRing<2, kRing, TPG, ZP> ring;                                                                 \
+        ring_start<2, kRing, TPG, ZP>(ring, wt, sc, srows, g_beg, g_end, zp);                             \
         for (int t0 = 0; t0 < T; t0 += kTokPass) {                                                        \
             const int nt = min(kTokPass, T - t0);                                                         \
             if (t0 > 0) {                                                                                 \
                 __syncthreads();                                                                          \
-                ring_start<2, kRing, TPG>(ring, wt, sc, srows, g_beg, g_end);                                    \
+                ring_start<2, kRing, TPG, ZP>(ring, wt, sc, srows, g_beg, g_end, zp);                     \
             }                                                                                             \
             stage_x(nt, t0);                                                                              \
             __syncthreads();                                                                              \
+            if (ZP) {                                                                                     \
+                stage_group_sums(xs, ldx, nt, G, group, gsum);                                            \
+                __syncthreads();                                                                          \
+            }                                                                                             \
             float out[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};                               \
             const int arow = n < nt ? n : zrow;                                                           \
-            ring_run<BITS, TPG, 2, kRing>(ring, wt, sc, srows, g_beg, g_end,                                    \
-                                          xs + arow * ldx + half * (QFmt<BITS>::KT / 2), 0, out);         \
+            ring_run<BITS, TPG, 2, kRing, ZP>(ring, wt, sc, srows, g_beg, g_end,                          \
+                                              xs + arow * ldx + half * (QFmt<BITS>::KT / 2), 0, out, zp,  \
+                                              gsum + 4 * half * G, G, 0);                                 \
             finish(nt, t0, out);                                                                          \
         }                                                                                                 \
     }
-    FATE_FORMAT_SWITCH_ALL(bits, tpg, FATE_UP_BODY)
+#define FATE_UP_BODY(BITS, TPG) FATE_UP_BODY_(BITS, TPG, false)
+#define FATE_UP_BODY_Z(BITS, TPG) FATE_UP_BODY_(BITS, TPG, true)
+    if (has_z) {
+        FATE_FORMAT_SWITCH_ZP(bits, tpg, FATE_UP_BODY_Z)
+    } else {
+        FATE_FORMAT_SWITCH_ALL(bits, tpg, FATE_UP_BODY)
+    }
 #undef FATE_UP_BODY
+#undef FATE_UP_BODY_Z
+#undef FATE_UP_BODY_
 }
 
 __global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
     extern __shared__ uint4 smem[];
     __shared__ float red[4][kTokPass][32];
     __shared__ float sgate[kTokPass];
+    __shared__ float gsum[kTokPass * kZpChunkGroups];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nrb = a.H >> 5;
     int b = blockIdx.x;
@@ -183,6 +208,13 @@ __global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
     const int n = lane & 31, half = lane >> 5;
     gu4_t wt[1] = {w2 + (size_t)rb * tiles_k * 64 + lane};
     gu16_t sc[1] = {as_global<uint16_t>(ex->s2) + rb * 32 + n};
+    const bool has_z = ex->z1 != nullptr;
+    if (has_z && (bits == 8 || ex->z2 == nullptr || ex->z3 == nullptr || a.H / group > kZpMaxGroups ||
+                  ge - gb > kZpChunkGroups)) {
+        if (tid == 0) atomicOr(a.status, 4);
+        return;
+    }
+    gu16_t zp[1] = {as_global<uint16_t>(has_z ? ex->z2 : ex->s2) + rb * 32 + n};
     const int srows = a.H;
     const int ng = ge - gb;
     const int g_beg = gb + ng * wave / 4, g_end = gb + ng * (wave + 1) / 4;
@@ -230,27 +262,40 @@ __global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
         }
     };
 
-#define FATE_DOWN_BODY(BITS, TPG)                                                                         \
+#define FATE_DOWN_BODY_(BITS, TPG, ZP)                                                                   \
     {                                                                                                     \
-        TileRing<1, kRing, TPG> ring;                                                                     \
-        ring_start<1, kRing, TPG>(ring, wt, sc, srows, g_beg, g_end);                                            \
+        TileRing<1, kRing, TPG, ZP> ring;                                                                 \
+        ring_start<1, kRing, TPG, ZP>(ring, wt, sc, srows, g_beg, g_end, zp);                             \
         for (int t0 = 0; t0 < T; t0 += kTokPass) {                                                        \
             const int nt = min(kTokPass, T - t0);                                                         \
             if (t0 > 0) {                                                                                 \
                 __syncthreads();                                                                          \
-                ring_start<1, kRing, TPG>(ring, wt, sc, srows, g_beg, g_end);                                    \
+                ring_start<1, kRing, TPG, ZP>(ring, wt, sc, srows, g_beg, g_end, zp);                     \
             }                                                                                             \
             stage_h(nt, t0);                                                                              \
             __syncthreads();                                                                              \
+            if (ZP) {                                                                                     \
+                stage_group_sums(xs, ldx, nt, ng, group, gsum);                                           \
+                __syncthreads();                                                                          \
+            }                                                                                             \
             float out[1][4] = {{0.f, 0.f, 0.f, 0.f}};                                                     \
             const int arow = n < nt ? n : zrow;                                                           \
-            ring_run<BITS, TPG, 1, kRing>(ring, wt, sc, srows, g_beg, g_end,                                    \
-                                          xs + arow * ldx + half * (QFmt<BITS>::KT / 2), k_base, out);    \
+            ring_run<BITS, TPG, 1, kRing, ZP>(ring, wt, sc, srows, g_beg, g_end,                          \
+                                              xs + arow * ldx + half * (QFmt<BITS>::KT / 2), k_base, out, \
+                                              zp, gsum + 4 * half * ng, ng, gb);                          \
             finish(nt, t0, out);                                                                          \
         }                                                                                                 \
     }
-    FATE_FORMAT_SWITCH_ALL(bits, tpg, FATE_DOWN_BODY)
+#define FATE_DOWN_BODY(BITS, TPG) FATE_DOWN_BODY_(BITS, TPG, false)
+#define FATE_DOWN_BODY_Z(BITS, TPG) FATE_DOWN_BODY_(BITS, TPG, true)
+    if (has_z) {
+        FATE_FORMAT_SWITCH_ZP(bits, tpg, FATE_DOWN_BODY_Z)
+    } else {
+        FATE_FORMAT_SWITCH_ALL(bits, tpg, FATE_DOWN_BODY)
+    }
 #undef FATE_DOWN_BODY
+#undef FATE_DOWN_BODY_Z
+#undef FATE_DOWN_BODY_
 }
 
 __global__ void f32_to_bf16_kernel(const float* __restrict__ src, uint16_t* __restrict__ dst, long long n) {

@@ -199,7 +199,42 @@ __device__ __forceinline__ void dequant_tile(const uint4& raw, uint32_t scale_bi
     }
 }
 
-template <int BITS, int NMAT, int kBM>
+// the same with a zero-point: w = (u - z) * s on the unsigned field u (exact), two roundings
+template <int BITS>
+__device__ __forceinline__ void dequant_tile_zp(const uint4& raw, uint32_t scale_bits, uint32_t zero_bits, f16x8_t* b) {
+    static_assert(BITS == 4 || BITS == 2, "zero-points come with the 4- and 2-bit formats");
+    const f16x2v_t s2 = {__builtin_bit_cast(_Float16, (unsigned short)scale_bits),
+                         __builtin_bit_cast(_Float16, (unsigned short)scale_bits)};
+    const f16x2v_t z2 = {__builtin_bit_cast(_Float16, (unsigned short)zero_bits),
+                         __builtin_bit_cast(_Float16, (unsigned short)zero_bits)};
+    const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
+    if constexpr (BITS == 2) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            f16x2_t f[8];
+            int2_fields_to_f16(r[d], f);
+            f16x2v_t w[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[i] = (__builtin_bit_cast(f16x2v_t, f[i]) - z2) * s2;
+            b[2 * d] = f16x8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
+            b[2 * d + 1] = f16x8_t{w[4].x, w[4].y, w[5].x, w[5].y, w[6].x, w[6].y, w[7].x, w[7].y};
+        }
+    } else {
+        const f16x2v_t cA = {(_Float16)1024.f, (_Float16)1024.f}, cB = {(_Float16)64.f, (_Float16)64.f};
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t hi = r[d] >> 8;
+            f16x2v_t w[4];
+            w[0] = ((__builtin_bit_cast(f16x2v_t, and_or_b32(r[d], 0x000f000fu, 0x64006400u)) - cA) - z2) * s2;
+            w[1] = ((__builtin_bit_cast(f16x2v_t, and_or_b32(r[d], 0x00f000f0u, 0x54005400u)) - cB) - z2) * s2;
+            w[2] = ((__builtin_bit_cast(f16x2v_t, and_or_b32(hi, 0x000f000fu, 0x64006400u)) - cA) - z2) * s2;
+            w[3] = ((__builtin_bit_cast(f16x2v_t, and_or_b32(hi, 0x00f000f0u, 0x54005400u)) - cB) - z2) * s2;
+            b[d] = f16x8_t{w[0].x, w[0].y, w[1].x, w[1].y, w[2].x, w[2].y, w[3].x, w[3].y};
+        }
+    }
+}
+
+template <int BITS, int NMAT, int kBM, bool ZP = false>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert* ex, int group, int row0, int T,
                                           int nblk, const int* arow, __half* xt, __half* out, int ldo,
                                           int out_row0, int Nout, int K, const __half* A, int lda) {
@@ -214,13 +249,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
     const int nmt = (min(kBM, T - row0) + 31) >> 5;        // 32-row tiles of this block that hold rows
     gu4p_t wt[NMAT];
     gu16p_t sc[NMAT];
+    gu16p_t zp[NMAT];
     {
         const void* wp[2] = {a.mode == 0 ? ex->w1 : ex->w2, ex->w3};
         const void* sp[2] = {a.mode == 0 ? ex->s1 : ex->s2, ex->s3};
+        const void* zq[2] = {a.mode == 0 ? ex->z1 : ex->z2, ex->z3};
 #pragma unroll
         for (int i = 0; i < NMAT; ++i) {
             wt[i] = (gu4p_t)(uintptr_t)wp[i] + (size_t)(wrow0 >> 5) * tiles_k * 64 + lane;
             sc[i] = (gu16p_t)(uintptr_t)sp[i] + wrow0 + n;          // group-major scales: [G][Nout]
+            zp[i] = (gu16p_t)(uintptr_t)(ZP ? zq[i] : sp[i]) + wrow0 + n;     // zero-points, same layout
         }
     }
     f32x16_t acc[NMAT][kBM / 32];
@@ -236,6 +274,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
     uint4 xr[kBM / 16];
     uint4 raw[kWRing][NMAT][TPC];
     uint32_t sbits[kWRing][NMAT][TPC];
+    uint32_t zbits[ZP ? kWRing : 1][NMAT][TPC];
     // (the load is unconditional and the row is clamped: a branch around a load makes the
     // compiler wait for every outstanding load at the next use, which empties the weight ring)
     // the rows this thread stages do not change from chunk to chunk; a missing row reads row 0
@@ -264,7 +303,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
                 const int tile = kc * TPC + tl;
                 raw[u][i][tl] = wt[i][(size_t)tile * 64];
                 sbits[u][i][tl] = sc[i][(size_t)((tile * KT) / group) * Nout];
+                if constexpr (ZP) zbits[u][i][tl] = zp[i][(size_t)((tile * KT) / group) * Nout];
             }
+    };
+    auto dequant = [&](int u, int i, int tl, f16x8_t* b) {
+        if constexpr (ZP) dequant_tile_zp<BITS>(raw[u][i][tl], sbits[u][i][tl], zbits[u][i][tl], b);
+        else dequant_tile<BITS>(raw[u][i][tl], sbits[u][i][tl], b);
     };
     // two activation tiles in LDS: chunk kc is multiplied from tile kc & 1 while chunk kc + 1 is
     // written into the other one, so a chunk costs one barrier and a wave's dequantisation is
@@ -327,7 +371,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
 #pragma unroll
                 for (int i = 0; i < NMAT; ++i)
 #pragma unroll
-                    for (int tl = 0; tl < TPC; ++tl) dequant_tile<BITS>(raw[u][i][tl], sbits[u][i][tl], &b[i][tl * SPT]);
+                    for (int tl = 0; tl < TPC; ++tl) dequant(u, i, tl, &b[i][tl * SPT]);
                 request_w(u, min(kc + kWRing, nchunk - 1));
                 multiply(b, u);
                 lds_only_barrier();   // chunk kc + 1 is visible, everyone is done reading chunk kc
@@ -349,7 +393,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
                     for (int i = 0; i < NMAT; ++i)
 #pragma unroll
                         for (int tl = 0; tl < TPC; ++tl)
-                            dequant_tile<BITS>(raw[u][i][tl], sbits[u][i][tl], &b[i][tl * SPT]);
+                            dequant(u, i, tl, &b[i][tl * SPT]);
                     if (kc + kWRing < nchunk) request_w(u, kc + kWRing);
                     multiply(b, u);
                 }
@@ -429,7 +473,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         if (threadIdx.x == 0) atomicOr(a.status, 4);
         return;
     }
-    if (bits == 4)
+    const bool has_z = ex->z1 != nullptr;
+    if (has_z && (bits == 8 || ex->z2 == nullptr || ex->z3 == nullptr)) {     // zero-points: 4- and 2-bit formats
+        if (threadIdx.x == 0) atomicOr(a.status, 4);
+        return;
+    }
+    if (has_z && bits == 4)
+        gemm_tile<4, NMAT, kBM, true>(a, ex, group, row0, T, nblk, arow, xt, out, ldo, out_row0, Nout, K, A, lda);
+    else if (has_z)
+        gemm_tile<2, NMAT, kBM, true>(a, ex, group, row0, T, nblk, arow, xt, out, ldo, out_row0, Nout, K, A, lda);
+    else if (bits == 4)
         gemm_tile<4, NMAT, kBM>(a, ex, group, row0, T, nblk, arow, xt, out, ldo, out_row0, Nout, K, A, lda);
     else if (bits == 2)
         gemm_tile<2, NMAT, kBM>(a, ex, group, row0, T, nblk, arow, xt, out, ldo, out_row0, Nout, K, A, lda);

@@ -249,7 +249,7 @@ __device__ __forceinline__ void b1_up_role(const B1Args& A, int ub, bool is_shar
         const fate_qexpert ex = a.shared[s];
         B1_TS(1);
         const bool absent = ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr || ex.bits != a.bits_s ||
-                            ex.group != a.group_s;
+                            ex.group != a.group_s || ex.z1 != nullptr;
         uint32_t hbits = 0;
         if (absent && tid == 0) atomicOr(a.status, 1);
         if (!absent && kb * kLayerNeurons < ex.I) {
@@ -284,7 +284,7 @@ __device__ __forceinline__ void b1_up_role(const B1Args& A, int ub, bool is_shar
         bool absent = true;
         if (e_cur >= 0) {
             absent = ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr || ex.bits != a.bits_r ||
-                     ex.group != a.group_r;
+                     ex.group != a.group_r || ex.z1 != nullptr;
             hbits = 0;
             if (!absent && kb * kLayerNeurons < ex.I) {
                 cx.I = ex.I; cx.kb = kb; cx.ex = ex;
@@ -324,7 +324,8 @@ __device__ __forceinline__ int b1_down_request(const fate_qexpert& ex, int H, in
     const int tiles_k2 = ex.I / KT;
     const int gmax = ex.I / group;
     ng = g0 + ng <= gmax ? ng : (gmax > g0 ? gmax - g0 : 0);
-    if (ng <= 0 || ex.w2 == nullptr || ex.w1 == nullptr || ex.w3 == nullptr || ex.bits != BITS || ex.group != group)
+    if (ng <= 0 || ex.w2 == nullptr || ex.w1 == nullptr || ex.w3 == nullptr || ex.bits != BITS || ex.group != group ||
+        ex.z1 != nullptr)
         return 0;
     const int nt = ng * TPG;
     gu4_t w2 = as_global<uint4>(ex.w2) + ((size_t)rb * tiles_k2 + (size_t)g0 * TPG) * 64 + lane;

@@ -525,7 +525,7 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
     const int I = ex.I;
     // (an entry of another width than the call's - a low-width copy left by a prefill - counts as absent)
     const bool absent = ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr || ex.bits != bits ||
-                        ex.group != group;
+                        ex.group != group || ex.z1 != nullptr;
     if (kb * kLayerNeurons >= I || absent) {
         // nothing to compute, but the reduction reads this block's rows: they must be zero
         if (absent && tid == 0) atomicOr(a.status, 1);

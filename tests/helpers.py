@@ -15,8 +15,9 @@ def f32(t):
 
 def oracle_expert(ex):
     ex = ex.cpu()
+    z = {} if ex.z1 is None else dict(z1=ex.z1.numpy(), z3=ex.z3.numpy(), z2=ex.z2.numpy())
     return O.OracleExpert(ex.w1.numpy(), ex.s1.numpy(), ex.w3.numpy(), ex.s3.numpy(), ex.w2.numpy(),
-                          ex.s2.numpy(), ex.bits, ex.group)
+                          ex.s2.numpy(), ex.bits, ex.group, **z)
 
 
 def bias_np(b):

@@ -50,12 +50,13 @@ def test_pack_weight_layout_int2(rows, K):
 class MixedLayer:
     """Expert table of one layer whose routed experts are stored at the widths in `bits_of` (default 4)."""
 
-    def __init__(self, cfg, layer, used, bits_of):
+    def __init__(self, cfg, layer, used, bits_of, zero_points=()):
         self.cfg = cfg
         self.host, self.packed, structs = {}, {}, []
         for e in range(cfg.E):
             if e in used:
-                ex = gen_expert(cfg, layer, e, device=DEV, bits=bits_of.get(e, cfg.bits), group=128)
+                ex = gen_expert(cfg, layer, e, device=DEV, bits=bits_of.get(e, cfg.bits), group=128,
+                                zero_points=e in zero_points)
                 self.host[e] = ex
                 self.packed[e] = B.PackedExpert(ex, DEV)
                 structs.append(self.packed[e].struct())

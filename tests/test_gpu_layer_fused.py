@@ -114,12 +114,14 @@ def test_one_launch_layer_with_outlier_activations(name, N):
     print(f"  max row error vs oracle {err:.2e}")
     assert err <= 2e-3
 
-@pytest.mark.parametrize("name,N", [("qwen", 1), ("qwen", 6), ("mixtral", 1)])
-def test_one_launch_layer_with_an_expert_that_is_not_resident(name, N):
-    """An activated expert whose table entry holds NULL pointers: status bit 0 is raised, its pairs
-    contribute nothing, everything else is as usual (one-item and looping kernels)."""
+@pytest.mark.parametrize("name,N,how", [("qwen", 1, "null"), ("qwen", 6, "null"), ("mixtral", 1, "null"),
+                                        ("qwen", 1, "zero_points"), ("qwen", 6, "zero_points")])
+def test_one_launch_layer_with_an_expert_that_is_not_resident(name, N, how):
+    """An activated expert whose table entry holds NULL pointers, or is stored in a format the one-launch
+    layer does not read (here: with zero-points): status bit 0 is raised, its pairs contribute nothing,
+    everything else is as usual (one-item and looping kernels)."""
     cfg = SHAPES[name]
-    print(f"case {name} N={N} one expert absent", flush=True)
+    print(f"case {name} N={N} one expert absent ({how})", flush=True)
     x = gen_hidden(cfg, N, device=DEV)
     lw = LayerWeights(cfg, 0, DEV)
     one = LayerBuffers(cfg, N, DEV)
@@ -128,7 +130,13 @@ def test_one_launch_layer_with_an_expert_that_is_not_resident(name, N):
     ids_h = one.ids.cpu().numpy()
     gone = int(ids_h[0, 0])                                  # the first token's first expert
     saved = lw.table.clone()
-    lw.table[gone * 64:(gone + 1) * 64].zero_()              # sizeof(fate_qexpert) = 64
+    sz = __import__('ctypes').sizeof(B.fate_qexpert)
+    if how == "null":
+        lw.table[gone * sz:(gone + 1) * sz].zero_()
+    else:                      # a non-NULL zero-point pointer (the scales' address: never read)
+        o = B.fate_qexpert
+        lw.table[gone * sz + o.z1.offset:gone * sz + o.z1.offset + 8] = \
+            lw.table[gone * sz + o.s1.offset:gone * sz + o.s1.offset + 8].clone()
     one.y.fill_(float("nan"))
     layer_forward(cfg, lw, None, x, one, one_launch=True)
     torch.cuda.synchronize()
@@ -209,7 +217,8 @@ def test_one_token_layer_with_prefetch_hints(name):
     others = [e for e in range(E) if e not in true]
     # an expert that is not selected and not resident: a hint may name it without consequences
     gone = others[0]
-    lw.table[gone * 64:(gone + 1) * 64].zero_()
+    sz = __import__('ctypes').sizeof(B.fate_qexpert)
+    lw.table[gone * sz:(gone + 1) * sz].zero_()
     hints = {
         "exact": true,
         "reversed": true[::-1],

@@ -103,6 +103,32 @@ def quantize_sym(w: torch.Tensor, bits: int, group: int):
     return codes.contiguous(), s.contiguous()
 
 
+def quantize_minmax(w: torch.Tensor, bits: int, group: int):
+    """Asymmetric group quantiser (plain min / max) used to prepare stored weights with zero-points.
+
+    w: [rows, K] fp32.  Returns (fields uint8 canonical layout, scales fp16, zero-points fp16):
+    w ~ (u - z) * s with u in [0, 2^bits - 1], s = fp16((max - min) / (2^bits - 1)) per group
+    (1 for a constant group), z = fp16(-min / s), u = round-half-even(w / s + z) clamped.
+    """
+    assert bits in (2, 4)
+    rows, K = w.shape
+    assert K % group == 0 and group % 4 == 0
+    umax = (1 << bits) - 1
+    wg = w.reshape(rows, K // group, group)
+    lo, hi = wg.amin(dim=-1), wg.amax(dim=-1)
+    s = ((hi - lo) / umax).to(torch.float16)
+    s = torch.where(s == 0, torch.ones_like(s), s)
+    sf = s.to(torch.float32)
+    z = (-lo / sf).to(torch.float16)
+    u = torch.clamp(torch.round(wg / sf.unsqueeze(-1) + z.to(torch.float32).unsqueeze(-1)), 0, umax)
+    u = u.reshape(rows, K).to(torch.uint8)
+    if bits == 4:
+        codes = u[:, 0::2] | (u[:, 1::2] << 4)
+    else:
+        codes = u[:, 0::4] | (u[:, 1::4] << 2) | (u[:, 2::4] << 4) | (u[:, 3::4] << 6)
+    return codes.contiguous(), s.contiguous(), z.contiguous()
+
+
 @dataclass
 class QExpertHost:
     """One SwiGLU expert in canonical stored form (torch tensors, any device)."""
@@ -116,19 +142,28 @@ class QExpertHost:
     group: int
     I: int
     H: int
+    z1: Optional[torch.Tensor] = None   # zero-points (formats that have them), shaped like the scales
+    z3: Optional[torch.Tensor] = None
+    z2: Optional[torch.Tensor] = None
+
+    def _tensors(self):
+        return [t for t in (self.w1, self.w3, self.w2, self.s1, self.s3, self.s2, self.z1, self.z3, self.z2)
+                if t is not None]
 
     def nbytes(self) -> int:
-        return sum(t.numel() * t.element_size() for t in (self.w1, self.w3, self.w2, self.s1, self.s3, self.s2))
+        return sum(t.numel() * t.element_size() for t in self._tensors())
 
     def cpu(self) -> "QExpertHost":
+        c = lambda t: None if t is None else t.cpu()
         return QExpertHost(self.w1.cpu(), self.w3.cpu(), self.w2.cpu(), self.s1.cpu(), self.s3.cpu(),
-                           self.s2.cpu(), self.bits, self.group, self.I, self.H)
+                           self.s2.cpu(), self.bits, self.group, self.I, self.H, c(self.z1), c(self.z3), c(self.z2))
 
 
 def gen_expert(cfg: MoEShape, layer: int, e: int, shared: bool = False, device="cpu", bits: Optional[int] = None,
-               group: Optional[int] = None) -> QExpertHost:
+               group: Optional[int] = None, zero_points: bool = False) -> QExpertHost:
     """Expert e of a layer: three N(0, w_std) matrices, quantised.  bits / group override the
-    configuration's format: the same weights (same random stream) stored at another width."""
+    configuration's format: the same weights (same random stream) stored at another width;
+    zero_points stores them in the asymmetric format (4 or 2 bits)."""
     I = cfg.I_shared if shared else cfg.I
     bits = bits or (cfg.shared_bits if shared else cfg.bits)
     group = group or cfg.group
@@ -136,8 +171,11 @@ def gen_expert(cfg: MoEShape, layer: int, e: int, shared: bool = False, device="
     mats = []
     for rows, K in ((I, cfg.H), (I, cfg.H), (cfg.H, I)):
         w = torch.randn(rows, K, generator=g, device=device, dtype=torch.float32) * cfg.w_std
-        mats.append(quantize_sym(w, bits, group))
+        mats.append(quantize_minmax(w, bits, group) if zero_points else quantize_sym(w, bits, group))
         del w
+    if zero_points:
+        (w1, s1, z1), (w3, s3, z3), (w2, s2, z2) = mats
+        return QExpertHost(w1, w3, w2, s1, s3, s2, bits, group, I, cfg.H, z1, z3, z2)
     (w1, s1), (w3, s3), (w2, s2) = mats
     return QExpertHost(w1, w3, w2, s1, s3, s2, bits, group, I, cfg.H)
 
