@@ -271,9 +271,34 @@ __device__ __forceinline__ void b1_up_role(const B1Args& A, int ub, bool is_shar
     float* wv = reinterpret_cast<float*>(dyn + L.w);
     int32_t* src_e = reinterpret_cast<int32_t*>(dyn + L.pairq);     // (regions the one-token kernel has no other use for)
     float* src_w = reinterpret_cast<float*>(dyn + L.wtok);
+    if (a.hint == nullptr) {
+        // no hint: slot j works on the expert of rank j, and that is all an up block has to know -
+        // every wave finds it by itself (j + 1 rounds of arg-max over the logits), no softmax, no
+        // second barrier, before the requests go out
+        const uint4* src = reinterpret_cast<const uint4*>(a.experts);
+        for (int i = tid; i < E * (int)(sizeof(fate_qexpert) / 16); i += kLayerThreads) tab[i] = src[i];
+        if (!wait_logits(a.zq, E, tag, zl)) {
+            if (tid == 0) atomicOr(a.status, 2);
+            b1_publish_h(hq_dst, tag, 0);
+            return;
+        }
+        const int e_true = __builtin_amdgcn_readfirstlane(wave_rank_expert(zl, E, slot));
+        const fate_qexpert ex = reinterpret_cast<const fate_qexpert*>(tab)[e_true < 0 ? 0 : e_true];
+        const bool absent = e_true < 0 || ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr ||
+                            ex.bits != a.bits_r || ex.group != a.group_r || ex.z1 != nullptr;
+        uint32_t hbits = 0;
+        if (absent && tid == 0) atomicOr(a.status, 1);
+        if (!absent && kb * kLayerNeurons < ex.I) {
+            cx.I = ex.I; cx.kb = kb; cx.ex = ex;
+            hbits = b1_up<BR, TR>(cx, load_x, store_x);
+        }
+        B1_TS(1);
+        b1_publish_h(hq_dst, tag, hbits);
+        return;
+    }
     int e_cur = -1;
     fate_qexpert ex{};
-    if (a.hint != nullptr) {
+    {
         e_cur = a.hint[slot];
         if (e_cur < 0 || e_cur >= E) e_cur = -1;
         if (e_cur >= 0) ex = a.experts[e_cur];
@@ -473,7 +498,26 @@ __device__ __forceinline__ void b1_down_role(const B1Args& A, int part, int rb, 
                 ng = b1_down_request<BR, TR>(exh, H, rb, it.g0, it.ng, raw, sc);
             }
         }
-        if (!b1_selection(A, tag, tab, zl, ids, wv, src_e, src_w)) {
+        if (a.hint == nullptr) {
+            // as in the up blocks: the wave's expert from the logits alone, W2 requested at once; the
+            // weights of the selection follow while the requests are in flight
+            const uint4* src = reinterpret_cast<const uint4*>(a.experts);
+            for (int i = tid; i < E * (int)(sizeof(fate_qexpert) / 16); i += kLayerThreads) tab[i] = src[i];
+            if (!wait_logits(a.zq, E, tag, zl)) {
+                failed = true;
+            } else {
+                const int e_true = __builtin_amdgcn_readfirstlane(wave_rank_expert(zl, E, slot));
+                if (it.ng > 0 && e_true >= 0) {
+                    const fate_qexpert ex = reinterpret_cast<const fate_qexpert*>(tab)[e_true];
+                    ng = b1_down_request<BR, TR>(ex, H, rb, it.g0, it.ng, raw, sc);
+                }
+                B1_TS(2);
+                if (wave == 0) wave_softmax_topk_rounds(zl, E, k, a.r.renorm, ids, wv);
+                lds_barrier();
+                wsrc = wv[slot];
+                if (ng > 0) out = b1_down_product<BR, TR>(raw, sc, ng, hq_src, tag, hl, zrow, &failed);
+            }
+        } else if (!b1_selection(A, tag, tab, zl, ids, wv, src_e, src_w)) {
             failed = true;
         } else {
             const int e_true = src_e[slot];

@@ -223,6 +223,47 @@ __device__ __forceinline__ void wave_softmax_topk_rounds_ns(const float* z, int 
         }
 }
 
+// The expert that wave_softmax_topk_rounds puts at rank r (0 = largest logit): its first r + 1
+// rounds of arg-max and nothing else - no softmax, no weights - for a consumer that only has
+// to know where to fetch from.  The result is the same in every lane.
+template <int NS>
+__device__ __forceinline__ int wave_rank_expert_ns(const float* z, int E, int r) {
+    const int lane = threadIdx.x & 63;
+    float v[NS];
+    bool taken[NS];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        const int e = lane + 64 * i;
+        float t = (e < E) ? z[e] : -INFINITY;
+        if (t != t) t = -INFINITY;
+        v[i] = t;
+        taken[i] = false;
+    }
+    int found = -1;
+    for (int q = 0; q <= r; ++q) {
+        float lbest = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+            if (lane + 64 * i < E && !taken[i]) lbest = fmaxf(lbest, v[i]);
+        const float vbest = wave_max(lbest);
+        found = -1;
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            const unsigned long long ball = __ballot(lane + 64 * i < E && !taken[i] && v[i] == vbest);
+            if (found < 0 && ball) found = 64 * i + __ffsll((long long)ball) - 1;
+        }
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+            if (found == lane + 64 * i) taken[i] = true;
+    }
+    return found;
+}
+__device__ __forceinline__ int wave_rank_expert(const float* z, int E, int r) {
+    if (E <= 64) return wave_rank_expert_ns<1>(z, E, r);
+    if (E <= 128) return wave_rank_expert_ns<2>(z, E, r);
+    return wave_rank_expert_ns<4>(z, E, r);
+}
+
 __device__ __forceinline__ void wave_softmax_topk_rounds(const float* z, int E, int m, int renorm,
                                                          int32_t* ids_out, float* w_out) {
     if (E <= 64) wave_softmax_topk_rounds_ns<1>(z, E, m, renorm, ids_out, w_out);
