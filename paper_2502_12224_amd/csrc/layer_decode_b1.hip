@@ -369,7 +369,9 @@ __device__ __forceinline__ int b1_down_request(const fate_qexpert& ex, int H, in
 template <int BITS, int TPG>
 __device__ __forceinline__ float b1_down_product(const uint4 (&raw)[kB1MaxTiles], const uint32_t (&sc)[kB1MaxTiles / TPG],
                                                  int ng, const unsigned long long* hq_src, uint32_t tag, _Float16* hl,
-                                                 const _Float16* zrow, bool* failed) {
+                                                 const _Float16* zrow, bool* failed,
+                                                 const unsigned long long* side = nullptr,
+                                                 unsigned long long* side_val = nullptr) {
     constexpr int KT = QFmt<BITS>::KT, S = QFmt<BITS>::MSTEPS, MAXG = kB1MaxTiles / TPG;
     static_assert(KT * TPG == 128, "one tagged word of a group per lane");
     const int lane = threadIdx.x & 63;
@@ -382,6 +384,9 @@ __device__ __forceinline__ float b1_down_product(const uint4 (&raw)[kB1MaxTiles]
             unsigned long long v[MAXG];
 #pragma unroll
             for (int j = 0; j < MAXG; ++j) v[j] = j < ng ? ld_dev(hq_src + lane + 64 * j) : tagw;
+            // a word the caller needs right after the product rides along with every poll (side: this
+            // lane's address or NULL), so that no memory round trip of its own follows the product
+            if (side != nullptr) *side_val = ld_dev(side);
             bool good = true;
 #pragma unroll
             for (int j = 0; j < MAXG; ++j) good = good && (uint32_t)(v[j] >> 32) == tag;
@@ -457,6 +462,8 @@ __device__ __forceinline__ void b1_down_role(const B1Args& A, int part, int rb, 
     float wsrc = 1.f;
     bool failed = false;
     float out = 0.f;
+    const unsigned long long* side = nullptr;
+    unsigned long long side_val = 0;
     if (is_shared) {
         const fate_qexpert ex = a.shared[it.ng > 0 ? it.src : 0];
         const unsigned long long* hq_src = A.a.hq + (size_t)it.src * a.nkb_s * 16 + (size_t)it.g0 * 64;
@@ -488,6 +495,9 @@ __device__ __forceinline__ void b1_down_role(const B1Args& A, int part, int rb, 
             A.a.hq + ((size_t)a.n_shared * a.nkb_s + (size_t)slot * a.nkb_r) * 16 + (size_t)it.g0 * 64;
         uint4 raw[kB1MaxTiles];
         uint32_t sc[kB1MaxTiles / TR];
+        // the block that writes y (two parts): its wave 0 reads the other part's partial output of
+        // its row along with the polls of h, lanes 0..31
+        if (wave == 0 && lane < 32 && A.nparts == 2 && part == 1) side = A.a.yq + rb * 32 + lane;
         // with a hint the W2 slice of the hinted expert is requested before the gate is known
         int e_cur = -1, ng = 0;
         if (a.hint != nullptr && it.ng > 0) {
@@ -515,7 +525,7 @@ __device__ __forceinline__ void b1_down_role(const B1Args& A, int part, int rb, 
                 if (wave == 0) wave_softmax_topk_rounds(zl, E, k, a.r.renorm, ids, wv);
                 lds_barrier();
                 wsrc = wv[slot];
-                if (ng > 0) out = b1_down_product<BR, TR>(raw, sc, ng, hq_src, tag, hl, zrow, &failed);
+                if (ng > 0) out = b1_down_product<BR, TR>(raw, sc, ng, hq_src, tag, hl, zrow, &failed, side, &side_val);
             }
         } else if (!b1_selection(A, tag, tab, zl, ids, wv, src_e, src_w)) {
             failed = true;
@@ -548,8 +558,12 @@ __device__ __forceinline__ void b1_down_role(const B1Args& A, int part, int rb, 
             bool good = true;
             for (int p = 0; p + 1 < A.nparts; ++p) {
                 const unsigned long long* src = A.a.yq + (size_t)p * H + row;
-                unsigned long long w = 0;
+                unsigned long long w = side != nullptr ? side_val : 0;      // (two parts: p = 0 is the side word)
                 int spin = 0;
+                if (side != nullptr && (uint32_t)(w >> 32) == tag) {
+                    sum += __uint_as_float((uint32_t)w);
+                    continue;
+                }
                 for (; spin < kSpinMax; ++spin) {
                     w = ld_dev(src);
                     if ((uint32_t)(w >> 32) == tag) break;
