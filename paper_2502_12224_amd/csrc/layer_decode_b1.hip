@@ -53,34 +53,59 @@ __host__ __device__ inline B1DownLds b1_down_lds(int E, int k) {
 
 // ---- up block: 32 neurons of one expert, one token -----------------------------------------
 // The straight-line up projection of the general kernel (register ring, codes + constant on the
-// matrix cores, constant removed per group), then h goes out as 16 tagged words.
-// Returns, in lanes 0..31 of wave 0, the fp16 bits of h of neuron kb*32 + lane.
-template <int BITS, int TPG, class LoadX, class StoreX>
-__device__ __forceinline__ uint32_t b1_up(const WorkCtx& c, LoadX&& load_x, StoreX&& store_x) {
-    constexpr int KT = QFmt<BITS>::KT, D = kUpRing, GR = D / TPG;
-    const int tid = c.tid, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n = lane & 31, half = lane >> 5;
-    const int H = c.H, I = c.I, kb = c.kb;
-    const int tiles_k = H / KT;
-    const int tw = tiles_k / kLayerWaves;
-    const int rounds = tw / D;
-    const int g_beg = wave * (tw / TPG);
-    const gu4_t wt[2] = {as_global<uint4>(c.ex.w1) + ((size_t)kb * tiles_k + wave * tw) * 64 + lane,
-                         as_global<uint4>(c.ex.w3) + ((size_t)kb * tiles_k + wave * tw) * 64 + lane};
-    const gu16_t sc[2] = {as_global<uint16_t>(c.ex.s1) + (size_t)g_beg * I + kb * 32 + n,
-                          as_global<uint16_t>(c.ex.s3) + (size_t)g_beg * I + kb * 32 + n};
+// matrix cores, constant removed per group) in two steps, so that the requests can be in flight
+// while the block does something else: b1_up_issue asks for the first ring of W1 / W3 tiles and
+// their scales, b1_up_compute multiplies and returns, in lanes 0..31 of wave 0, the fp16 bits of
+// h of neuron kb*32 + lane.
+template <int TPG>
+struct B1UpRegs {
+    uint4 raw[2][kUpRing];
+    uint32_t scr[2][kUpRing / TPG];
+};
+
+template <int BITS, int TPG>
+struct B1UpAddr {
+    gu4_t wt[2];
+    gu16_t sc[2];
+    int g_beg, tw;
+    __device__ __forceinline__ B1UpAddr(const WorkCtx& c) {
+        constexpr int KT = QFmt<BITS>::KT;
+        const int lane = c.tid & 63, wave = __builtin_amdgcn_readfirstlane(c.tid >> 6);
+        const int n = lane & 31;
+        const int tiles_k = c.H / KT;
+        tw = tiles_k / kLayerWaves;
+        g_beg = wave * (tw / TPG);
+        wt[0] = as_global<uint4>(c.ex.w1) + ((size_t)c.kb * tiles_k + wave * tw) * 64 + lane;
+        wt[1] = as_global<uint4>(c.ex.w3) + ((size_t)c.kb * tiles_k + wave * tw) * 64 + lane;
+        sc[0] = as_global<uint16_t>(c.ex.s1) + (size_t)g_beg * c.I + c.kb * 32 + n;
+        sc[1] = as_global<uint16_t>(c.ex.s3) + (size_t)g_beg * c.I + c.kb * 32 + n;
+    }
+};
+
+template <int BITS, int TPG, class LoadX>
+__device__ __forceinline__ void b1_up_issue(const WorkCtx& c, B1UpRegs<TPG>& R, LoadX&& load_x) {
+    constexpr int D = kUpRing, GR = D / TPG;
+    const B1UpAddr<BITS, TPG> ad(c);
     if (c.defer_x) load_x();
-    uint4 raw[2][D];
-    uint32_t scr[2][GR];
 #pragma unroll
     for (int j = 0; j < D; ++j)
 #pragma unroll
-        for (int i = 0; i < 2; ++i) raw[i][j] = wt[i][(size_t)j * 64];
+        for (int i = 0; i < 2; ++i) R.raw[i][j] = ad.wt[i][(size_t)j * 64];
 #pragma unroll
     for (int jg = 0; jg < GR; ++jg)
 #pragma unroll
-        for (int i = 0; i < 2; ++i) scr[i][jg] = sc[i][(size_t)jg * I];
+        for (int i = 0; i < 2; ++i) R.scr[i][jg] = ad.sc[i][(size_t)jg * c.I];
     B1_TS(2);
+}
+
+template <int BITS, int TPG, class StoreX>
+__device__ __forceinline__ uint32_t b1_up_compute(const WorkCtx& c, B1UpRegs<TPG>& R, StoreX&& store_x) {
+    constexpr int KT = QFmt<BITS>::KT, D = kUpRing;
+    const int tid = c.tid, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 31, half = lane >> 5;
+    const B1UpAddr<BITS, TPG> ad(c);
+    const int tw = ad.tw, g_beg = ad.g_beg, I = c.I;
+    const int rounds = tw / D;
     if (c.defer_x) store_x(true);
     lds_barrier();            // x and the zero row are in LDS
     B1_TS(3);
@@ -109,8 +134,8 @@ __device__ __forceinline__ uint32_t b1_up(const WorkCtx& c, LoadX&& load_x, Stor
     const _Float16* xa = c.xs + arow * c.ldx + half * (KT / 2) + (size_t)wave * tw * KT;
     const float* cxg = c.cx + g_beg * kCxLd;
     for (int r = 0; r + 1 < rounds; ++r)
-        up_round<BITS, TPG, true>(raw, scr, wt, sc, I, r, xa, cxg, ctok, bc, out, [] {});
-    up_round<BITS, TPG, false>(raw, scr, wt, sc, I, rounds - 1, xa, cxg, ctok, bc, out, [] {});
+        up_round<BITS, TPG, true>(R.raw, R.scr, ad.wt, ad.sc, I, r, xa, cxg, ctok, bc, out, [] {});
+    up_round<BITS, TPG, false>(R.raw, R.scr, ad.wt, ad.sc, I, rounds - 1, xa, cxg, ctok, bc, out, [] {});
     B1_TS(4);
     if (half == 0) {
         c.red[(wave * 2 + 0) * 32 + n] = out[0][0];
@@ -149,8 +174,8 @@ __device__ __forceinline__ void b1_publish_h(unsigned long long* hq_dst, uint32_
 // blocks of slot j have started on expert hint[j] before the gate was known: slot j keeps it
 // if it is among the selected ones (first occurrence only), and the selected experts that
 // no slot holds go, in rank order, to the slots whose hint missed.  One wave; k <= 64.
-__device__ __forceinline__ void b1_assign_slots(const int32_t* hint, const int32_t* ids, const float* wv, int k,
-                                                int E, int32_t* src_e, float* src_w) {
+__device__ __forceinline__ void b1_assign_slots(const int32_t* hint, const int32_t* ids, int k, int E, int32_t* src_e,
+                                                int32_t* src_r) {
     const int lane = threadIdx.x & 63;
     const int mine = lane < k ? ids[lane] : -1;          // lane r: the expert of rank r
     int hj = -1;
@@ -183,12 +208,17 @@ __device__ __forceinline__ void b1_assign_slots(const int32_t* hint, const int32
     const int e_mine = __shfl(mine, r_mine < 0 ? 0 : r_mine, 64);
     if (lane < k) {
         src_e[lane] = e_mine;
-        src_w[lane] = wv[r_mine < 0 ? 0 : r_mine];
+        src_r[lane] = r_mine < 0 ? 0 : r_mine;        // its rank: where the selection's weights will hold its weight
     }
 }
 
-__device__ __forceinline__ bool b1_selection(const B1Args& A, uint32_t tag, uint4* tab, float* zl, int32_t* ids, float* wv,
-                                             int32_t* src_e, float* src_w) {
+// Routed blocks: wait for the logits (the expert table travels to LDS meanwhile) and find the
+// expert of the block's slot - ids only, no softmax: the selection's weights are needed much later
+// and only by the down blocks.  Without a hint every wave finds the expert of rank `slot` by itself;
+// with a hint wave 0 takes all k ranks, matches them against the hinted experts and the other
+// waves read the result after one LDS barrier.  Returns false when the wait ran out.
+__device__ __forceinline__ bool b1_slot_expert(const B1Args& A, uint32_t tag, int slot, uint4* tab, float* zl, int32_t* ids,
+                                               int32_t* src_e, int32_t* src_r, int* e_true, int* rank) {
     const LayerArgs& a = A.a;
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int E = a.r.E;
@@ -198,16 +228,28 @@ __device__ __forceinline__ bool b1_selection(const B1Args& A, uint32_t tag, uint
         if (tid == 0) atomicOr(a.status, 2);
         return false;
     }
-    if (wave == 0) {
-        wave_softmax_topk_rounds(zl, E, a.r.k, a.r.renorm, ids, wv);
-        __builtin_amdgcn_wave_barrier();
-        b1_assign_slots(a.hint, ids, wv, a.r.k, E, src_e, src_w);
+    if (a.hint == nullptr) {
+        *e_true = __builtin_amdgcn_readfirstlane(wave_rank_expert(zl, E, slot));
+        *rank = slot;
+        return true;
     }
-    __syncthreads();
+    if (wave == 0) {
+        wave_topk_ids(zl, E, a.r.k, ids);
+        __builtin_amdgcn_wave_barrier();
+        b1_assign_slots(a.hint, ids, a.r.k, E, src_e, src_r);
+    }
+    lds_barrier();
+    *e_true = src_e[slot];
+    *rank = src_r[slot];
     return true;
 }
 
-template <int BR, int TR, int BS, int TS>
+__device__ __forceinline__ bool b1_entry_usable(const fate_qexpert& ex, int bits, int group) {
+    return ex.w1 != nullptr && ex.w3 != nullptr && ex.w2 != nullptr && ex.bits == bits && ex.group == group &&
+           ex.z1 == nullptr;
+}
+
+template <int BR, int TR, int BS, int TS, bool HINTED>
 __device__ __forceinline__ void b1_up_role(const B1Args& A, int ub, bool is_shared, uint32_t tag, char* dyn) {
     const LayerArgs& a = A.a;
     const int tid = threadIdx.x;
@@ -248,90 +290,62 @@ __device__ __forceinline__ void b1_up_role(const B1Args& A, int ub, bool is_shar
         unsigned long long* hq_dst = A.a.hq + ((size_t)s * a.nkb_s + kb) * 16;
         const fate_qexpert ex = a.shared[s];
         B1_TS(1);
-        const bool absent = ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr || ex.bits != a.bits_s ||
-                            ex.group != a.group_s || ex.z1 != nullptr;
+        const bool absent = !b1_entry_usable(ex, a.bits_s, a.group_s);
         uint32_t hbits = 0;
         if (absent && tid == 0) atomicOr(a.status, 1);
         if (!absent && kb * kLayerNeurons < ex.I) {
             cx.I = ex.I; cx.kb = kb; cx.ex = ex;
-            hbits = b1_up<BS, TS>(cx, load_x, store_x);
+            B1UpRegs<TS> R;
+            b1_up_issue<BS, TS>(cx, R, load_x);
+            hbits = b1_up_compute<BS, TS>(cx, R, store_x);
         }
         b1_publish_h(hq_dst, tag, hbits);
         return;
     }
-    // Routed slot.  With a hint the block starts on the hinted expert at once (the paper's
-    // cross-layer prediction used as a prefetch: section 4.3) and only checks it against the gate's
-    // selection afterwards; a wrong hint costs a second pass with the right expert.
+    // Routed slot.  With a hint (the paper's cross-layer prediction used as a prefetch: section 4.3)
+    // the requests for the hinted expert go out before the gate is known; once the logits are there
+    // the block checks the hint against the gate's selection and asks again only if it was wrong.
     const int slot = ub / a.nkb_r;
     const int kb = ub - slot * a.nkb_r;
     unsigned long long* hq_dst = A.a.hq + ((size_t)a.n_shared * a.nkb_s + (size_t)slot * a.nkb_r + kb) * 16;
     uint4* tab = reinterpret_cast<uint4*>(dyn + L.tab);
     float* zl = reinterpret_cast<float*>(dyn + L.zl);
     int32_t* ids = reinterpret_cast<int32_t*>(dyn + L.ids);
-    float* wv = reinterpret_cast<float*>(dyn + L.w);
     int32_t* src_e = reinterpret_cast<int32_t*>(dyn + L.pairq);     // (regions the one-token kernel has no other use for)
-    float* src_w = reinterpret_cast<float*>(dyn + L.wtok);
-    if (a.hint == nullptr) {
-        // no hint: slot j works on the expert of rank j, and that is all an up block has to know -
-        // every wave finds it by itself (j + 1 rounds of arg-max over the logits), no softmax, no
-        // second barrier, before the requests go out
-        const uint4* src = reinterpret_cast<const uint4*>(a.experts);
-        for (int i = tid; i < E * (int)(sizeof(fate_qexpert) / 16); i += kLayerThreads) tab[i] = src[i];
-        if (!wait_logits(a.zq, E, tag, zl)) {
-            if (tid == 0) atomicOr(a.status, 2);
-            b1_publish_h(hq_dst, tag, 0);
-            return;
-        }
-        const int e_true = __builtin_amdgcn_readfirstlane(wave_rank_expert(zl, E, slot));
-        const fate_qexpert ex = reinterpret_cast<const fate_qexpert*>(tab)[e_true < 0 ? 0 : e_true];
-        const bool absent = e_true < 0 || ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr ||
-                            ex.bits != a.bits_r || ex.group != a.group_r || ex.z1 != nullptr;
-        uint32_t hbits = 0;
-        if (absent && tid == 0) atomicOr(a.status, 1);
-        if (!absent && kb * kLayerNeurons < ex.I) {
-            cx.I = ex.I; cx.kb = kb; cx.ex = ex;
-            hbits = b1_up<BR, TR>(cx, load_x, store_x);
-        }
-        B1_TS(1);
-        b1_publish_h(hq_dst, tag, hbits);
-        return;
-    }
+    int32_t* src_r = reinterpret_cast<int32_t*>(dyn + L.wtok);
+    B1UpRegs<TR> R;
     int e_cur = -1;
-    fate_qexpert ex{};
-    {
+    bool in_flight = false;                 // requests for expert e_cur are under way
+    if constexpr (HINTED) {
         e_cur = a.hint[slot];
         if (e_cur < 0 || e_cur >= E) e_cur = -1;
-        if (e_cur >= 0) ex = a.experts[e_cur];
-    }
-    bool selected = false;
-    uint32_t hbits = 0;
-    for (int pass = 0; pass < 2; ++pass) {
-        bool absent = true;
         if (e_cur >= 0) {
-            absent = ex.w1 == nullptr || ex.w3 == nullptr || ex.w2 == nullptr || ex.bits != a.bits_r ||
-                     ex.group != a.group_r || ex.z1 != nullptr;
-            hbits = 0;
-            if (!absent && kb * kLayerNeurons < ex.I) {
+            const fate_qexpert ex = a.experts[e_cur];
+            if (b1_entry_usable(ex, a.bits_r, a.group_r) && kb * kLayerNeurons < ex.I) {
                 cx.I = ex.I; cx.kb = kb; cx.ex = ex;
-                hbits = b1_up<BR, TR>(cx, load_x, store_x);
+                b1_up_issue<BR, TR>(cx, R, load_x);
+                in_flight = true;
             }
         }
-        if (!selected) {
-            if (!b1_selection(A, tag, tab, zl, ids, wv, src_e, src_w)) {
-                b1_publish_h(hq_dst, tag, 0);
-                return;
-            }
-            selected = true;
-        }
-        const int e_true = src_e[slot];
-        if (e_cur == e_true) {
-            if (absent && tid == 0) atomicOr(a.status, 1);
-            break;
-        }
-        e_cur = e_true;
-        ex = reinterpret_cast<const fate_qexpert*>(tab)[e_true];
-        lds_barrier();          // every wave is done with the first pass's sums
     }
+    int e_true = -1, rank = 0;
+    if (!b1_slot_expert(A, tag, slot, tab, zl, ids, src_e, src_r, &e_true, &rank)) {
+        b1_publish_h(hq_dst, tag, 0);
+        return;
+    }
+    bool ready = in_flight && e_true == e_cur;
+    if (!ready && e_true >= 0) {
+        const fate_qexpert ex = reinterpret_cast<const fate_qexpert*>(tab)[e_true];
+        const bool usable = b1_entry_usable(ex, a.bits_r, a.group_r);
+        if (!usable && tid == 0) atomicOr(a.status, 1);
+        if (usable && kb * kLayerNeurons < ex.I) {
+            cx.I = ex.I; cx.kb = kb; cx.ex = ex;
+            b1_up_issue<BR, TR>(cx, R, load_x);
+            ready = true;
+        }
+    }
+    uint32_t hbits = 0;
+    if (ready) hbits = b1_up_compute<BR, TR>(cx, R, store_x);
     B1_TS(1);
     b1_publish_h(hq_dst, tag, hbits);
 }
@@ -489,7 +503,7 @@ __device__ __forceinline__ void b1_down_role(const B1Args& A, int part, int rb, 
         int32_t* ids = reinterpret_cast<int32_t*>(dyn + L.ids);
         float* wv = reinterpret_cast<float*>(dyn + L.w);
         int32_t* src_e = reinterpret_cast<int32_t*>(dyn + L.src_e);
-        float* src_w = reinterpret_cast<float*>(dyn + L.src_w);
+        int32_t* src_r = reinterpret_cast<int32_t*>(dyn + L.src_w);
         const int slot = it.ng > 0 ? it.src - a.n_shared : 0;
         const unsigned long long* hq_src =
             A.a.hq + ((size_t)a.n_shared * a.nkb_s + (size_t)slot * a.nkb_r) * 16 + (size_t)it.g0 * 64;
@@ -508,36 +522,23 @@ __device__ __forceinline__ void b1_down_role(const B1Args& A, int part, int rb, 
                 ng = b1_down_request<BR, TR>(exh, H, rb, it.g0, it.ng, raw, sc);
             }
         }
-        if (a.hint == nullptr) {
-            // as in the up blocks: the wave's expert from the logits alone, W2 requested at once; the
-            // weights of the selection follow while the requests are in flight
-            const uint4* src = reinterpret_cast<const uint4*>(a.experts);
-            for (int i = tid; i < E * (int)(sizeof(fate_qexpert) / 16); i += kLayerThreads) tab[i] = src[i];
-            if (!wait_logits(a.zq, E, tag, zl)) {
-                failed = true;
-            } else {
-                const int e_true = __builtin_amdgcn_readfirstlane(wave_rank_expert(zl, E, slot));
-                if (it.ng > 0 && e_true >= 0) {
+        int e_true = -1, rank = 0;
+        if (!b1_slot_expert(A, tag, slot, tab, zl, ids, src_e, src_r, &e_true, &rank)) {
+            failed = true;
+        } else {
+            if (it.ng > 0 && e_true != e_cur) {
+                ng = 0;
+                if (e_true >= 0) {
                     const fate_qexpert ex = reinterpret_cast<const fate_qexpert*>(tab)[e_true];
                     ng = b1_down_request<BR, TR>(ex, H, rb, it.g0, it.ng, raw, sc);
                 }
-                B1_TS(2);
-                if (wave == 0) wave_softmax_topk_rounds(zl, E, k, a.r.renorm, ids, wv);
-                lds_barrier();
-                wsrc = wv[slot];
-                if (ng > 0) out = b1_down_product<BR, TR>(raw, sc, ng, hq_src, tag, hl, zrow, &failed, side, &side_val);
-            }
-        } else if (!b1_selection(A, tag, tab, zl, ids, wv, src_e, src_w)) {
-            failed = true;
-        } else {
-            const int e_true = src_e[slot];
-            wsrc = src_w[slot];
-            if (it.ng > 0 && e_true != e_cur) {
-                const fate_qexpert ex = reinterpret_cast<const fate_qexpert*>(tab)[e_true];
-                ng = b1_down_request<BR, TR>(ex, H, rb, it.g0, it.ng, raw, sc);
             }
             B1_TS(2);
-            if (ng > 0) out = b1_down_product<BR, TR>(raw, sc, ng, hq_src, tag, hl, zrow, &failed);
+            // the weights of the selection, while the requests are in flight
+            if (wave == 0) wave_softmax_topk_rounds(zl, E, k, a.r.renorm, ids, wv);
+            lds_barrier();
+            wsrc = wv[rank];
+            if (ng > 0) out = b1_down_product<BR, TR>(raw, sc, ng, hq_src, tag, hl, zrow, &failed, side, &side_val);
         }
     }
     B1_TS(4);
@@ -598,11 +599,13 @@ __global__ __launch_bounds__(kLayerThreads) __attribute__((amdgpu_waves_per_eu(2
     if (b < a.nb_route) {
         route_role(a, b, tag, dyn, rsm);
     } else if ((b -= a.nb_route) < A.n_up_s) {
-        b1_up_role<BR, TR, BS, TS>(A, b, true, tag, dyn);
+        b1_up_role<BR, TR, BS, TS, false>(A, b, true, tag, dyn);
     } else if ((b -= A.n_up_s) < nd_s) {
         b1_down_role<BR, TR, BS, TS>(A, b / A.nrb, b % A.nrb, tag, dyn);
     } else if ((b -= nd_s) < A.n_up_r) {
-        b1_up_role<BR, TR, BS, TS>(A, b, false, tag, dyn);
+        // (two copies of the routed up block: without a hint there is one place that asks for weights)
+        if (a.hint != nullptr) b1_up_role<BR, TR, BS, TS, true>(A, b, false, tag, dyn);
+        else b1_up_role<BR, TR, BS, TS, false>(A, b, false, tag, dyn);
     } else if ((b -= A.n_up_r) < nd_r) {
         b1_down_role<BR, TR, BS, TS>(A, A.nparts_s + b / A.nrb, b % A.nrb, tag, dyn);
     }

@@ -258,6 +258,43 @@ __device__ __forceinline__ int wave_rank_expert_ns(const float* z, int E, int r)
     }
     return found;
 }
+// The same rounds for all of the first m ranks: ids_out[r] = the expert of rank r (one wave).
+template <int NS>
+__device__ __forceinline__ void wave_topk_ids_ns(const float* z, int E, int m, int32_t* ids_out) {
+    const int lane = threadIdx.x & 63;
+    float v[NS];
+    bool taken[NS];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        const int e = lane + 64 * i;
+        float t = (e < E) ? z[e] : -INFINITY;
+        if (t != t) t = -INFINITY;
+        v[i] = t;
+        taken[i] = false;
+    }
+    for (int r = 0; r < m; ++r) {
+        float lbest = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+            if (lane + 64 * i < E && !taken[i]) lbest = fmaxf(lbest, v[i]);
+        const float vbest = wave_max(lbest);
+        int found = -1;
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            const unsigned long long ball = __ballot(lane + 64 * i < E && !taken[i] && v[i] == vbest);
+            if (found < 0 && ball) found = 64 * i + __ffsll((long long)ball) - 1;
+        }
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+            if (found == lane + 64 * i) taken[i] = true;
+        if (lane == 0) ids_out[r] = found;
+    }
+}
+__device__ __forceinline__ void wave_topk_ids(const float* z, int E, int m, int32_t* ids_out) {
+    if (E <= 64) wave_topk_ids_ns<1>(z, E, m, ids_out);
+    else if (E <= 128) wave_topk_ids_ns<2>(z, E, m, ids_out);
+    else wave_topk_ids_ns<4>(z, E, m, ids_out);
+}
 __device__ __forceinline__ int wave_rank_expert(const float* z, int E, int r) {
     if (E <= 64) return wave_rank_expert_ns<1>(z, E, r);
     if (E <= 128) return wave_rank_expert_ns<2>(z, E, r);
