@@ -337,7 +337,7 @@ fate_cache* fate_cache_create(int num_layers, int E, int cache_total, int L_shal
                               int staging_slots, fate_copy_fn copy, void* user);
 void fate_cache_destroy(fate_cache*);
 int32_t fate_cache_total_slots(const fate_cache*);
-/* Changes the cap on prefetched experts per layer (section 4.2: n = floor(T / t_expert)); the
+/* Changes the cap on prefetched experts per layer (section 4.3: n = floor(T / t_expert)); the
  * ratio differs between prefill and decode, so a caller re-calibrates between the phases.
  * n_max < 0 -> FATE_EINVAL. */
 fate_status fate_cache_set_n_max(fate_cache*, int n_max);

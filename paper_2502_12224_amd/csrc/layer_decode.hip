@@ -11,6 +11,11 @@ fate_status launch_layer_loop_4_2(hipStream_t, int, int, int, int, int, const La
 fate_status launch_layer_loop_4_4(hipStream_t, int, int, int, int, int, const LayerArgs&);
 fate_status launch_layer_loop_8_2(hipStream_t, int, int, int, int, int, const LayerArgs&);
 fate_status launch_layer_loop_8_4(hipStream_t, int, int, int, int, int, const LayerArgs&);
+int layer_loop_blocks_per_cu_4_1(int, int, int, int);
+int layer_loop_blocks_per_cu_4_2(int, int, int, int);
+int layer_loop_blocks_per_cu_4_4(int, int, int, int);
+int layer_loop_blocks_per_cu_8_2(int, int, int, int);
+int layer_loop_blocks_per_cu_8_4(int, int, int, int);
 
 // y[t] = sum over the k pairs of token t and the 32-neuron blocks of their experts, plus the
 // shared experts' blocks.  A workgroup owns 32 consecutive outputs of one token; one wave load
@@ -74,8 +79,9 @@ fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArg
         if (b1_plan(d, a, &b1, &nblocks)) return launch_layer_decode_b1(st, d, b1, nblocks);
     }
     // work items: 32-neuron blocks of the shared experts, then of the routed slots.  With more
-    // items than workgroups fit on the device (two per compute unit), the launch has that many
-    // work blocks and a block takes every nwork-th item.
+    // items than workgroups of the looping kernel fit on the device (asked of the occupancy
+    // calculator for this launch's LDS size), the launch has that many work blocks and a block
+    // takes every nwork-th item.
     static int cu_count = 0;
     if (cu_count == 0) {
         int dev = 0;
@@ -83,11 +89,32 @@ fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArg
         FATE_HIP(hipDeviceGetAttribute(&cu_count, hipDeviceAttributeMultiprocessorCount, dev));
     }
     a.nitems = d.n_shared * a.nkb_s + a.nact * a.nkb_r;
-    const int fit = std::max(1, 2 * cu_count - a.nb_route);
-    a.nwork = a.nitems > fit ? fit : a.nitems;
-    const int grid = a.nb_route + a.nwork;
     const int bits_s = d.n_shared ? d.shared_bits : d.bits, group_s = d.n_shared ? d.shared_group : d.group;
     const int tpg_r = d.group / (d.bits == 4 ? 64 : 32), tpg_s = group_s / (bits_s == 4 ? 64 : 32);
+    int per_cu = 2;
+    if (a.nitems > 2 * cu_count - a.nb_route) {
+        // the query is not free: one answer per format combination and LDS size is kept
+        static int key_seen[4] = {-1, -1, -1, -1}, val_seen[4] = {0, 0, 0, 0};
+        const int key = ((d.bits * 8 + tpg_r) * 16 + bits_s) * 8 + tpg_s;
+        int slot = -1;
+        for (int i = 0; i < 4; ++i)
+            if (key_seen[i] == key * 4096 + L.bytes / 64) slot = i;
+        if (slot < 0) {
+            int nb = 0;
+#define FATE_OCC_BODY(BR, TR) nb = layer_loop_blocks_per_cu_##BR##_##TR(bits_s, tpg_s, L.bytes, kLdsMax);
+            FATE_FORMAT_SWITCH(d.bits, tpg_r, FATE_OCC_BODY)
+#undef FATE_OCC_BODY
+            if (nb < 1) FATE_FAIL(FATE_EHIP, "fused layer: the looping kernel does not fit on a compute unit (LDS %d bytes)", L.bytes);
+            static int next = 0;
+            slot = next++ % 4;
+            key_seen[slot] = key * 4096 + L.bytes / 64;
+            val_seen[slot] = nb;
+        }
+        per_cu = val_seen[slot];
+    }
+    const int fit = std::max(1, per_cu * cu_count - a.nb_route);
+    a.nwork = a.nitems > fit ? fit : a.nitems;
+    const int grid = a.nb_route + a.nwork;
     fate_status rc = FATE_OK;
 #define FATE_ROUTED_BODY(BR, TR)                                                                          \
     rc = a.nwork < a.nitems ? launch_layer_loop_##BR##_##TR(st, bits_s, tpg_s, grid, L.bytes, kLdsMax, a)    \

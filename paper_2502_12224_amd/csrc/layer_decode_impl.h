@@ -749,6 +749,24 @@ static fate_status launch_layer_kernel_v(hipStream_t st, int grid, int lds_bytes
     moe_layer_decode_kernel<BR, TR, BS, TS, LOOP><<<grid, kLayerThreads, lds_bytes, st>>>(a);
     return FATE_OK;
 }
+// workgroups of one kernel variant that fit on a compute unit with lds_bytes of dynamic LDS (0: the query failed)
+template <int BR, int TR, int BS, int TS, bool LOOP>
+static int layer_kernel_blocks_per_cu(int lds_bytes, int lds_max) {
+    const void* f = reinterpret_cast<const void*>(moe_layer_decode_kernel<BR, TR, BS, TS, LOOP>);
+    if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds_max) != hipSuccess) return 0;
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, f, kLayerThreads, (size_t)lds_bytes) != hipSuccess) return 0;
+    return nb;
+}
+template <int BR, int TR, bool LOOP>
+static int layer_routed_blocks_per_cu(int bits_s, int tpg_s, int lds_bytes, int lds_max) {
+    int nb = 0;
+#define FATE_SHARED_BODY(BS, TS) nb = layer_kernel_blocks_per_cu<BR, TR, BS, TS, LOOP>(lds_bytes, lds_max);
+    FATE_FORMAT_SWITCH(bits_s, tpg_s, FATE_SHARED_BODY)
+#undef FATE_SHARED_BODY
+    return nb;
+}
+
 template <int BR, int TR, bool LOOP>
 static fate_status launch_layer_routed(hipStream_t st, int bits_s, int tpg_s, int grid, int lds_bytes, int lds_max,
                                        const LayerArgs& a) {

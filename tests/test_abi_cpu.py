@@ -178,7 +178,7 @@ def test_cpp_cache_matches_oracle_on_random_traces(seed):
 
 
 def test_cache_set_n_max_changes_the_prefetch_cap():
-    # section 4.2: the cap n is re-derived per phase; the C++ cache follows the oracle after a change
+    # section 4.3: the cap n is re-derived per phase; the C++ cache follows the oracle after a change
     nl, E = 3, 16
     ref = OC.CacheOracle(nl, E, 6, 0, 0, 2 * E)
     cc = _Cache(nl, E, 6, 0, 0, 2 * E)
@@ -285,3 +285,23 @@ def test_hybrid_width_of_the_prefetch_list_follows_the_oracle():
         assert cc.copy_bits.count(2) == seen_low
         cc.close()
     assert B.lib().fate_cache_set_low_precision(None, 25, 4, 2) == 1
+
+
+def test_cache_policy_under_address_and_ub_sanitizers(tmp_path):
+    """cache.cpp (host-only policy code) built with -fsanitize=address,undefined together with a driver that runs
+    random traces through every mode of the cache step and the co-activation predictor: any report aborts the run."""
+    import shutil
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    if shutil.which("g++") is None:
+        pytest.skip("no host compiler")
+    exe = str(tmp_path / "cache_san")
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-fno-omit-frame-pointer", os.path.join(root, "tests", "native", "cache_sanitizer_driver.cpp"),
+           os.path.join(root, "paper_2502_12224_amd", "csrc", "cache.cpp"), "-o", exe]
+    b = subprocess.run(cmd, capture_output=True, text=True)
+    assert b.returncode == 0, b.stderr[-2000:]
+    env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=1", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
+    assert r.returncode == 0, (r.stdout + r.stderr)[-3000:]
+    assert "cache sanitizer driver: ok" in r.stdout
