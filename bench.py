@@ -451,6 +451,15 @@ def bench_prefill(args, emit=True):
     if bad:
         raise SystemExit(f"bench.py: the FFN reported a non-zero status word {bad}: the timing is not valid")
 
+    if args.calibrate_copy:
+        # a plain device copy of known size, so that a counter run of this command can be scaled
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # roofline of the dominant kernel: the up/gate grouped GEMM (2/3 of the FLOPs)
     up_flops = 4.0 * H * (N * cfg.k * cfg.I + N * cfg.n_shared * (cfg.I_shared or 0))
     layer_flops = 1.5 * up_flops

@@ -9,7 +9,7 @@ LIB = os.path.join(HERE, "libfate.so")
 SOURCES = ["api.cpp", "route.hip", "pack.hip", "ffn.hip", "ffn_decode.hip", "layer_decode.hip", "layer_decode_b1.hip", "layer_decode_loop_r41.hip", "layer_decode_loop_r42.hip", "layer_decode_loop_r44.hip", "layer_decode_loop_r82.hip", "layer_decode_loop_r84.hip", "ffn_prefill.hip", "cache.cpp",
            "cache_hip.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = (["-DFATE_PROBE"] if os.environ.get("FATE_PROBE") else []) + ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-result", "-Wno-unknown-warning-option"]
 
 

@@ -127,10 +127,5 @@ fate_status launch_layer_decode(hipStream_t st, const fate_ffn_desc& d, LayerArg
     return FATE_OK;
 }
 
-#ifdef FATE_PROBE
-extern "C" int fate_debug_probe(unsigned long long* host_out, int nblocks) {
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_probe), (size_t)nblocks * 8 * sizeof(unsigned long long));
-}
-#endif
 
 }  // namespace fate

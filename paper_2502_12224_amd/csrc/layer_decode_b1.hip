@@ -21,12 +21,6 @@
 
 namespace fate {
 
-#ifdef FATE_PROBE
-__device__ unsigned long long g_probe_b1[1024 * 8];
-#define B1_TS(i) do { if (threadIdx.x == 0) g_pts[i] = wall_clock64(); } while (0)
-#else
-#define B1_TS(i) do { } while (0)
-#endif
 
 // ---- LDS of a down block -----------------------------------------------------------------
 constexpr int kB1HRegion = kB1MaxTiles * 64;          // halves of h per wave (tiles of at most 64 columns)
@@ -95,7 +89,6 @@ __device__ __forceinline__ void b1_up_issue(const WorkCtx& c, B1UpRegs<TPG>& R, 
     for (int jg = 0; jg < GR; ++jg)
 #pragma unroll
         for (int i = 0; i < 2; ++i) R.scr[i][jg] = ad.sc[i][(size_t)jg * c.I];
-    B1_TS(2);
 }
 
 template <int BITS, int TPG, class StoreX>
@@ -108,7 +101,6 @@ __device__ __forceinline__ uint32_t b1_up_compute(const WorkCtx& c, B1UpRegs<TPG
     const int rounds = tw / D;
     if (c.defer_x) store_x(true);
     lds_barrier();            // x and the zero row are in LDS
-    B1_TS(3);
     {   // sums of x times the codes' constant for this wave's groups: 8 lanes per token row
         constexpr int per = KT * TPG / 8;
         const int t = lane >> 3, sub = lane & 7;
@@ -136,7 +128,6 @@ __device__ __forceinline__ uint32_t b1_up_compute(const WorkCtx& c, B1UpRegs<TPG
     for (int r = 0; r + 1 < rounds; ++r)
         up_round<BITS, TPG, true>(R.raw, R.scr, ad.wt, ad.sc, I, r, xa, cxg, ctok, bc, out, [] {});
     up_round<BITS, TPG, false>(R.raw, R.scr, ad.wt, ad.sc, I, rounds - 1, xa, cxg, ctok, bc, out, [] {});
-    B1_TS(4);
     if (half == 0) {
         c.red[(wave * 2 + 0) * 32 + n] = out[0][0];
         c.red[(wave * 2 + 1) * 32 + n] = out[1][0];
@@ -289,7 +280,6 @@ __device__ __forceinline__ void b1_up_role(const B1Args& A, int ub, bool is_shar
         const int kb = ub - s * a.nkb_s;
         unsigned long long* hq_dst = A.a.hq + ((size_t)s * a.nkb_s + kb) * 16;
         const fate_qexpert ex = a.shared[s];
-        B1_TS(1);
         const bool absent = !b1_entry_usable(ex, a.bits_s, a.group_s);
         uint32_t hbits = 0;
         if (absent && tid == 0) atomicOr(a.status, 1);
@@ -346,7 +336,6 @@ __device__ __forceinline__ void b1_up_role(const B1Args& A, int ub, bool is_shar
     }
     uint32_t hbits = 0;
     if (ready) hbits = b1_up_compute<BR, TR>(cx, R, store_x);
-    B1_TS(1);
     b1_publish_h(hq_dst, tag, hbits);
 }
 
@@ -423,7 +412,6 @@ __device__ __forceinline__ float b1_down_product(const uint4 (&raw)[kB1MaxTiles]
             return 0.f;
         }
     }
-    B1_TS(3);
     const _Float16* ha = (n == 0 ? hl : zrow) + half * (KT / 2);
     const BiasConst bc = bias_const();
     const f32x16_t zero = f32x16_zero();
@@ -481,11 +469,9 @@ __device__ __forceinline__ void b1_down_role(const B1Args& A, int part, int rb, 
     if (is_shared) {
         const fate_qexpert ex = a.shared[it.ng > 0 ? it.src : 0];
         const unsigned long long* hq_src = A.a.hq + (size_t)it.src * a.nkb_s * 16 + (size_t)it.g0 * 64;
-        B1_TS(1);
         uint4 raw[kB1MaxTiles];
         uint32_t sc[kB1MaxTiles / TS];
         const int ng = it.ng > 0 ? b1_down_request<BS, TS>(ex, H, rb, it.g0, it.ng, raw, sc) : 0;
-        B1_TS(2);
         // the gate of the shared experts, evaluated behind the W2 requests, before the wait for h
         if (a.shared_gate != nullptr) {
             if (wave == 0) {
@@ -533,7 +519,6 @@ __device__ __forceinline__ void b1_down_role(const B1Args& A, int part, int rb, 
                     ng = b1_down_request<BR, TR>(ex, H, rb, it.g0, it.ng, raw, sc);
                 }
             }
-            B1_TS(2);
             // the weights of the selection, while the requests are in flight
             if (wave == 0) wave_softmax_topk_rounds(zl, E, k, a.r.renorm, ids, wv);
             lds_barrier();
@@ -541,7 +526,6 @@ __device__ __forceinline__ void b1_down_role(const B1Args& A, int part, int rb, 
             if (ng > 0) out = b1_down_product<BR, TR>(raw, sc, ng, hq_src, tag, hl, zrow, &failed, side, &side_val);
         }
     }
-    B1_TS(4);
     if (failed && lane == 0) atomicOr(a.status, 2);
     if (lane < 32) red[wave * 32 + lane] = wsrc * out;
     __syncthreads();
@@ -589,11 +573,6 @@ __global__ __launch_bounds__(kLayerThreads) __attribute__((amdgpu_waves_per_eu(2
     const LayerArgs& a = A.a;
     uint32_t tag = (uint32_t)ld_dev(a.sync) + 1u;
     if (tag == 0u) tag = 1u;
-#ifdef FATE_PROBE
-    const unsigned long long t_start = wall_clock64();
-    if (threadIdx.x < 8) g_pts[threadIdx.x] = 0;
-    __syncthreads();
-#endif
     int b = blockIdx.x;
     const int nd_s = A.nparts_s * A.nrb, nd_r = (A.nparts - A.nparts_s) * A.nrb;
     if (b < a.nb_route) {
@@ -611,11 +590,6 @@ __global__ __launch_bounds__(kLayerThreads) __attribute__((amdgpu_waves_per_eu(2
     }
     // the workgroup that leaves last opens the next epoch
     __syncthreads();
-    B1_TS(6);
-#ifdef FATE_PROBE
-    if (threadIdx.x < 8 && blockIdx.x < 1024)
-        g_probe_b1[blockIdx.x * 8 + threadIdx.x] = threadIdx.x == 0 ? t_start : g_pts[threadIdx.x];
-#endif
     if (threadIdx.x == 0 && atomicAdd(a.sync + 1, 1) == (int)gridDim.x - 1) {
         st_dev(a.sync + 1, 0);
         st_dev(a.sync, (int32_t)tag);
@@ -726,10 +700,5 @@ fate_status launch_layer_decode_b1(hipStream_t st, const fate_ffn_desc& d, const
     return FATE_OK;
 }
 
-#ifdef FATE_PROBE
-extern "C" int fate_debug_probe_b1(unsigned long long* host_out, int nblocks) {
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_probe_b1), (size_t)nblocks * 8 * sizeof(unsigned long long));
-}
-#endif
 
 }  // namespace fate

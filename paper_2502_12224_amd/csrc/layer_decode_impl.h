@@ -41,18 +41,6 @@ constexpr int kSpinMax = 1 << 18;
 constexpr int kUpRing = 8;        // tiles in flight per matrix per wave
 constexpr int kDownRing = 8;      // W2 pieces in flight per wave
 
-#ifdef FATE_PROBE
-// Timing probes (builds with -DFATE_PROBE only): per workgroup eight 100 MHz
-// timestamps, read back with fate_debug_probe().
-// The stamps stay in LDS until the workgroup leaves: a store to memory in the middle of
-// the work would sit in front of the next wait for outstanding memory operations.
-__device__ unsigned long long g_probe[4096 * 8];
-__shared__ unsigned long long g_pts[8];
-#define FATE_TS(i) do { if (threadIdx.x == 0) g_pts[i] = wall_clock64(); } while (0)
-#else
-#define FATE_TS(i) do { } while (0)
-#endif
-
 struct TaggedStore {
     unsigned long long* zq; int N, E; uint32_t tag;
     __device__ __forceinline__ void operator()(int g, int t, int e, float v) const {
@@ -86,7 +74,6 @@ __device__ __forceinline__ void route_role(const LayerArgs& a, int b, uint32_t t
     const int tid = threadIdx.x;
     const FusedRouteArgs& r = a.r;
     fused_gate_rows(r, b, TaggedStore{a.zq, r.N, r.E, tag});
-    FATE_TS(1);
     if (b != a.nb_route - 1) return;
     // the routing outputs of the API (consumers inside this launch do not read them)
     float* zl = reinterpret_cast<float*>(dyn);
@@ -95,9 +82,7 @@ __device__ __forceinline__ void route_role(const LayerArgs& a, int b, uint32_t t
         if (tid == 0) atomicOr(a.status, 2);
         return;
     }
-    FATE_TS(2);
     fused_select(r, rsm, nullptr, LdsLoad{zl, r.N, r.E});
-    FATE_TS(3);
 }
 
 // ---- Fast body: shapes whose per-wave share is a whole number of register rings ----
@@ -275,11 +260,9 @@ __device__ __forceinline__ void body_fast(const WorkCtx& c, LoadX&& load_x, Stor
     };
     auto issue = [&](piece_t (&d)[NQ], uint32_t (&sd)[NQ], int chunk) { issue_w(d, chunk); issue_s(sd, chunk); };
     issue_w(dA, 0);           // its scales follow once half of the ring has been consumed
-    FATE_TS(5);
     if (c.defer_x) store_x(true);
     if (c.is_shared) shared_gate();
     lds_barrier();            // x, token ids and weights are in LDS
-    FATE_TS(2);
     // bias sums of x for this wave's groups: 8 lanes per token, each a slice of the group
     {
         constexpr int per = KT * TPG / 8;            // columns per lane
@@ -310,7 +293,6 @@ __device__ __forceinline__ void body_fast(const WorkCtx& c, LoadX&& load_x, Stor
     up_round<BITS, TPG, false>(raw, scr, wt, sc, I, rounds - 1, xa, cxg, ctok, bc, out, [&] { issue_s(sA, 0); });
     const int nchunk = nq / NQ;
     if (nchunk > 1) issue(dB, sB, 1);     // the ring's registers are free now
-    FATE_TS(3);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -336,7 +318,6 @@ __device__ __forceinline__ void body_fast(const WorkCtx& c, LoadX&& load_x, Stor
         if (n == 0) c.ch[t] = bsum;
     }
     lds_barrier();
-    FATE_TS(4);
     // down projection: two matrix-core steps per piece (16 columns of h per half-wave)
     const _Float16* ha = c.hs + (n < T ? n : kTokPass) * kHsLd + 16 * half;
     float wj[4], chj[4];
@@ -465,7 +446,6 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
         part = a.part_s + ((size_t)s * a.nkb_s + kb) * N * H;
         part_stride = H;
         if (tid < N) tokid[tid] = tid;
-        FATE_TS(1);
     } else {
         uint4* tab = reinterpret_cast<uint4*>(dyn + L.tab);
         float* zl = reinterpret_cast<float*>(dyn + L.zl);
@@ -480,7 +460,6 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
                 if constexpr (LOOP) state |= 4;
                 return;
             }
-            FATE_TS(1);
             for (int t = wave; t < N; t += kLayerWaves)
                 wave_softmax_topk_rounds(zl + t * E, E, k, a.r.renorm, ids + t * k, wv + t * k);
             __syncthreads();
@@ -595,17 +574,14 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
             }                                                                                             \
         };                                                                                                \
         issue(dA, sA, 0);                                                                                 \
-        FATE_TS(5);                                                                                       \
         if (defer_x) store_x(true);                                                                       \
         if (is_shared) shared_gate();                                                                     \
         lds_barrier();            /* x, token ids and weights are in LDS */                               \
-        FATE_TS(2);                                                                                       \
         float out[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};                                   \
         const int arow = n < T ? tokid[n] : N;                                                            \
         ring_run<BITS, TPG, 2, kUpRing>(ring, wt, sc, I, g_beg, g_end,                                      \
                                         xs + arow * ldx + half * (QFmt<BITS>::KT / 2), 0, out);           \
         issue(dB, sB, 1);         /* the ring's registers are free now */                                 \
-        FATE_TS(3);                                                                                       \
         _Pragma("unroll")                                                                                 \
         for (int i = 0; i < 2; ++i)                                                                       \
             _Pragma("unroll")                                                                             \
@@ -623,7 +599,6 @@ __device__ __forceinline__ void work_role(const LayerArgs& a, int wb, uint32_t t
             hs[t * kHsLd + n32] = (_Float16)(a1 / (1.0f + expf(-a1)) * a3);                               \
         }                                                                                                 \
         lds_barrier();                                                                                    \
-        FATE_TS(4);                                                                                       \
         /* down projection of the 32 values of h: int8 spreads them over both half-waves (16 each),  */  \
         /* int4 keeps them in the half-wave that owns the columns                                    */  \
         const bool arow_ok = n < T && mine;                                                               \
@@ -706,11 +681,6 @@ __global__ __launch_bounds__(kLayerThreads) __attribute__((amdgpu_waves_per_eu(2
     char* dyn = reinterpret_cast<char*>(smem);
     uint32_t tag = (uint32_t)ld_dev(a.sync) + 1u;
     if (tag == 0u) tag = 1u;         // a zero-filled workspace must never look current
-#ifdef FATE_PROBE
-    const unsigned long long t_start = wall_clock64();
-    if (threadIdx.x < 8) g_pts[threadIdx.x] = 0;
-    __syncthreads();
-#endif
     const int b = blockIdx.x;
     if (b < a.nb_route) {
         route_role(a, b, tag, dyn, rsm);
@@ -728,10 +698,6 @@ __global__ __launch_bounds__(kLayerThreads) __attribute__((amdgpu_waves_per_eu(2
     }
     // the workgroup that leaves last opens the next epoch
     __syncthreads();
-    FATE_TS(6);
-#ifdef FATE_PROBE
-    if (threadIdx.x < 8 && blockIdx.x < 4096) g_probe[blockIdx.x * 8 + threadIdx.x] = threadIdx.x == 0 ? t_start : g_pts[threadIdx.x];
-#endif
     if (threadIdx.x == 0 && atomicAdd(a.sync + 1, 1) == (int)gridDim.x - 1) {
         st_dev(a.sync + 1, 0);
         st_dev(a.sync, (int32_t)tag);
