@@ -323,7 +323,9 @@ def bench_decode(args):
                    "prediction_accuracy_topk": acc_k, "prediction_recall_topm": rec_m, "m": cfg.m,
                    "near_tie_rows": near_ties, "routed_rows": S * N * L,
                    "cache_hit_rate": tot["hits"] / max(1, tot["hits"] + tot["misses"])},
-        "roofline": {"bound": "hbm", "kernel": "moe_layer_decode_kernel + layer_reduce_kernel", "achieved": achieved,
+        "roofline": {"bound": "hbm",
+                     "kernel": "moe_layer_decode_b1_kernel (one launch per layer)" if qwen else "moe_layer_decode_kernel + layer_reduce_kernel",
+                     "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic("decode_qwen_b1_traffic.txt") if qwen else None,
                      "bytes_per_launch": layer_bytes, "us_per_launch": kern_us},
