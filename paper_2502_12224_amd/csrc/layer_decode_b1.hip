@@ -5,17 +5,18 @@
 //                       epoch-tagged words; the last one writes the API's routing outputs
 //   shared up blocks    32 intermediate neurons of a shared expert: W1 / W3 row block, SwiGLU,
 //                       h published as tagged pairs of fp16
-//   shared down blocks  32 output rows: each wave fetches its K range of W2 of a shared expert
-//                       first, then polls the h of that range, multiplies, and the block
-//                       publishes a tagged partial output
-//   routed up blocks    as the shared ones, after polling the logits and redoing the selection
+//   routed up blocks    as the shared ones, after polling the logits and finding the slot's expert
 //                       (slot j = the expert with the j-th largest logit)
-//   routed down blocks  as the shared ones; the last block of an output row block polls the
-//                       other blocks' partial outputs, adds them in a fixed order and writes y
+//   down blocks         32 output rows: each wave fetches a K range of W2 of a shared expert at once
+//                       and a K range of W2 of a routed slot as soon as the selection is known,
+//                       polls the shared h of its range and multiplies, then the routed h; the
+//                       block publishes a tagged partial output, and the last block of an output
+//                       row block polls the other blocks' partial outputs, adds them in a fixed
+//                       order and writes y
 // Every wait is on data of blocks with lower ids, bounded, and turns into status bit 1.
 // Requests that do not depend on the routing (shared W1 / W3 / W2) all go out at the start;
 // W2 of the routed experts goes out as soon as a down block knows the selection, long before
-// the routed h exists.
+// the routed h exists; when it exists, half of every down wave's products are already done.
 #include "layer_decode_impl.h"
 #include "layer_decode_b1.h"
 
@@ -25,7 +26,7 @@ namespace fate {
 // ---- LDS of a down block -----------------------------------------------------------------
 constexpr int kB1HRegion = kB1MaxTiles * 64;          // halves of h per wave (tiles of at most 64 columns)
 struct B1DownLds {
-    int hl, zrow, red, tab, zl, ids, w, src_e, src_w, gate, bytes;
+    int hl, zrow, red, red2, tab, zl, ids, w, src_e, src_w, gate, bytes;
 };
 __host__ __device__ inline B1DownLds b1_down_lds(int E, int k) {
     auto up = [](int v) { return (v + 15) & ~15; };
@@ -34,6 +35,7 @@ __host__ __device__ inline B1DownLds b1_down_lds(int E, int k) {
     L.hl = off; off += up(kLayerWaves * kB1HRegion * 2);
     L.zrow = off; off += up(kB1HRegion * 2);
     L.red = off; off += up(kLayerWaves * 32 * 4);
+    L.red2 = off; off += up(kLayerWaves * 32 * 4);
     L.tab = off; off += up(E * (int)sizeof(fate_qexpert));
     L.zl = off; off += up(2 * E * 4);
     L.ids = off; off += up(k * 4);
@@ -418,30 +420,32 @@ __device__ __forceinline__ float b1_down_product(const uint4 (&raw)[kB1MaxTiles]
     float out = 0.f;
     // two groups at a time, each with an accumulator of its own: the dependent matrix-core steps
     // of one group run under those of the other
-    static_assert(MAXG % 2 == 0, "groups are taken in pairs");
 #pragma unroll
     for (int jg = 0; jg < MAXG; jg += 2) {
-        f32x16_t acc0, acc1;
+        constexpr bool kOdd = MAXG % 2 != 0;
+        const bool pair = !kOdd || jg + 1 < MAXG;
+        f32x16_t acc0, acc1 = zero;
 #pragma unroll
         for (int tl = 0; tl < TPG; ++tl) {
-            const int j0 = jg * TPG + tl, j1 = (jg + 1) * TPG + tl;
+            const int j0 = jg * TPG + tl, j1 = pair ? (jg + 1) * TPG + tl : j0;
             f16x8_t a0[S], a1[S], b0[S], b1[S];
 #pragma unroll
             for (int st = 0; st < S; ++st) {
                 a0[st] = *reinterpret_cast<const f16x8_t*>(ha + j0 * KT + 8 * st);
-                a1[st] = *reinterpret_cast<const f16x8_t*>(ha + j1 * KT + 8 * st);
+                if (pair) a1[st] = *reinterpret_cast<const f16x8_t*>(ha + j1 * KT + 8 * st);
             }
             biased_tile<BITS>(raw[j0], bc, b0);
-            biased_tile<BITS>(raw[j1], bc, b1);
+            if (pair) biased_tile<BITS>(raw[j1], bc, b1);
 #pragma unroll
             for (int st = 0; st < S; ++st) {
                 acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0[st], b0[st], (tl == 0 && st == 0) ? zero : acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1[st], b1[st], (tl == 0 && st == 0) ? zero : acc1, 0, 0, 0);
+                if (pair)
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1[st], b1[st], (tl == 0 && st == 0) ? zero : acc1, 0, 0, 0);
             }
         }
         // groups past the item's end multiply stale h with repeated tiles: they do not count
         if (jg < ng) out = fmaf(half_bits_to_float(sc[jg]), acc0[0] - ch[jg], out);
-        if (jg + 1 < ng) out = fmaf(half_bits_to_float(sc[jg + 1]), acc1[0] - ch[jg + 1], out);
+        if (pair && jg + 1 < ng) out = fmaf(half_bits_to_float(sc[pair ? jg + 1 : jg]), acc1[0] - ch[pair ? jg + 1 : jg], out);
     }
     return out;
 }
@@ -454,84 +458,92 @@ __device__ __forceinline__ void b1_down_role(const B1Args& A, int part, int rb, 
     const B1DownLds L = b1_down_lds(E, k);
     _Float16* hl = reinterpret_cast<_Float16*>(dyn + L.hl) + wave * kB1HRegion;
     _Float16* zrow = reinterpret_cast<_Float16*>(dyn + L.zrow);
-    float* red = reinterpret_cast<float*>(dyn + L.red);
+    float* red_s = reinterpret_cast<float*>(dyn + L.red);
+    float* red_r = reinterpret_cast<float*>(dyn + L.red2);
     float* gate = reinterpret_cast<float*>(dyn + L.gate);
-    const bool is_shared = part < A.nparts_s;
-    const B1Item it = A.items[part * kLayerWaves + wave];
+    uint4* tab = reinterpret_cast<uint4*>(dyn + L.tab);
+    float* zl = reinterpret_cast<float*>(dyn + L.zl);
+    int32_t* ids = reinterpret_cast<int32_t*>(dyn + L.ids);
+    float* wv = reinterpret_cast<float*>(dyn + L.w);
+    int32_t* src_e = reinterpret_cast<int32_t*>(dyn + L.src_e);
+    int32_t* src_r = reinterpret_cast<int32_t*>(dyn + L.src_w);
+    const B1Item its = A.items_s[part * kLayerWaves + wave], itr = A.items_r[part * kLayerWaves + wave];
     for (int c = tid; c < kB1HRegion / 8; c += kLayerThreads)
         *reinterpret_cast<uint4*>(zrow + c * 8) = make_uint4(0, 0, 0, 0);
     lds_barrier();
-    float wsrc = 1.f;
     bool failed = false;
-    float out = 0.f;
+    float out_s = 0.f, out_r = 0.f, wsrc = 1.f;
+
+    // the wave's piece of a shared expert: requested at once
+    uint4 raw_s[kB1MaxTiles];
+    uint32_t sc_s[kB1MaxTiles / TS];
+    int ng_s = 0;
+    if (its.ng > 0) {
+        const fate_qexpert ex = a.shared[its.src];
+        ng_s = b1_down_request<BS, TS>(ex, H, rb, its.g0, its.ng, raw_s, sc_s);
+    }
+    const unsigned long long* hq_s = A.a.hq + (size_t)its.src * a.nkb_s * 16 + (size_t)its.g0 * 64;
+    // the gate of the shared experts, evaluated behind those requests
+    if (a.shared_gate != nullptr) {
+        if (wave == 0) {
+            const float g = wave_sigmoid_dot_bf16(reinterpret_cast<const uint4*>(a.r.x),
+                                                  reinterpret_cast<const uint4*>(a.shared_gate), H >> 3);
+            if (lane == 0) gate[0] = g;
+        }
+    } else if (tid == 0) {
+        gate[0] = 1.f;
+    }
+
+    // the wave's piece of a routed slot: with a hint the hinted expert's W2 slice is requested before
+    // the gate is known, else (or if the hint was wrong) as soon as the slot's expert is
+    const int slot = itr.ng > 0 ? itr.src : 0;
+    const unsigned long long* hq_r =
+        A.a.hq + ((size_t)a.n_shared * a.nkb_s + (size_t)slot * a.nkb_r) * 16 + (size_t)itr.g0 * 64;
+    uint4 raw_r[kB1MaxTiles];
+    uint32_t sc_r[kB1MaxTiles / TR];
+    // the block that writes y (two parts): its wave 0 reads the other part's partial output of its
+    // row along with the polls of the routed h, lanes 0..31
     const unsigned long long* side = nullptr;
     unsigned long long side_val = 0;
-    if (is_shared) {
-        const fate_qexpert ex = a.shared[it.ng > 0 ? it.src : 0];
-        const unsigned long long* hq_src = A.a.hq + (size_t)it.src * a.nkb_s * 16 + (size_t)it.g0 * 64;
-        uint4 raw[kB1MaxTiles];
-        uint32_t sc[kB1MaxTiles / TS];
-        const int ng = it.ng > 0 ? b1_down_request<BS, TS>(ex, H, rb, it.g0, it.ng, raw, sc) : 0;
-        // the gate of the shared experts, evaluated behind the W2 requests, before the wait for h
-        if (a.shared_gate != nullptr) {
-            if (wave == 0) {
-                const float g = wave_sigmoid_dot_bf16(reinterpret_cast<const uint4*>(a.r.x),
-                                                      reinterpret_cast<const uint4*>(a.shared_gate), H >> 3);
-                if (lane == 0) gate[0] = g;
-            }
-        } else if (tid == 0) {
-            gate[0] = 1.f;
-        }
-        if (ng > 0) out = b1_down_product<BS, TS>(raw, sc, ng, hq_src, tag, hl, zrow, &failed);
-    } else {
-        uint4* tab = reinterpret_cast<uint4*>(dyn + L.tab);
-        float* zl = reinterpret_cast<float*>(dyn + L.zl);
-        int32_t* ids = reinterpret_cast<int32_t*>(dyn + L.ids);
-        float* wv = reinterpret_cast<float*>(dyn + L.w);
-        int32_t* src_e = reinterpret_cast<int32_t*>(dyn + L.src_e);
-        int32_t* src_r = reinterpret_cast<int32_t*>(dyn + L.src_w);
-        const int slot = it.ng > 0 ? it.src - a.n_shared : 0;
-        const unsigned long long* hq_src =
-            A.a.hq + ((size_t)a.n_shared * a.nkb_s + (size_t)slot * a.nkb_r) * 16 + (size_t)it.g0 * 64;
-        uint4 raw[kB1MaxTiles];
-        uint32_t sc[kB1MaxTiles / TR];
-        // the block that writes y (two parts): its wave 0 reads the other part's partial output of
-        // its row along with the polls of h, lanes 0..31
-        if (wave == 0 && lane < 32 && A.nparts == 2 && part == 1) side = A.a.yq + rb * 32 + lane;
-        // with a hint the W2 slice of the hinted expert is requested before the gate is known
-        int e_cur = -1, ng = 0;
-        if (a.hint != nullptr && it.ng > 0) {
-            e_cur = a.hint[slot];
-            if (e_cur < 0 || e_cur >= E) e_cur = -1;
-            if (e_cur >= 0) {
-                const fate_qexpert exh = a.experts[e_cur];
-                ng = b1_down_request<BR, TR>(exh, H, rb, it.g0, it.ng, raw, sc);
-            }
-        }
-        int e_true = -1, rank = 0;
-        if (!b1_slot_expert(A, tag, slot, tab, zl, ids, src_e, src_r, &e_true, &rank)) {
-            failed = true;
-        } else {
-            if (it.ng > 0 && e_true != e_cur) {
-                ng = 0;
-                if (e_true >= 0) {
-                    const fate_qexpert ex = reinterpret_cast<const fate_qexpert*>(tab)[e_true];
-                    ng = b1_down_request<BR, TR>(ex, H, rb, it.g0, it.ng, raw, sc);
-                }
-            }
-            // the weights of the selection, while the requests are in flight
-            if (wave == 0) wave_softmax_topk_rounds(zl, E, k, a.r.renorm, ids, wv);
-            lds_barrier();
-            wsrc = wv[rank];
-            if (ng > 0) out = b1_down_product<BR, TR>(raw, sc, ng, hq_src, tag, hl, zrow, &failed, side, &side_val);
+    if (wave == 0 && lane < 32 && A.nparts == 2 && part == 1) side = A.a.yq + rb * 32 + lane;
+    int e_cur = -1, ng_r = 0;
+    if (a.hint != nullptr && itr.ng > 0) {
+        e_cur = a.hint[slot];
+        if (e_cur < 0 || e_cur >= E) e_cur = -1;
+        if (e_cur >= 0) {
+            const fate_qexpert exh = a.experts[e_cur];
+            ng_r = b1_down_request<BR, TR>(exh, H, rb, itr.g0, itr.ng, raw_r, sc_r);
         }
     }
+    int e_true = -1, rank = 0;
+    if (!b1_slot_expert(A, tag, slot, tab, zl, ids, src_e, src_r, &e_true, &rank)) {
+        failed = true;
+    } else {
+        if (itr.ng > 0 && e_true != e_cur) {
+            ng_r = 0;
+            if (e_true >= 0) {
+                const fate_qexpert ex = reinterpret_cast<const fate_qexpert*>(tab)[e_true];
+                ng_r = b1_down_request<BR, TR>(ex, H, rb, itr.g0, itr.ng, raw_r, sc_r);
+            }
+        }
+        // the weights of the selection, while the requests are in flight
+        if (wave == 0) wave_softmax_topk_rounds(zl, E, k, a.r.renorm, ids, wv);
+        lds_barrier();
+        wsrc = wv[rank];
+    }
+    // the shared piece first: its h exists long before the routed one
+    if (ng_s > 0) out_s = b1_down_product<BS, TS>(raw_s, sc_s, ng_s, hq_s, tag, hl, zrow, &failed);
+    if (ng_r > 0 && !failed)
+        out_r = b1_down_product<BR, TR>(raw_r, sc_r, ng_r, hq_r, tag, hl, zrow, &failed, side, &side_val);
     if (failed && lane == 0) atomicOr(a.status, 2);
-    if (lane < 32) red[wave * 32 + lane] = wsrc * out;
+    if (lane < 32) {
+        red_s[wave * 32 + lane] = out_s;
+        red_r[wave * 32 + lane] = wsrc * out_r;
+    }
     __syncthreads();
-    const float gsh = is_shared ? gate[0] : 1.f;
     if (tid < 32) {
-        float v = gsh * ((red[tid] + red[32 + tid]) + (red[64 + tid] + red[96 + tid]));
+        float v = gate[0] * ((red_s[tid] + red_s[32 + tid]) + (red_s[64 + tid] + red_s[96 + tid])) +
+                  ((red_r[tid] + red_r[32 + tid]) + (red_r[64 + tid] + red_r[96 + tid]));
         const int row = rb * 32 + tid;
         if (part + 1 < A.nparts) {
             __hip_atomic_store(A.a.yq + (size_t)part * H + row,
@@ -574,19 +586,17 @@ __global__ __launch_bounds__(kLayerThreads) __attribute__((amdgpu_waves_per_eu(2
     uint32_t tag = (uint32_t)ld_dev(a.sync) + 1u;
     if (tag == 0u) tag = 1u;
     int b = blockIdx.x;
-    const int nd_s = A.nparts_s * A.nrb, nd_r = (A.nparts - A.nparts_s) * A.nrb;
+    const int nd = A.nparts * A.nrb;
     if (b < a.nb_route) {
         route_role(a, b, tag, dyn, rsm);
     } else if ((b -= a.nb_route) < A.n_up_s) {
         b1_up_role<BR, TR, BS, TS, false>(A, b, true, tag, dyn);
-    } else if ((b -= A.n_up_s) < nd_s) {
-        b1_down_role<BR, TR, BS, TS>(A, b / A.nrb, b % A.nrb, tag, dyn);
-    } else if ((b -= nd_s) < A.n_up_r) {
+    } else if ((b -= A.n_up_s) < A.n_up_r) {
         // (two copies of the routed up block: without a hint there is one place that asks for weights)
         if (a.hint != nullptr) b1_up_role<BR, TR, BS, TS, true>(A, b, false, tag, dyn);
         else b1_up_role<BR, TR, BS, TS, false>(A, b, false, tag, dyn);
-    } else if ((b -= A.n_up_r) < nd_r) {
-        b1_down_role<BR, TR, BS, TS>(A, A.nparts_s + b / A.nrb, b % A.nrb, tag, dyn);
+    } else if ((b -= A.n_up_r) < nd) {
+        b1_down_role<BR, TR, BS, TS>(A, b / A.nrb, b % A.nrb, tag, dyn);
     }
     // the workgroup that leaves last opens the next epoch
     __syncthreads();
@@ -668,24 +678,23 @@ bool b1_plan(const fate_ffn_desc& d, const LayerArgs& a, B1Args* b, int* nblocks
     b->nrb = d.H / 32;
     b->n_up_s = d.n_shared * a.nkb_s;
     b->n_up_r = d.k * a.nkb_r;
-    for (int i = 0; i < kB1MaxItems; ++i) b->items[i] = B1Item{0, 0, 0, 0};
-    int n = 0;
+    for (int i = 0; i < kB1MaxItems; ++i) b->items_s[i] = b->items_r[i] = B1Item{0, 0, 0, 0};
+    int ns = 0, nr = 0;
     const int maxg_s = kB1MaxTiles / (group_s / kt_s), maxg_r = kB1MaxTiles / (d.group / kt_r);
     for (int s = 0; s < d.n_shared; ++s)
-        if ((n = b1_add_items(b->items, n, s, d.I_shared_max / group_s, maxg_s)) < 0) return false;
-    n = (n + kLayerWaves - 1) / kLayerWaves * kLayerWaves;        // routed items start in a block of their own
-    b->nparts_s = n / kLayerWaves;
+        if ((ns = b1_add_items(b->items_s, ns, s, d.I_shared_max / group_s, maxg_s)) < 0) return false;
     for (int j = 0; j < d.k; ++j)
-        if ((n = b1_add_items(b->items, n, d.n_shared + j, d.I_max / d.group, maxg_r)) < 0) return false;
-    b->nparts = (n + kLayerWaves - 1) / kLayerWaves;
-    if (b->nparts > kB1MaxItems / kLayerWaves) return false;
+        if ((nr = b1_add_items(b->items_r, nr, j, d.I_max / d.group, maxg_r)) < 0) return false;
+    b->nparts = (std::max(ns, nr) + kLayerWaves - 1) / kLayerWaves;
+    if (b->nparts < 1 || b->nparts > kLayerMaxParts) return false;
     *nblocks = a.nb_route + b->n_up_s + b->n_up_r + b->nparts * b->nrb;
-    // The routing blocks and everything of the shared experts must be on the device from the start
-    // (their requests do not wait for anything); the routed blocks have nothing to do before the
-    // logits exist and may start as earlier blocks leave (a block only waits for lower ids).  A
-    // launch several times larger than the device is left to the general kernel.
+    // The routing blocks and the shared experts' up blocks must be on the device from the start
+    // (their requests do not wait for anything); the other blocks have nothing to do before the
+    // logits exist and may start as earlier blocks leave (a block only waits for lower ids) - the
+    // down blocks then ask for their shared W2 pieces later, nothing else changes.  A launch
+    // several times larger than the device is left to the general kernel.
     const int resident = b1_resident_blocks(d);
-    const int early = a.nb_route + b->n_up_s + b->nparts_s * b->nrb;
+    const int early = a.nb_route + b->n_up_s;
     return resident > 0 && early <= resident && *nblocks <= 2 * resident;
 }
 
