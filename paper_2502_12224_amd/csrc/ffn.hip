@@ -43,8 +43,14 @@ static void carve(const fate_ffn_desc& d, void* base, FfnWorkspace* w) {
     w->h_s = reinterpret_cast<__half*>(p + off);
     off += align_up((size_t)d.n_shared * d.N * (d.n_shared ? d.I_shared_max : 0) * 2, 256);
     const bool mfma = d.mode == 2 || (d.mode == 0 && d.N > 16);
-    w->ybuf = reinterpret_cast<float*>(p + off);
-    if (!d.y_is_fp32 && !mfma) off += align_up((size_t)d.N * d.H * 4, 256);
+    w->part_r = w->part_s = reinterpret_cast<float*>(p + off);
+    if (!mfma) {
+        const int ncr = decode_down_chunks(d.I_max / d.group);
+        const int ncs = d.n_shared ? decode_down_chunks(d.I_shared_max / d.shared_group) : 0;
+        off += align_up((size_t)d.N * d.k * ncr * d.H * 4, 256);
+        w->part_s = reinterpret_cast<float*>(p + off);
+        off += align_up((size_t)d.n_shared * ncs * d.N * d.H * 4, 256);
+    }
     if (mfma) {
         const size_t nseg1 = (size_t)d.E + d.n_shared + 1;
         w->ms.xh = reinterpret_cast<__half*>(p + off); off += align_up((size_t)d.N * d.H * 2, 256);
@@ -102,7 +108,7 @@ static fate_status ffn_q_phase(int phase, const PartSel& sel, void* stream, cons
     a.bits_s = d->n_shared ? d->shared_bits : d->bits; a.group_s = d->n_shared ? d->shared_group : d->group;
     a.h_r = w.h_r; a.ldh_r = d->I_max;
     a.h_s = w.h_s; a.ldh_s = d->n_shared ? d->I_shared_max : 0;
-    a.y = d->y_is_fp32 ? static_cast<float*>(y) : w.ybuf;
+    a.part_r = w.part_r; a.part_s = w.part_s;
     a.status = w.status;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int mode = d->mode ? d->mode : (d->N <= 16 ? 1 : 2);

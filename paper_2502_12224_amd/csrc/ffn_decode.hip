@@ -1,13 +1,16 @@
 // Decode-side expert FFN behind fate_moe_ffn_q: bandwidth-bound dequant-GEMV
-// kernels, two launches per layer.
+// kernels, three launches per layer.
 //  up:   a workgroup owns 32 intermediate neurons of one activated expert (or
 //        of a shared expert): it streams the matching 32-row blocks of W1 and
 //        W3 (device-native 1 KiB tiles, one contiguous KiB per wave load),
 //        the four waves splitting the reduction dimension, and writes
-//        h = silu(W1 x) * (W3 x) as fp16.  It also clears its slice of y.
+//        h = silu(W1 x) * (W3 x) as fp16.
 //  down: a workgroup owns 32 output rows of W2 of one expert and a chunk of
-//        the reduction dimension, and adds weight * (W2 h) into y (fp32
-//        atomics; at most a few contributions per element).
+//        the reduction dimension, and stores weight * (W2 h) as a partial
+//        output row of its own (per pair and chunk; per shared expert, chunk
+//        and token).
+//  sum:  adds a token's partial rows in a fixed order and writes y - the
+//        result does not depend on the order in which workgroups ran.
 // Every wave requests its first tiles before anything else and keeps a ring
 // of them in flight (decode_device.h), so the HBM stream starts while the
 // activations are still being staged in LDS.
@@ -73,13 +76,6 @@ __global__ __launch_bounds__(256, 2) void ffn_up_decode_kernel(DecodeArgs a) {
             if (tid == 0) atomicOr(a.status, 1);
             live = false;
         }
-    }
-    {   // clear this block's slice of y
-        const long long total = (long long)a.N * a.H;
-        const long long per = (total + gridDim.x - 1) / gridDim.x;
-        const long long b0 = (long long)blockIdx.x * per;
-        const long long b1 = b0 + per < total ? b0 + per : total;
-        for (long long i = b0 + tid; i < b1; i += 256) a.y[i] = 0.f;
     }
     if (!live) return;
     const int H = a.H, nvec = H >> 3, G = H / group;
@@ -172,7 +168,7 @@ __global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
     int b = blockIdx.x;
     const int nrout = a.nact * nrb * a.nchunk_r;
     const fate_qexpert* ex;
-    int rb, ch, cg, T, sbeg = 0, bits, group, ldh;
+    int rb, ch, cg, T, sbeg = 0, bits, group, ldh, sidx = 0;
     const __half* hbuf;
     const bool is_shared = b >= nrout;
     if (!is_shared) {
@@ -191,29 +187,42 @@ __global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
         const int rem = b - s * (nrb * a.nchunk_s);
         rb = rem / a.nchunk_s; ch = rem - rb * a.nchunk_s; cg = a.cg_s;
         ex = a.shared + s;
+        sidx = s;
         T = a.N;
         hbuf = a.h_s + (size_t)s * a.N * a.ldh_s; ldh = a.ldh_s;
     }
     bits = ex->bits; group = ex->group;
-    if (!entry_format_ok(bits, group, a.H, ex->I)) return;     // flagged by the up kernel
+    // this block's partial output rows: per pair (sorted order) and chunk, or per shared expert, chunk and token
+    const int nchunk = is_shared ? a.nchunk_s : a.nchunk_r;
+    auto part_row = [&](int t) -> float* {
+        return is_shared ? a.part_s + (((size_t)sidx * nchunk + ch) * a.N + t) * a.H
+                         : a.part_r + ((size_t)(sbeg + t) * nchunk + ch) * a.H;
+    };
+    auto nothing = [&]() {      // a block without weights to multiply still owes its rows: zeros
+        for (int i = tid; i < T * 32; i += 256) part_row(i >> 5)[rb * 32 + (i & 31)] = 0.f;
+    };
+    if (!entry_format_ok(bits, group, a.H, ex->I)) {          // flagged by the up kernel
+        nothing();
+        return;
+    }
     // the launch cut the reduction dimension into chunks of cg groups of the descriptor's group size
     cg = cg * (is_shared ? a.group_s : a.group_r) / group;
     const int I = ex->I, G = I / group;
     const int gb = ch * cg, ge = min(G, gb + cg);
-    if (gb >= ge) return;
     gu4_t w2 = as_global<uint4>(ex->w2);
-    if (w2 == nullptr) return;   // flagged by the up kernel
+    const bool has_z = ex->z1 != nullptr;
+    const bool bad_z = has_z && (bits == 8 || ex->z2 == nullptr || ex->z3 == nullptr || a.H / group > kZpMaxGroups ||
+                                 ge - gb > kZpChunkGroups);
+    if (bad_z && tid == 0) atomicOr(a.status, 4);
+    if (gb >= ge || w2 == nullptr || ex->w1 == nullptr || ex->w3 == nullptr || bad_z) {   // (a missing expert is flagged by the up kernel)
+        nothing();
+        return;
+    }
     const int KT = tile_columns(bits);
     const int tiles_k = I / KT, tpg = group / KT;
     const int n = lane & 31, half = lane >> 5;
     gu4_t wt[1] = {w2 + (size_t)rb * tiles_k * 64 + lane};
     gu16_t sc[1] = {as_global<uint16_t>(ex->s2) + rb * 32 + n};
-    const bool has_z = ex->z1 != nullptr;
-    if (has_z && (bits == 8 || ex->z2 == nullptr || ex->z3 == nullptr || a.H / group > kZpMaxGroups ||
-                  ge - gb > kZpChunkGroups)) {
-        if (tid == 0) atomicOr(a.status, 4);
-        return;
-    }
     gu16_t zp[1] = {as_global<uint16_t>(has_z ? ex->z2 : ex->s2) + rb * 32 + n};
     const int srows = a.H;
     const int ng = ge - gb;
@@ -248,17 +257,10 @@ __global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
         if (tid < 32 * nt) {
             const int t = tid >> 5, nn = tid & 31;
             const float v = red[0][t][nn] + red[1][t][nn] + red[2][t][nn] + red[3][t][nn];
-            int tok;
             float wgt;
-            if (is_shared) {
-                tok = t0 + t;
-                wgt = a.shared_gate ? sgate[t] : 1.0f;
-            } else {
-                const int p = a.perm[sbeg + t0 + t];
-                tok = p / a.k;
-                wgt = a.topk_w[p];
-            }
-            atomicAdd(a.y + (size_t)tok * a.H + rb * 32 + nn, wgt * v);
+            if (is_shared) wgt = a.shared_gate ? sgate[t] : 1.0f;
+            else wgt = a.topk_w[a.perm[sbeg + t0 + t]];
+            part_row(t0 + t)[rb * 32 + nn] = wgt * v;
         }
     };
 
@@ -298,9 +300,31 @@ __global__ __launch_bounds__(256) void ffn_down_decode_kernel(DecodeArgs a) {
 #undef FATE_DOWN_BODY_
 }
 
-__global__ void f32_to_bf16_kernel(const float* __restrict__ src, uint16_t* __restrict__ dst, long long n) {
-    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) dst[i] = (uint16_t)f32_to_bf16_bits(src[i]);
+// y[t,:] = sum over the token's pairs (in pair order) and their chunks, then over the shared experts and theirs
+__global__ __launch_bounds__(256) void ffn_sum_decode_kernel(DecodeArgs a, void* y_out, int y_is_fp32) {
+    const int t = blockIdx.x;
+    const int H = a.H;
+    for (int c = threadIdx.x; c < (H >> 2); c += 256) {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        auto add = [&](const float* row) {
+            const float4 v = reinterpret_cast<const float4*>(row)[c];
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        };
+        for (int j = 0; j < a.k; ++j) {
+            const int pos = a.inv_perm[t * a.k + j];
+            if (pos < 0) continue;                       // a pair whose expert id was out of range
+            for (int ch = 0; ch < a.nchunk_r; ++ch) add(a.part_r + ((size_t)pos * a.nchunk_r + ch) * H);
+        }
+        for (int s = 0; s < a.n_shared; ++s)
+            for (int ch = 0; ch < a.nchunk_s; ++ch) add(a.part_s + (((size_t)s * a.nchunk_s + ch) * a.N + t) * H);
+        if (y_is_fp32) {
+            reinterpret_cast<float4*>(static_cast<float*>(y_out) + (size_t)t * H)[c] = acc;
+        } else {
+            const uint32_t lo = f32_to_bf16_bits(acc.x) | (f32_to_bf16_bits(acc.y) << 16);
+            const uint32_t hi = f32_to_bf16_bits(acc.z) | (f32_to_bf16_bits(acc.w) << 16);
+            reinterpret_cast<uint2*>(static_cast<uint16_t*>(y_out) + (size_t)t * H)[c] = make_uint2(lo, hi);
+        }
+    }
 }
 
 constexpr size_t kLdsMax = 96 * 1024;
@@ -309,8 +333,8 @@ fate_status launch_ffn_decode(hipStream_t st, const fate_ffn_desc& d, DecodeArgs
     if (!decode_group_ok(d.bits, d.group) || (d.n_shared && !decode_group_ok(d.shared_bits, d.shared_group)))
         FATE_FAIL(FATE_ESHAPE, "decode path: group must be 64, 128 or 256 (int4) / 64 or 128 (int8)");
     const int Gr = d.I_max / d.group, Gs = d.n_shared ? d.I_shared_max / d.shared_group : 0;
-    a.nchunk_r = (Gr + 15) / 16; a.cg_r = (Gr + a.nchunk_r - 1) / a.nchunk_r;
-    a.nchunk_s = Gs ? (Gs + 15) / 16 : 1; a.cg_s = Gs ? (Gs + a.nchunk_s - 1) / a.nchunk_s : 1;
+    a.nchunk_r = decode_down_chunks(Gr); a.cg_r = (Gr + a.nchunk_r - 1) / a.nchunk_r;
+    a.nchunk_s = decode_down_chunks(Gs); a.cg_s = Gs ? (Gs + a.nchunk_s - 1) / a.nchunk_s : 1;
     // LDS: the activation rows of one pass + one zero row, fp16, padded
     a.lds_rows = (d.N < kTokPass ? d.N : kTokPass) + 1;
     const size_t lu = (size_t)a.lds_rows * (d.H + kLdsPad) * 2;
@@ -334,11 +358,8 @@ fate_status launch_ffn_decode(hipStream_t st, const fate_ffn_desc& d, DecodeArgs
     ffn_up_decode_kernel<<<grid_up, 256, lu, st>>>(a);
     ffn_down_decode_kernel<<<grid_down, 256, ld, st>>>(a);
     FATE_HIP(hipGetLastError());
-    if (!d.y_is_fp32) {
-        const long long n = (long long)d.N * d.H;
-        f32_to_bf16_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(a.y, static_cast<uint16_t*>(y_out), n);
-        FATE_HIP(hipGetLastError());
-    }
+    ffn_sum_decode_kernel<<<d.N, 256, 0, st>>>(a, y_out, d.y_is_fp32);
+    FATE_HIP(hipGetLastError());
     return FATE_OK;
 }
 

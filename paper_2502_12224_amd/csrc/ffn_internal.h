@@ -23,7 +23,8 @@ struct DecodeArgs {
     int bits_r, group_r, bits_s, group_s;
     __half* h_r; int ldh_r;   // [P][I_max] fp16, rows in sorted pair order
     __half* h_s; int ldh_s;   // [n_shared*N][I_shared_max] fp16
-    float* y;                 // [N,H] fp32 accumulator
+    float* part_r;            // [P][nchunk_r][H] fp32: weighted partial outputs, rows in sorted pair order
+    float* part_s;            // [n_shared][nchunk_s][N][H] fp32 (gated)
     int32_t* status;
     int nchunk_r, nchunk_s, cg_r, cg_s;   // reduction chunks of the down kernel
     int lds_rows;        // activation rows staged in LDS per pass, plus one zero row
@@ -42,12 +43,15 @@ struct FfnWorkspace {
     int32_t* status;
     __half* h_r;
     __half* h_s;
-    float* ybuf;     // decode path, only when the output is bf16
+    float* part_r;   // decode path: partial outputs of the down kernel, summed in a fixed order by a last launch
+    float* part_s;
     MfmaScratch ms;  // MFMA path only
     size_t bytes;
 };
 
 fate_status launch_ffn_decode(hipStream_t st, const fate_ffn_desc& d, DecodeArgs a, void* y_out);
+// reduction chunks (of at most 16 groups) of the decode down kernel for an intermediate size of G groups
+inline int decode_down_chunks(int G) { return G > 0 ? (G + 15) / 16 : 1; }
 // Piece of a layer (matrix-core path): the routed experts of `mask` (bit e), the shared experts and
 // the preparation of x with the first piece, the per-token combination with the last one.
 struct PartSel {

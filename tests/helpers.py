@@ -98,10 +98,11 @@ class GpuLayer:
         return B.make_ffn_desc(N, c.H, c.E, c.k, c.I, c.bits, c.group, c.n_shared, c.I_shared or 0, c.shared_bits,
                                c.group, y_is_fp32, mode)
 
-    def ffn(self, x, counts, offsets, perm, inv_perm, order, topk_w, mode=0, y_is_fp32=True):
+    def ffn(self, x, counts, offsets, perm, inv_perm, order, topk_w, mode=0, y_is_fp32=True, ws_fill=0):
         N = x.shape[0]
         d = self.desc(N, mode, y_is_fp32)
-        ws = torch.zeros(B.fate_moe_ffn_q_workspace(d), dtype=torch.uint8, device=x.device)
+        ws = torch.full((B.fate_moe_ffn_q_workspace(d),), ws_fill, dtype=torch.uint8, device=x.device)
+        ws[:256] = 0                # the status word starts at zero
         y = torch.full((N, self.cfg.H), float("nan"), dtype=torch.float32 if y_is_fp32 else torch.bfloat16,
                        device=x.device)
         B.fate_moe_ffn_q(d, x, self.table, counts, offsets, perm, inv_perm, order, topk_w, self.shared_table,

@@ -98,6 +98,38 @@ def test_ffn_flags_missing_expert():
     L = GpuLayer(cfg, 0, experts=used[1:])        # one activated expert is not on the device
     y, ws = L.ffn(x, counts, offsets, perm, inv, order, w, mode=1)
     assert int(ws[:4].view(torch.int32)[0]) != 0
+    # the missing expert's pairs contribute nothing, everything else is as usual
+    ids_h = ids.cpu().numpy()
+    w_ref = w.cpu().numpy().astype(np.float64)
+    w_ref[ids_h == used[0]] = 0.0
+    experts = {e: oracle_expert(L.host[e]) for e in used[1:]}
+    experts[used[0]] = experts[used[1]]          # (weight 0: any expert will do)
+    y_ref = O.moe_ffn(f32(x), ids_h, w_ref, experts, [oracle_expert(ex) for ex in L.shared_host],
+                      None if L.shared_gate is None else f32(L.shared_gate))
+    assert ffn_rel_err(f32(y), y_ref).max() <= TOL
+
+
+@pytest.mark.parametrize("name,N", [("qwen", 5), ("deepseek", 13), ("mixtral", 3), ("tiny", 16)])
+def test_ffn_decode_is_reproducible_bit_for_bit(name, N):
+    """The decode kernels store partial outputs and add them in a fixed order: two runs on the same inputs (the
+    second one over a workspace filled with other values) give the same bits."""
+    cfg = SHAPES[name]
+    x = gen_hidden(cfg, N, device=DEV)
+    Wg, b = gen_gate(cfg, 0, device=DEV)
+    ids, w, _ = gpu_route(x, Wg, b, cfg.k, cfg.renorm, want_probs=False)
+    counts, offsets, perm, inv, order = gpu_permute(ids, cfg.E)
+    torch.cuda.synchronize()
+    used = sorted(set(ids.cpu().numpy().ravel().tolist()))
+    L = GpuLayer(cfg, 0, experts=used)
+    y1, ws = L.ffn(x, counts, offsets, perm, inv, order, w, mode=1)
+    y1 = y1.clone()
+    outs = []
+    for rep in range(3):
+        y2, ws2 = L.ffn(x, counts, offsets, perm, inv, order, w, mode=1, ws_fill=0x7f if rep else 0)
+        assert int(ws2[:4].view(torch.int32)[0]) == 0
+        outs.append(y2.clone())
+    for y2 in outs:
+        assert torch.equal(y1, y2)
 
 
 def _mfma_case(name, N, rows=None, layer=0, y_is_fp32=True):
