@@ -24,7 +24,28 @@ def _snapshot(buf, fields):
                                          ("deepseek", 8, False), ("deepseek", 1, False), ("mixtral", 1, False),
                                          ("mixtral", 4, False)])
 def test_one_launch_layer_equals_separate_calls_and_oracle(name, N, last):
-    cfg = SHAPES[name]
+    _one_launch_case(SHAPES[name], name, N, last)
+
+
+# the other kernel instantiations of the one-token form, and a layer without shared experts: the Qwen shape with
+# 8-bit routed experts, with an 8-bit shared expert, with both, and with no shared expert at all
+import dataclasses
+_QWEN = SHAPES["qwen"]
+VARIANTS = {
+    "qwen-routed8": dataclasses.replace(_QWEN, name="qwen-routed8", bits=8),
+    "qwen-shared8": dataclasses.replace(_QWEN, name="qwen-shared8", shared_bits=8),
+    "qwen-both8": dataclasses.replace(_QWEN, name="qwen-both8", bits=8, shared_bits=8),
+    "qwen-noshared": dataclasses.replace(_QWEN, name="qwen-noshared", n_shared=0, I_shared=0, shared_gate=False),
+}
+
+
+@pytest.mark.parametrize("name,N", [("qwen-routed8", 1), ("qwen-shared8", 1), ("qwen-both8", 1), ("qwen-noshared", 1),
+                                    ("qwen-noshared", 3)])
+def test_one_launch_layer_on_other_formats_and_without_shared_experts(name, N):
+    _one_launch_case(VARIANTS[name], name, N, False)
+
+
+def _one_launch_case(cfg, name, N, last):
     print(f"case {name} N={N} last={last}", flush=True)
     x = gen_hidden(cfg, N, device=DEV)
     lw = LayerWeights(cfg, 0, DEV)
