@@ -422,7 +422,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const fate_qexpert*
 }
 
 template <int NMAT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void grouped_gemm_kernel(GemmArgs a) {
+__device__ __forceinline__ void grouped_gemm_body(const GemmArgs& a) {
     constexpr int kBM = NMAT == 2 ? kBMUp : kBMDown;
     __shared__ __align__(16) __half xt[2 * kBM * kLdsRow];
     __shared__ int arow[kBM];
@@ -488,6 +488,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         gemm_tile<2, NMAT, kBM>(a, ex, group, row0, T, nblk, arow, xt, out, ldo, out_row0, Nout, K, A, lda);
     else
         gemm_tile<8, NMAT, kBM>(a, ex, group, row0, T, nblk, arow, xt, out, ldo, out_row0, Nout, K, A, lda);
+}
+
+// two waves per SIMD for the up GEMM (two matrices: 256 registers), three for the down GEMM
+template <int NMAT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void grouped_gemm_kernel(GemmArgs a) {
+    grouped_gemm_body<NMAT>(a);
+}
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void grouped_gemm_down_kernel(GemmArgs a) {
+    grouped_gemm_body<1>(a);
 }
 
 // y[t,:] = sum_j w[t,j] * Yp_r[inv_perm[t*k+j], :] + sum_s g_s(t) * Yp_s[s*N+t, :]
@@ -580,7 +589,7 @@ fate_status launch_ffn_mfma(hipStream_t st, const fate_ffn_desc& d, DecodeArgs d
         g.out_r = ms.yp_r; g.ldo_r = d.H; g.out_s = ms.yp_s; g.ldo_s = d.H;
         const long long grid = ((long long)mb_r_down + (long long)d.n_shared * mb_s_down) * nb_down;
         if (grid > 0x7fffffffLL) FATE_FAIL(FATE_ESHAPE, "too many tiles");
-        grouped_gemm_kernel<1><<<(unsigned)grid, 256, 0, st>>>(g);
+        grouped_gemm_down_kernel<<<(unsigned)grid, 256, 0, st>>>(g);
         FATE_HIP(hipGetLastError());
         if (sel.last)
             combine_kernel<<<d.N, 256, 0, st>>>(ms.yp_r, ms.yp_s, da.inv_perm, da.topk_w,
